@@ -1,0 +1,96 @@
+"""Pins of the oracle's acceptance arithmetic against closed forms and laws (no GPU)."""
+import itertools
+
+import numpy as np
+from scipy import stats
+
+from oracle import philox, spec_round as sr
+
+
+def test_log_ratio_equals_gaussian_log_density_difference():
+    # log alpha = log N(x; mu_q, s^2 I) - log N(x; mu_p, s^2 I) at x = mu_p + s xi  (Section 3.1 ratio
+    # vs Section 3.2 closed form): the densities come from scipy, not from the oracle's formula.
+    rng = np.random.default_rng(1)
+    for D in (2, 32, 160):
+        mu_p = rng.standard_normal((6, D)); mu_q = mu_p + 0.3 * rng.standard_normal((6, D))
+        sig = rng.uniform(0.05, 2.0, 6); xi = rng.standard_normal((6, D))
+        l, dd, dx = sr.log_ratio(mu_p, mu_q, sig, xi)
+        for r in range(6):
+            x = mu_p[r] + sig[r] * xi[r]
+            ref = stats.norm.logpdf(x, mu_q[r], sig[r]).sum() - stats.norm.logpdf(x, mu_p[r], sig[r]).sum()
+            assert abs(l[r] - ref) < 1e-9 * max(1.0, abs(ref))
+            assert dd[r] >= 0
+
+
+def test_acceptance_probability_is_one_minus_total_variation():
+    # E[accept] = 1 - TV(N(mu_p), N(mu_q)) = 2 Phi(-|d|/2) for equal isotropic covariances.
+    n, D = 120_000, 8
+    env = np.arange(n) % 4096; t = 1 + np.arange(n) // 4096
+    xi = philox.normal(11, env, t, D)
+    logu = np.log(philox.uniform(11, env, t))
+    rng = np.random.default_rng(2)
+    for delta in (0.0, 0.1, 0.5, 1.0, 2.0, 4.0):
+        dirn = rng.standard_normal(D); dirn /= np.linalg.norm(dirn)
+        sig = 0.7
+        mu_q = np.zeros((n, D)); mu_p = mu_q + delta * sig * dirn
+        l, _, _ = sr.log_ratio(mu_p, mu_q, np.full(n, sig), xi)
+        rate = np.mean(logu <= l)
+        p = 2 * stats.norm.cdf(-delta / 2)
+        assert abs(rate - p) <= 4 * np.sqrt(max(p * (1 - p), 1e-12) / n) + 1e-12, (delta, rate, p)
+
+
+def test_first_rejection_brute_force():
+    for K in range(0, 9):
+        for pat in itertools.product([0, 1], repeat=K):
+            j = sr.first_rejection(pat)
+            rej = [i + 1 for i, a in enumerate(pat) if a == 0]
+            assert j == (min(rej) if rej else K + 1)
+            assert all(pat[i] == 1 for i in range(j - 1))            # the committed prefix is all accepted
+
+
+def test_reflection_is_an_isometry_that_flips_only_the_mean_difference_axis():
+    rng = np.random.default_rng(3)
+    for D in (2, 7, 160):
+        mu_p = rng.standard_normal(D); mu_q = rng.standard_normal(D); xi = rng.standard_normal(D); sig = 0.37
+        x = sr.reflect(mu_p, mu_q, sig, xi)
+        e = (mu_p - mu_q) / np.linalg.norm(mu_p - mu_q)
+        a, b = x - mu_q, sig * xi                                     # corrected and drafted offsets
+        assert abs(np.linalg.norm(a) - np.linalg.norm(b)) < 1e-12
+        assert abs(a @ e + b @ e) < 1e-12                             # component along e changes sign
+        np.testing.assert_allclose(a - (a @ e) * e, b - (b @ e) * e, atol=1e-12)   # the rest is kept
+        np.testing.assert_allclose(sr.reflect(mu_p, mu_q, sig, (x - mu_q) / sig),  # an involution
+                                   mu_q + sig * xi, atol=1e-12)
+
+
+def _one_step_outputs(n, mu_p, mu_q, sig, seed):
+    D = len(mu_p)
+    env = np.arange(n) % 8192; t = 1 + np.arange(n) // 8192
+    xi = philox.normal(seed, env, t, D)
+    logu = np.log(philox.uniform(seed, env, t))
+    MP = np.broadcast_to(mu_p, (n, D)); MQ = np.broadcast_to(mu_q, (n, D))
+    l, _, _ = sr.log_ratio(MP, MQ, np.full(n, sig), xi)
+    acc = logu <= l
+    out = MP + sig * xi
+    for i in np.nonzero(~acc)[0]:
+        out[i] = sr.reflect(mu_p, mu_q, sig, xi[i])
+    return out, acc
+
+
+def test_accept_or_reflect_output_follows_the_target_law():
+    # Marginal of (accepted draft) U (reflected draft) is exactly N(mu_q, sig^2 I)  (Section 3.1).
+    n = 100_000
+    mu_p = np.array([0.4, -0.2]); mu_q = np.array([-0.1, 0.3]); sig = 0.5
+    out, acc = _one_step_outputs(n, mu_p, mu_q, sig, seed=21)
+    assert 0.2 < acc.mean() < 0.8                                     # both branches are exercised
+    z = (out - mu_q) / sig
+    for a in range(2):
+        assert stats.kstest(z[:, a], "norm").pvalue > 1e-3
+        assert abs(z[:, a].mean()) < 4 / np.sqrt(n)
+        assert abs(z[:, a].var() - 1) < 4 * np.sqrt(2 / n)
+    assert abs(np.corrcoef(z.T)[0, 1]) < 4 / np.sqrt(n)
+    # along the mean-difference axis too (the axis the reflection acts on)
+    e = (mu_p - mu_q) / np.linalg.norm(mu_p - mu_q)
+    assert stats.kstest(z @ e, "norm").pvalue > 1e-3
+    # the drafted samples themselves follow the draft law, not the target: the test can tell
+    zp = (out[acc] - mu_q) / sig
+    assert stats.kstest(zp @ e, "norm").pvalue < 1e-6
