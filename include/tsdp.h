@@ -1,0 +1,134 @@
+/*
+ * tsdp.h - C ABI of the MI355X speculative draft-then-verify denoising round of TS-DP.
+ *
+ * One call of tsdp_round() performs, for a batch of B independent environments, one round of the
+ * paper's Section 3.2: the drafter rolls out up to K DDPM reverse steps (Draft Generation Procedure,
+ * Eq. (3)), the base denoiser scores all drafted input states in one ragged batch (Verification of
+ * Speculative Drafts), and every drafted transition passes the Gaussian likelihood-ratio test of
+ * Section 3.1 (Eq. (2), first-rejection index Eq. (3) of the preliminaries) with the first rejected
+ * draft corrected by reflection-maximal coupling (Section 3.1, reflection equations).  tsdp_draft,
+ * tsdp_verify and tsdp_accept expose the three stages on caller-owned buffers.
+ *
+ * Conventions
+ *  - Every function returns 0 on success or a negative TSDP_E_* code; nothing throws or aborts.
+ *    tsdp_last_error() returns a message for the last failing call on that context.
+ *  - Pointers named d_* are DEVICE pointers owned by the caller; h_* are HOST pointers.  The library
+ *    neither frees nor keeps caller pointers beyond the work it enqueues (exception: tsdp_set_cond
+ *    caches derived tensors in context-owned memory, not the pointer).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work is enqueued on it and
+ *    no call synchronises, except tsdp_create / tsdp_load_weights / tsdp_destroy / tsdp_status.
+ *  - Latents, noise predictions, noises and means are fp32 in every configuration; only the network
+ *    internals follow tsdp_config.dtype.  All tensors are dense row-major.
+ *  - Timesteps run t = T-1 .. 0; a latent "at t" is x_t; t = -1 marks a finished environment.
+ *  - Ragged row table: environment b owns rows row_ptr[b] .. row_ptr[b+1]-1; row row_ptr[b]+k-1 holds the
+ *    input state y_{k-1} of drafted transition k at timestep t0[b]-k+1.  K_eff = min(K, t0).  An
+ *    environment at t0 = 0 owns one row (the deterministic last base step); a finished one owns none.
+ *  - H*A must be a multiple of 4.  The context owns weights, tables and workspace; calls on one
+ *    context must not overlap in time (they share the workspace).
+ */
+#ifndef TSDP_H
+#define TSDP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TSDP_OK        0
+#define TSDP_E_INVAL  -1   /* null pointer, bad enum, value out of range */
+#define TSDP_E_SHAPE  -2   /* shape not supported or exceeding B_max / K_max / blob size mismatch */
+#define TSDP_E_NOMEM  -3   /* device or host allocation failed */
+#define TSDP_E_HIP    -4   /* a HIP runtime call failed */
+#define TSDP_E_STATE  -5   /* weights not loaded / conditioning not set */
+
+typedef struct tsdp_ctx tsdp_ctx;
+
+typedef struct {
+  int32_t dtype;          /* 0 = fp32 network, 1 = bf16 weights + bf16 matrix-multiply inputs, fp32 accumulate */
+  int32_t H, A;           /* horizon (tokens per latent), action dimension */
+  int32_t cond_mode;      /* 0 = conditioning vector through FiLM, 1 = observation tokens through cross-attention */
+  int32_t cond_dim;       /* vector length (mode 0) or feature size of one token (mode 1) */
+  int32_t cond_tokens;    /* number of observation tokens (mode 1), 0 otherwise */
+  int32_t base_layers, base_d, base_heads, base_mlp_ratio;
+  int32_t draft_layers, draft_d, draft_heads, draft_mlp_ratio;
+  int32_t T;              /* DDPM steps */
+  int32_t schedule;       /* 0 = linear beta0..beta1, 1 = squared cosine (offset 0.008, beta cap 0.999) */
+  float   beta0, beta1;
+  int32_t clip_x0;        /* 1 = clamp the predicted clean sample to [-clip_val, clip_val] */
+  float   clip_val;
+  int32_t B_max, K_max;   /* largest batch and largest per-environment draft count */
+  uint64_t seed;          /* Philox4x32-10 key */
+} tsdp_config;
+
+/* Builds the DDPM tables (fp64 on the host, stored fp32) and an empty context.  Synchronous. */
+int tsdp_create(const tsdp_config* cfg, tsdp_ctx** out_ctx);
+
+/* Frees everything the context owns.  Synchronises the device.  NULL is allowed. */
+void tsdp_destroy(tsdp_ctx* ctx);
+
+/* Loads one denoiser (which: 0 = base, 1 = drafter) from a HOST blob of fp32 values: the tensors
+ * tok_w[d,A] tok_b[d] pos[H,d] t_w1[d,d] t_b1[d] t_w2[d,d] t_b2[d] (mode 0: c_w[d,C] c_b[d]) then per
+ * layer mod_w[4d,d] mod_b[4d] qkv_w[3d,d] qkv_b[3d] o_w[d,d] o_b[d] (mode 1: cq_w[d,d] cq_b[d]
+ * ck_w[d,Cdim] ck_b[d] cv_w[d,Cdim] cv_b[d] co_w[d,d] co_b[d]) up_w[m,d] up_b[m] dn_w[d,m] dn_b[d]
+ * and finally head_w[A,d] head_b[A]; Linear weights are [out,in] row-major, m = mlp_ratio*d.
+ * nbytes must equal the blob size exactly.  In bf16 mode all values are rounded to bfloat16 (nearest
+ * even).  The blob is copied and re-laid-out; the caller may free it on return.  Synchronous. */
+int tsdp_load_weights(tsdp_ctx* ctx, int which, const float* h_blob, size_t nbytes);
+
+/* Conditioning of the B environments of the following calls: d_cond is [B,cond_dim] (mode 0) or
+ * [B,cond_tokens,cond_dim] (mode 1), fp32.  Caches what depends on it only (conditioning embedding, or
+ * the cross-attention keys / values of every layer) for both networks.  Needs both weight sets. */
+int tsdp_set_cond(tsdp_ctx* ctx, const float* d_cond, int B, void* stream);
+
+/* Drafter rollout (Section 3.2, Draft Generation Procedure).
+ * in : d_x[B,H,A], d_t0[B], d_K[B] (clamped to 0..K_max), d_sigma_scale[B],
+ *      d_env_id[B] global environment index used as Philox counter word (NULL = 0..B-1)
+ * out: d_row_ptr[B+1], d_row_t[R_cap], d_row_env[R_cap], d_states[R_cap,H,A], d_eps_p[R_cap,H,A],
+ *      d_xi[R_cap,H,A], d_y_last[B,H,A] (the latent after the last drafted step; x itself if no step
+ *      was drafted).  R_cap = B*K_max rows must be allocated; rows beyond row_ptr[B] are not written. */
+int tsdp_draft(tsdp_ctx* ctx, int B, const float* d_x, const int32_t* d_t0, const int32_t* d_K,
+               const float* d_sigma_scale, const int32_t* d_env_id,
+               int32_t* d_row_ptr, int32_t* d_row_t, int32_t* d_row_env,
+               float* d_states, float* d_eps_p, float* d_xi, float* d_y_last, void* stream);
+
+/* Batched verification (Section 3.2, Verification of Speculative Drafts): base-network noise
+ * prediction for every row of a ragged batch.  R_cap bounds the launch (<= B_max*K_max); the live row
+ * count is read on the device from d_row_ptr[B].  Row r uses timestep d_row_t[r] and the conditioning
+ * of environment d_row_env[r] (index into the batch given to tsdp_set_cond).
+ * out: d_eps_q[R_cap,H,A]. */
+int tsdp_verify(tsdp_ctx* ctx, int B, int R_cap, const int32_t* d_row_ptr, const int32_t* d_row_t,
+                const int32_t* d_row_env, const float* d_states, float* d_eps_q, void* stream);
+
+/* Acceptance (Section 3.1 Eqs. (2),(3) and reflection coupling; Section 3.2 log acceptance ratio):
+ * per row d = (mu_p - mu_q)/(s sigma_t), log alpha = -|d|^2/2 - <d,xi>; accepted iff
+ * log U_{env,t} <= log alpha; first rejection j*; the output latent is y_{K_eff} if all drafts pass,
+ * else the reflection of draft j*; t_next = t0 - (steps advanced).  Arithmetic is fp64 on fp32 data.
+ * out: d_x_out[B,H,A], d_t_next[B], d_n_accept[B]; optional (NULL to skip): d_n_adv[B],
+ *      d_flags[R] (1 = accepted draft), d_logratio[R], d_logu[R] (0 on the lone row of a t0 = 0 env). */
+int tsdp_accept(tsdp_ctx* ctx, int B, const int32_t* d_row_ptr, const int32_t* d_row_t,
+                const int32_t* d_env_id, const float* d_sigma_scale, const float* d_states,
+                const float* d_eps_p, const float* d_eps_q, const float* d_xi, const float* d_y_last,
+                float* d_x_out, int32_t* d_t_next, int32_t* d_n_accept, int32_t* d_n_adv,
+                uint8_t* d_flags, float* d_logratio, float* d_logu, void* stream);
+
+/* One whole round on context-owned ragged buffers: d_x[B,H,A] and d_t[B] are updated in place;
+ * d_n_accept[B] = accepted drafts, d_n_advanced[B] = denoising steps advanced (both may be NULL). */
+int tsdp_round(tsdp_ctx* ctx, int B, float* d_x, int32_t* d_t, const int32_t* d_K,
+               const float* d_sigma_scale, const int32_t* d_env_id,
+               int32_t* d_n_accept, int32_t* d_n_advanced, void* stream);
+
+/* Synchronises `stream` and returns the device status word accumulated since the last call:
+ * bit 0 = some K was outside 0..K_max (clamped), bit 1 = some t0 was >= T (treated as T-1). */
+int tsdp_status(tsdp_ctx* ctx, void* stream, int32_t* h_status);
+
+/* Name of the kernel path used for a network ("f32-ops", "bf16-mfma-fused", ...). which: 0 base, 1 drafter. */
+const char* tsdp_path_name(const tsdp_ctx* ctx, int which);
+
+const char* tsdp_last_error(const tsdp_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TSDP_H */

@@ -1,0 +1,249 @@
+// Row-table planning, the drafter's DDPM step and the acceptance kernel of the speculative round.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "philox.hpp"
+
+namespace tsdp {
+
+struct SchedTables {          // device pointers, fp32[T] each
+  const float* sqrt_abar; const float* sqrt_1m; const float* c0; const float* cx; const float* sigma;
+  int T;
+};
+
+// K_eff = min(clamp(K), t0), rows per env = live ? max(K_eff,1) : 0, exclusive scan into row_ptr[B+1].
+// Single workgroup of 1024 threads, chunks of 1024 environments.
+__global__ __launch_bounds__(1024) void k_plan(const int32_t* __restrict__ t0, const int32_t* __restrict__ K,
+                                               int B, int K_max, int T, int32_t* __restrict__ K_eff,
+                                               int32_t* __restrict__ row_ptr, int32_t* __restrict__ status) {
+  __shared__ int32_t part[1024];
+  __shared__ int32_t carry;
+  if (threadIdx.x == 0) carry = 0;
+  __syncthreads();
+  for (int base = 0; base < B; base += 1024) {
+    const int b = base + threadIdx.x;
+    int n = 0;
+    if (b < B) {
+      int k = K[b], t = t0[b];
+      if (k < 0 || k > K_max) { atomicOr(status, 1); k = k < 0 ? 0 : K_max; }
+      if (t >= T) { atomicOr(status, 2); t = T - 1; }
+      const int ke = t < 0 ? 0 : (k < t ? k : t);
+      K_eff[b] = ke;
+      n = t < 0 ? 0 : (ke > 1 ? ke : 1);
+    }
+    part[threadIdx.x] = n;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {            // inclusive Hillis-Steele scan
+      const int v = threadIdx.x >= o ? part[threadIdx.x - o] : 0;
+      __syncthreads();
+      part[threadIdx.x] += v;
+      __syncthreads();
+    }
+    if (b < B) row_ptr[b] = carry + part[threadIdx.x] - n;
+    __syncthreads();
+    if (threadIdx.x == 1023) carry += part[1023];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) row_ptr[B] = carry;
+}
+
+// Fills row_t / row_env, copies x into y (the rollout state), and for t0 = 0 environments writes the
+// lone base-step row (state = x, eps_p = xi = 0).  One workgroup per environment.
+__global__ void k_rows(const float* __restrict__ x, const int32_t* __restrict__ t0, const int32_t* __restrict__ row_ptr,
+                       int T, int D, int32_t* __restrict__ row_t, int32_t* __restrict__ row_env,
+                       float* __restrict__ y, float* __restrict__ states, float* __restrict__ eps_p,
+                       float* __restrict__ xi) {
+  const int b = blockIdx.x;
+  const int r0 = row_ptr[b], n = row_ptr[b + 1] - r0;
+  int t = t0[b];
+  if (t >= T) t = T - 1;
+  for (int j = threadIdx.x; j < n; j += blockDim.x) { row_t[r0 + j] = t - j; row_env[r0 + j] = b; }
+  for (int e = threadIdx.x; e < D; e += blockDim.x) {
+    const float v = x[(long long)b * D + e];
+    y[(long long)b * D + e] = v;
+    if (t == 0) {
+      states[(long long)r0 * D + e] = v;
+      eps_p[(long long)r0 * D + e] = 0.0f;
+      xi[(long long)r0 * D + e] = 0.0f;
+    }
+  }
+}
+
+// Drafted transition k for every environment with K_eff >= k:
+//   states[row] = y;  eps_p[row] = eps;  xi[row] = xi_{env,t};  y <- mu_p(y, eps, t) + s sigma_t xi.
+// One thread per 4 elements (one Philox block).
+__global__ void k_draft_step(int k, const float* __restrict__ eps, const int32_t* __restrict__ t0,
+                             const int32_t* __restrict__ K_eff, const int32_t* __restrict__ row_ptr,
+                             const float* __restrict__ sigma_scale, const int32_t* __restrict__ env_id,
+                             SchedTables tb, int clip, float clip_val, uint64_t seed, int B, int D,
+                             float* __restrict__ y, float* __restrict__ states, float* __restrict__ eps_p,
+                             float* __restrict__ xi) {
+  const int nb = D >> 2;
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (long long)B * nb) return;
+  const int b = (int)(i / nb), blk = (int)(i % nb);
+  if (K_eff[b] < k) return;
+  int t = t0[b];
+  if (t >= tb.T) t = tb.T - 1;
+  t = t - k + 1;
+  const long long row = row_ptr[b] + k - 1;
+  const float4 yv = *reinterpret_cast<const float4*>(y + (long long)b * D + 4 * blk);
+  const float4 ev = *reinterpret_cast<const float4*>(eps + (long long)b * D + 4 * blk);
+  const float4 z = xi_block(seed, env_id ? env_id[b] : b, t, blk);
+  const float sa = tb.sqrt_abar[t], s1 = tb.sqrt_1m[t], c0 = tb.c0[t], cx = tb.cx[t];
+  const float sig = sigma_scale[b] * tb.sigma[t];
+  const float yy[4] = {yv.x, yv.y, yv.z, yv.w}, ee[4] = {ev.x, ev.y, ev.z, ev.w}, zz[4] = {z.x, z.y, z.z, z.w};
+  float o[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float x0 = (yy[j] - s1 * ee[j]) / sa;
+    if (clip) x0 = fminf(fmaxf(x0, -clip_val), clip_val);
+    o[j] = c0 * x0 + cx * yy[j] + sig * zz[j];
+  }
+  *reinterpret_cast<float4*>(states + row * D + 4 * blk) = yv;
+  *reinterpret_cast<float4*>(eps_p + row * D + 4 * blk) = ev;
+  *reinterpret_cast<float4*>(xi + row * D + 4 * blk) = z;
+  *reinterpret_cast<float4*>(y + (long long)b * D + 4 * blk) = make_float4(o[0], o[1], o[2], o[3]);
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// Acceptance: one wavefront per environment.  For each of its rows the wave streams eps_p, eps_q, xi
+// (and the state when x0 is clamped), reduces |d|^2 and <d,xi> in fp64, tests log U <= log alpha, keeps
+// the first rejection, then writes the committed or reflected latent.
+template <bool CLIP>
+__global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __restrict__ row_ptr,
+                                                const int32_t* __restrict__ row_t, const int32_t* __restrict__ env_id,
+                                                const float* __restrict__ sigma_scale, const float* __restrict__ states,
+                                                const float* __restrict__ eps_p, const float* __restrict__ eps_q,
+                                                const float* __restrict__ xi, const float* __restrict__ y_last,
+                                                SchedTables tb, float clip_val, uint64_t seed,
+                                                float* __restrict__ x_out, int32_t* __restrict__ t_next,
+                                                int32_t* __restrict__ n_accept, int32_t* __restrict__ n_adv,
+                                                uint8_t* __restrict__ flags, float* __restrict__ logratio,
+                                                float* __restrict__ logu_out) {
+  const int lane = threadIdx.x & 63;
+  const int b = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (b >= B) return;
+  const int r0 = row_ptr[b], r1 = row_ptr[b + 1];
+  const int nb = D >> 2;
+  float4* xo = reinterpret_cast<float4*>(x_out + (long long)b * D);
+  if (r1 == r0) {                                   // finished environment: latent passes through
+    const float4* yl = reinterpret_cast<const float4*>(y_last + (long long)b * D);
+    for (int i = lane; i < nb; i += 64) xo[i] = yl[i];
+    if (lane == 0) { t_next[b] = -1; n_accept[b] = 0; if (n_adv) n_adv[b] = 0; }
+    return;
+  }
+  const int t0 = row_t[r0];
+  const double cv = (double)clip_val;
+  if (t0 == 0) {                                    // deterministic last step of the base model
+    const double sa = tb.sqrt_abar[0], s1 = tb.sqrt_1m[0], c0 = tb.c0[0], cx = tb.cx[0];
+    const float4* st = reinterpret_cast<const float4*>(states + (long long)r0 * D);
+    const float4* eq = reinterpret_cast<const float4*>(eps_q + (long long)r0 * D);
+    for (int i = lane; i < nb; i += 64) {
+      const float4 y = st[i], e = eq[i];
+      const float yy[4] = {y.x, y.y, y.z, y.w}, ee[4] = {e.x, e.y, e.z, e.w};
+      float o[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        double x0 = ((double)yy[j] - s1 * (double)ee[j]) / sa;
+        if (CLIP) x0 = fmin(fmax(x0, -cv), cv);
+        o[j] = (float)(c0 * x0 + cx * (double)yy[j]);
+      }
+      xo[i] = make_float4(o[0], o[1], o[2], o[3]);
+    }
+    if (lane == 0) {
+      t_next[b] = -1; n_accept[b] = 0; if (n_adv) n_adv[b] = 1;
+      if (flags) flags[r0] = 0;
+      if (logratio) logratio[r0] = 0.0f;
+      if (logu_out) logu_out[r0] = 0.0f;
+    }
+    return;
+  }
+  const double s = (double)sigma_scale[b];
+  const int env = env_id ? env_id[b] : b;
+  int jstar = 0;                                    // 0 = no rejection yet; else 1-based row index
+  double rej_dd = 0.0, rej_dx = 0.0;
+  for (int r = r0; r < r1; ++r) {
+    const int t = row_t[r];
+    const double sa = tb.sqrt_abar[t], s1 = tb.sqrt_1m[t], c0 = tb.c0[t], sig = s * (double)tb.sigma[t];
+    const float4* ep = reinterpret_cast<const float4*>(eps_p + (long long)r * D);
+    const float4* eq = reinterpret_cast<const float4*>(eps_q + (long long)r * D);
+    const float4* zz = reinterpret_cast<const float4*>(xi + (long long)r * D);
+    const float4* st = reinterpret_cast<const float4*>(states + (long long)r * D);
+    double dd = 0.0, dx = 0.0;                      // sums of delta^2 and delta*xi, delta = x0_p - x0_q
+    for (int i = lane; i < nb; i += 64) {
+      const float4 p = ep[i], q = eq[i], z = zz[i];
+      const float pp[4] = {p.x, p.y, p.z, p.w}, qq[4] = {q.x, q.y, q.z, q.w}, zv[4] = {z.x, z.y, z.z, z.w};
+      if (CLIP) {
+        const float4 y = st[i];
+        const float yy[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const double xp = fmin(fmax(((double)yy[j] - s1 * (double)pp[j]) / sa, -cv), cv);
+          const double xq = fmin(fmax(((double)yy[j] - s1 * (double)qq[j]) / sa, -cv), cv);
+          const double de = xp - xq;
+          dd = fma(de, de, dd); dx = fma(de, (double)zv[j], dx);
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {               // x0_p - x0_q = -(s1/sa)(eps_p - eps_q)
+          const double de = (double)pp[j] - (double)qq[j];
+          dd = fma(de, de, dd); dx = fma(de, (double)zv[j], dx);
+        }
+      }
+    }
+    dd = wave_sum(dd); dx = wave_sum(dx);
+    const double kap = CLIP ? c0 / sig : -(c0 * s1) / (sa * sig);   // d = kap * delta
+    const double n2 = kap * kap * dd, ip = kap * dx;                // |d|^2, <d,xi>
+    const double l = -0.5 * n2 - ip;
+    const double lu = log((double)accept_uniform(seed, env, t));
+    const bool acc = lu <= l;
+    if (!acc && jstar == 0) { jstar = r - r0 + 1; rej_dd = n2; rej_dx = ip; }
+    if (lane == 0) {
+      if (flags) flags[r] = acc ? 1 : 0;
+      if (logratio) logratio[r] = (float)l;
+      if (logu_out) logu_out[r] = (float)lu;
+    }
+  }
+  const int K_eff = r1 - r0;
+  if (jstar == 0) {                                 // every draft accepted: commit y_{K_eff}
+    const float4* yl = reinterpret_cast<const float4*>(y_last + (long long)b * D);
+    for (int i = lane; i < nb; i += 64) xo[i] = yl[i];
+    if (lane == 0) { t_next[b] = t0 - K_eff; n_accept[b] = K_eff; if (n_adv) n_adv[b] = K_eff; }
+    return;
+  }
+  {                                                 // reflect the first rejected draft about the target mean
+    const int r = r0 + jstar - 1;
+    const int t = row_t[r];
+    const double sa = tb.sqrt_abar[t], s1 = tb.sqrt_1m[t], c0 = tb.c0[t], cx = tb.cx[t], sig = s * (double)tb.sigma[t];
+    const double coef = rej_dd > 0.0 ? 2.0 * rej_dx / rej_dd : 0.0;   // 2 <d,xi>/|d|^2
+    const float4* ep = reinterpret_cast<const float4*>(eps_p + (long long)r * D);
+    const float4* eq = reinterpret_cast<const float4*>(eps_q + (long long)r * D);
+    const float4* zz = reinterpret_cast<const float4*>(xi + (long long)r * D);
+    const float4* st = reinterpret_cast<const float4*>(states + (long long)r * D);
+    for (int i = lane; i < nb; i += 64) {
+      const float4 p = ep[i], q = eq[i], z = zz[i], y = st[i];
+      const float pp[4] = {p.x, p.y, p.z, p.w}, qq[4] = {q.x, q.y, q.z, q.w}, zv[4] = {z.x, z.y, z.z, z.w},
+                  yy[4] = {y.x, y.y, y.z, y.w};
+      float o[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        double xp = ((double)yy[j] - s1 * (double)pp[j]) / sa;
+        double xq = ((double)yy[j] - s1 * (double)qq[j]) / sa;
+        if (CLIP) { xp = fmin(fmax(xp, -cv), cv); xq = fmin(fmax(xq, -cv), cv); }
+        const double muq = c0 * xq + cx * (double)yy[j];
+        const double dmu = c0 * (xp - xq);                          // mu_p - mu_q
+        o[j] = (float)(muq + sig * (double)zv[j] - coef * dmu);
+      }
+      xo[i] = make_float4(o[0], o[1], o[2], o[3]);
+    }
+    if (lane == 0) { t_next[b] = t0 - jstar; n_accept[b] = jstar - 1; if (n_adv) n_adv[b] = jstar; }
+  }
+}
+
+}  // namespace tsdp

@@ -1,0 +1,490 @@
+// C ABI of the speculative denoising round: context, weights, tables, workspace and launch sequences.
+// Definitions of the operations: Section 3.1 (acceptance test, first rejection, reflection coupling)
+// and Section 3.2 (drafter rollout, batched verification, log acceptance ratio) of the TS-DP paper.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/tsdp.h"
+#include "kernels_f32.hpp"
+#include "round_kernels.hpp"
+
+using namespace tsdp;
+
+namespace {
+
+struct LayerOff {
+  size_t mod_w, mod_b, qkv_w, qkv_b, o_w, o_b, cq_w, cq_b, ck_w, ck_b, cv_w, cv_b, co_w, co_b, up_w, up_b, dn_w, dn_b;
+};
+
+struct Net {
+  int L = 0, d = 0, heads = 0, m = 0;
+  size_t n_floats = 0;
+  size_t tok_w, tok_b, pos, t_w1, t_b1, t_w2, t_b2, c_w, c_b, head_w, head_b;
+  std::vector<LayerOff> lay;
+  float* blob = nullptr;        // device copy of the (rounded) canonical blob
+  float* temb = nullptr;        // [T, d] timestep embedding of every timestep
+  float* modw = nullptr;        // [L*4d, d] FiLM projections of all layers, concatenated
+  float* modb = nullptr;        // [L*4d]
+  float* cemb = nullptr;        // [B_max, d] conditioning embedding (mode 0)
+  float* kc = nullptr;          // [L, B_max*S, d] cross-attention keys (mode 1)
+  float* vc = nullptr;          // [L, B_max*S, d] cross-attention values (mode 1)
+  bool loaded = false;
+  const char* path = "f32-ops";
+};
+
+}  // namespace
+
+struct tsdp_ctx {
+  tsdp_config cfg;
+  int D = 0;
+  std::string err;
+  float* tables = nullptr;      // 5 x T fp32: sqrt_abar, sqrt_1m, c0, cx, sigma
+  SchedTables tb;
+  Net net[2];
+  bool cond_set = false;
+  int cond_B = 0;
+  int32_t* status = nullptr;
+  int32_t* K_eff = nullptr;     // [B_max]
+  // network workspace (lazy)
+  bool ws_ready = false;
+  float *h = nullptr, *a = nullptr, *qkv = nullptr, *ao = nullptr, *u = nullptr, *sg = nullptr, *mod = nullptr;
+  float* eps_tmp = nullptr;     // [B_max, D] drafter output of the current step
+  int32_t* Bconst = nullptr;    // device ints holding B for row-count reads of dense (per-env) launches
+  // round-owned ragged buffers (lazy)
+  bool rb_ready = false;
+  int32_t *row_ptr = nullptr, *row_t = nullptr, *row_env = nullptr, *t_next = nullptr, *n_acc = nullptr, *n_adv = nullptr;
+  float *states = nullptr, *eps_p = nullptr, *eps_q = nullptr, *xi = nullptr, *y_last = nullptr;
+  std::vector<void*> owned;
+};
+
+namespace {
+
+int fail(tsdp_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg;
+  return code;
+}
+
+#define HIPCHK(c, expr)                                                                         \
+  do {                                                                                          \
+    hipError_t e_ = (expr);                                                                     \
+    if (e_ != hipSuccess)                                                                       \
+      return fail(c, e_ == hipErrorOutOfMemory ? TSDP_E_NOMEM : TSDP_E_HIP,                     \
+                  std::string(#expr) + ": " + hipGetErrorString(e_));                           \
+  } while (0)
+
+template <typename T>
+int dev_alloc(tsdp_ctx* c, T** p, size_t count) {
+  void* v = nullptr;
+  HIPCHK(c, hipMalloc(&v, (count ? count : 1) * sizeof(T)));
+  c->owned.push_back(v);
+  *p = static_cast<T*>(v);
+  return TSDP_OK;
+}
+
+float bf16_round(float f) {
+  uint32_t b;
+  std::memcpy(&b, &f, 4);
+  if ((b & 0x7F800000u) == 0x7F800000u) return f;     // inf / nan unchanged
+  b = (b + 0x7FFFu + ((b >> 16) & 1u)) & 0xFFFF0000u;
+  std::memcpy(&f, &b, 4);
+  return f;
+}
+
+size_t layout_net(const tsdp_config& cf, int which, Net& n) {
+  n.L = which == 0 ? cf.base_layers : cf.draft_layers;
+  n.d = which == 0 ? cf.base_d : cf.draft_d;
+  n.heads = which == 0 ? cf.base_heads : cf.draft_heads;
+  n.m = (which == 0 ? cf.base_mlp_ratio : cf.draft_mlp_ratio) * n.d;
+  const size_t d = n.d, m = n.m, A = cf.A, H = cf.H, C = cf.cond_dim;
+  size_t o = 0;
+  auto take = [&](size_t cnt) { size_t r = o; o += cnt; return r; };
+  n.tok_w = take(d * A); n.tok_b = take(d); n.pos = take(H * d);
+  n.t_w1 = take(d * d); n.t_b1 = take(d); n.t_w2 = take(d * d); n.t_b2 = take(d);
+  n.c_w = n.c_b = 0;
+  if (cf.cond_mode == 0) { n.c_w = take(d * C); n.c_b = take(d); }
+  n.lay.resize(n.L);
+  for (auto& l : n.lay) {
+    l.mod_w = take(4 * d * d); l.mod_b = take(4 * d);
+    l.qkv_w = take(3 * d * d); l.qkv_b = take(3 * d);
+    l.o_w = take(d * d); l.o_b = take(d);
+    if (cf.cond_mode == 1) {
+      l.cq_w = take(d * d); l.cq_b = take(d);
+      l.ck_w = take(d * C); l.ck_b = take(d);
+      l.cv_w = take(d * C); l.cv_b = take(d);
+      l.co_w = take(d * d); l.co_b = take(d);
+    }
+    l.up_w = take(m * d); l.up_b = take(m);
+    l.dn_w = take(d * m); l.dn_b = take(d);
+  }
+  n.head_w = take(A * d); n.head_b = take(A);
+  n.n_floats = o;
+  return o;
+}
+
+inline dim3 grid1(long long n, int bs) { return dim3((unsigned)((n + bs - 1) / bs)); }
+
+template <int EPI>
+void linear(hipStream_t s, const float* in, const float* W, const float* bias, float* out, int units_cap,
+            int rows_per_unit, int N, int K, const int32_t* d_R) {
+  const long long M = (long long)units_cap * rows_per_unit;
+  dim3 g((N + 63) / 64, (unsigned)((M + 63) / 64));
+  hipLaunchKernelGGL(k_linear<EPI>, g, dim3(256), 0, s, in, W, bias, out, rows_per_unit, N, K, d_R, units_cap);
+}
+
+// eps[R,H,A] = network(x_rows; t, cond) with the fp32 operator kernels.
+void forward_f32(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t* d_R, const int32_t* t_arr,
+                 int t_sub, const int32_t* env_arr, float* eps_out, hipStream_t s) {
+  const tsdp_config& cf = c->cfg;
+  const int H = cf.H, A = cf.A, d = n.d, L = n.L, m = n.m, dh = n.d / n.heads;
+  const long long M = (long long)R_cap * H;
+  const float* w = n.blob;
+  hipLaunchKernelGGL(k_embed, grid1(M * d, 256), dim3(256), 0, s, x_rows, w + n.tok_w, w + n.tok_b, w + n.pos, c->h,
+                     H, A, d, d_R, R_cap);
+  hipLaunchKernelGGL(k_gvec, grid1((long long)R_cap * d, 256), dim3(256), 0, s, t_arr, t_sub, env_arr, n.temb,
+                     cf.cond_mode == 0 ? n.cemb : nullptr, c->sg, d, cf.T, d_R, R_cap);
+  const int ms = L * 4 * d;                         // modulation row stride
+  linear<0>(s, c->sg, n.modw, n.modb, c->mod, R_cap, 1, ms, d, d_R);
+  const dim3 lng((unsigned)((M + 3) / 4));
+  for (int l = 0; l < L; ++l) {
+    const LayerOff& o = n.lay[l];
+    const float* mod = c->mod + (size_t)l * 4 * d;
+    hipLaunchKernelGGL(k_lnmod, lng, dim3(256), 0, s, c->h, mod, mod + d, ms, c->a, H, d, d_R, R_cap);
+    linear<0>(s, c->a, w + o.qkv_w, w + o.qkv_b, c->qkv, R_cap, H, 3 * d, d, d_R);
+    hipLaunchKernelGGL(k_attn, dim3(R_cap, n.heads), dim3(256), H * H * sizeof(float), s, c->qkv, 3 * d, c->qkv + d,
+                       c->qkv + 2 * d, 3 * d, (const int32_t*)nullptr, c->ao, d, H, H, dh, d_R, R_cap);
+    linear<2>(s, c->ao, w + o.o_w, w + o.o_b, c->h, R_cap, H, d, d, d_R);
+    if (cf.cond_mode == 1) {
+      const int S = cf.cond_tokens;
+      const size_t per_layer = (size_t)cf.B_max * S * d;
+      hipLaunchKernelGGL(k_lnmod, lng, dim3(256), 0, s, c->h, (const float*)nullptr, (const float*)nullptr, 0, c->a, H,
+                         d, d_R, R_cap);
+      linear<0>(s, c->a, w + o.cq_w, w + o.cq_b, c->qkv, R_cap, H, d, d, d_R);
+      hipLaunchKernelGGL(k_attn, dim3(R_cap, n.heads), dim3(256), H * S * sizeof(float), s, c->qkv, d,
+                         n.kc + l * per_layer, n.vc + l * per_layer, d, env_arr, c->ao, d, H, S, dh, d_R, R_cap);
+      linear<2>(s, c->ao, w + o.co_w, w + o.co_b, c->h, R_cap, H, d, d, d_R);
+    }
+    hipLaunchKernelGGL(k_lnmod, lng, dim3(256), 0, s, c->h, mod + 2 * d, mod + 3 * d, ms, c->a, H, d, d_R, R_cap);
+    linear<1>(s, c->a, w + o.up_w, w + o.up_b, c->u, R_cap, H, m, d, d_R);
+    linear<2>(s, c->u, w + o.dn_w, w + o.dn_b, c->h, R_cap, H, d, m, d_R);
+  }
+  hipLaunchKernelGGL(k_lnmod, lng, dim3(256), 0, s, c->h, (const float*)nullptr, (const float*)nullptr, 0, c->a, H, d,
+                     d_R, R_cap);
+  linear<0>(s, c->a, w + n.head_w, w + n.head_b, eps_out, R_cap, H, A, d, d_R);
+}
+
+int ensure_workspace(tsdp_ctx* c) {
+  if (c->ws_ready) return TSDP_OK;
+  const tsdp_config& cf = c->cfg;
+  const size_t Rw = (size_t)cf.B_max * cf.K_max, Mw = Rw * cf.H;
+  const size_t dmax = std::max(cf.base_d, cf.draft_d);
+  const size_t mmax = std::max(c->net[0].m, c->net[1].m);
+  const size_t lmax = std::max(cf.base_layers, cf.draft_layers);
+  int rc;
+  if ((rc = dev_alloc(c, &c->h, Mw * dmax))) return rc;
+  if ((rc = dev_alloc(c, &c->a, Mw * dmax))) return rc;
+  if ((rc = dev_alloc(c, &c->qkv, Mw * 3 * dmax))) return rc;
+  if ((rc = dev_alloc(c, &c->ao, Mw * dmax))) return rc;
+  if ((rc = dev_alloc(c, &c->u, Mw * mmax))) return rc;
+  if ((rc = dev_alloc(c, &c->sg, Rw * dmax))) return rc;
+  if ((rc = dev_alloc(c, &c->mod, Rw * lmax * 4 * dmax))) return rc;
+  if ((rc = dev_alloc(c, &c->eps_tmp, (size_t)cf.B_max * c->D))) return rc;
+  c->ws_ready = true;
+  return TSDP_OK;
+}
+
+int ensure_round_buffers(tsdp_ctx* c) {
+  if (c->rb_ready) return TSDP_OK;
+  const tsdp_config& cf = c->cfg;
+  const size_t Rw = (size_t)cf.B_max * cf.K_max, B = cf.B_max, D = c->D;
+  int rc;
+  if ((rc = dev_alloc(c, &c->row_ptr, B + 1))) return rc;
+  if ((rc = dev_alloc(c, &c->row_t, Rw))) return rc;
+  if ((rc = dev_alloc(c, &c->row_env, Rw))) return rc;
+  if ((rc = dev_alloc(c, &c->t_next, B))) return rc;
+  if ((rc = dev_alloc(c, &c->n_acc, B))) return rc;
+  if ((rc = dev_alloc(c, &c->n_adv, B))) return rc;
+  if ((rc = dev_alloc(c, &c->states, Rw * D))) return rc;
+  if ((rc = dev_alloc(c, &c->eps_p, Rw * D))) return rc;
+  if ((rc = dev_alloc(c, &c->eps_q, Rw * D))) return rc;
+  if ((rc = dev_alloc(c, &c->xi, Rw * D))) return rc;
+  if ((rc = dev_alloc(c, &c->y_last, B * D))) return rc;
+  c->rb_ready = true;
+  return TSDP_OK;
+}
+
+int check_ready(tsdp_ctx* c, int B, bool need_nets) {
+  if (!c) return TSDP_E_INVAL;
+  if (B < 0 || B > c->cfg.B_max) return fail(c, TSDP_E_SHAPE, "B outside 0..B_max");
+  if (need_nets) {
+    if (!c->net[0].loaded || !c->net[1].loaded) return fail(c, TSDP_E_STATE, "weights of both networks must be loaded");
+    if (!c->cond_set) return fail(c, TSDP_E_STATE, "tsdp_set_cond has not been called");
+    if (B > c->cond_B) return fail(c, TSDP_E_SHAPE, "B exceeds the batch given to tsdp_set_cond");
+  }
+  return TSDP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int tsdp_create(const tsdp_config* cfg, tsdp_ctx** out) {
+  if (!cfg || !out) return TSDP_E_INVAL;
+  *out = nullptr;
+  const tsdp_config& f = *cfg;
+  auto bad = [&](int d, int heads, int L, int mr) {
+    return L < 1 || L > 64 || d < 8 || d > 1024 || d % 4 || heads < 1 || d % heads || (d / heads) > 128 || mr < 1 || mr > 8;
+  };
+  if (f.dtype < 0 || f.dtype > 1 || f.H < 1 || f.H > 64 || f.A < 1 || f.A > 64 || (f.H * f.A) % 4 || f.cond_mode < 0 ||
+      f.cond_mode > 1 || f.cond_dim < 4 || f.cond_dim % 4 || (f.cond_mode == 1 && (f.cond_tokens < 1 || f.cond_tokens > 256)) ||
+      bad(f.base_d, f.base_heads, f.base_layers, f.base_mlp_ratio) ||
+      bad(f.draft_d, f.draft_heads, f.draft_layers, f.draft_mlp_ratio) || f.T < 1 || f.T > 4096 || f.schedule < 0 ||
+      f.schedule > 1 || f.B_max < 1 || f.K_max < 1 || f.K_max > 64 || (f.clip_x0 && !(f.clip_val > 0.0f)))
+    return TSDP_E_INVAL;
+  if (f.schedule == 0 && !(f.beta0 > 0.0f && f.beta1 >= f.beta0 && f.beta1 < 1.0f)) return TSDP_E_INVAL;
+  if ((long long)f.B_max * f.K_max > (1ll << 24)) return TSDP_E_SHAPE;
+  tsdp_ctx* c = new (std::nothrow) tsdp_ctx();
+  if (!c) return TSDP_E_NOMEM;
+  c->cfg = f;
+  c->D = f.H * f.A;
+  layout_net(f, 0, c->net[0]);
+  layout_net(f, 1, c->net[1]);
+  // DDPM tables: textbook epsilon-prediction posterior with the fixed-small variance, fp64 then fp32
+  const int T = f.T;
+  std::vector<double> beta(T), abar(T);
+  const double PI = 3.14159265358979323846;
+  for (int i = 0; i < T; ++i) {
+    if (f.schedule == 0) {
+      beta[i] = T == 1 ? (double)f.beta0 : (double)f.beta0 + ((double)f.beta1 - (double)f.beta0) * i / (T - 1);
+    } else {
+      auto fc = [&](double j) { double v = std::cos(((j / T) + 0.008) / 1.008 * PI / 2.0); return v * v; };
+      beta[i] = std::min(1.0 - fc(i + 1.0) / fc((double)i), 0.999);
+    }
+    abar[i] = (i ? abar[i - 1] : 1.0) * (1.0 - beta[i]);
+  }
+  std::vector<float> tab(5 * (size_t)T);
+  for (int t = 0; t < T; ++t) {
+    const double ap = t ? abar[t - 1] : 1.0;
+    tab[0 * T + t] = (float)std::sqrt(abar[t]);
+    tab[1 * T + t] = (float)std::sqrt(1.0 - abar[t]);
+    tab[2 * T + t] = (float)(std::sqrt(ap) * beta[t] / (1.0 - abar[t]));
+    tab[3 * T + t] = (float)(std::sqrt(1.0 - beta[t]) * (1.0 - ap) / (1.0 - abar[t]));
+    tab[4 * T + t] = (float)std::sqrt(beta[t] * (1.0 - ap) / (1.0 - abar[t]));
+  }
+  auto cleanup = [&](int code) { tsdp_destroy(c); return code; };
+  if (dev_alloc(c, &c->tables, tab.size())) return cleanup(TSDP_E_NOMEM);
+  if (hipMemcpy(c->tables, tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess)
+    return cleanup(TSDP_E_HIP);
+  c->tb = {c->tables, c->tables + T, c->tables + 2 * T, c->tables + 3 * T, c->tables + 4 * T, T};
+  if (dev_alloc(c, &c->status, 1) || dev_alloc(c, &c->K_eff, (size_t)f.B_max)) return cleanup(TSDP_E_NOMEM);
+  if (hipMemset(c->status, 0, sizeof(int32_t)) != hipSuccess) return cleanup(TSDP_E_HIP);
+  *out = c;
+  return TSDP_OK;
+}
+
+void tsdp_destroy(tsdp_ctx* c) {
+  if (!c) return;
+  (void)hipDeviceSynchronize();
+  for (void* p : c->owned) (void)hipFree(p);
+  delete c;
+}
+
+int tsdp_load_weights(tsdp_ctx* c, int which, const float* h_blob, size_t nbytes) {
+  if (!c) return TSDP_E_INVAL;
+  if (!h_blob || which < 0 || which > 1) return fail(c, TSDP_E_INVAL, "bad argument to tsdp_load_weights");
+  Net& n = c->net[which];
+  if (nbytes != n.n_floats * sizeof(float))
+    return fail(c, TSDP_E_SHAPE, "weight blob has " + std::to_string(nbytes) + " bytes, expected " +
+                                     std::to_string(n.n_floats * sizeof(float)));
+  const tsdp_config& cf = c->cfg;
+  std::vector<float> w(h_blob, h_blob + n.n_floats);
+  if (cf.dtype == 1)
+    for (auto& v : w) v = bf16_round(v);
+  const int d = n.d, T = cf.T, L = n.L;
+  // timestep embedding of every timestep (depends on the weights only): fp64 on the host
+  std::vector<float> temb((size_t)T * d);
+  {
+    const int half = d / 2;
+    std::vector<double> e(d), hdn(d);
+    for (int t = 0; t < T; ++t) {
+      for (int i = 0; i < half; ++i) {
+        const double fr = std::exp(-std::log(10000.0) * i / half);
+        e[i] = std::sin(t * fr);
+        e[half + i] = std::cos(t * fr);
+      }
+      for (int i = 2 * half; i < d; ++i) e[i] = 0.0;
+      for (int o = 0; o < d; ++o) {
+        double acc = w[n.t_b1 + o];
+        for (int i = 0; i < d; ++i) acc += (double)w[n.t_w1 + (size_t)o * d + i] * e[i];
+        hdn[o] = acc / (1.0 + std::exp(-acc));
+      }
+      for (int o = 0; o < d; ++o) {
+        double acc = w[n.t_b2 + o];
+        for (int i = 0; i < d; ++i) acc += (double)w[n.t_w2 + (size_t)o * d + i] * hdn[i];
+        temb[(size_t)t * d + o] = (float)acc;
+      }
+    }
+  }
+  std::vector<float> modw((size_t)L * 4 * d * d), modb((size_t)L * 4 * d);
+  for (int l = 0; l < L; ++l) {
+    std::memcpy(&modw[(size_t)l * 4 * d * d], &w[n.lay[l].mod_w], sizeof(float) * 4 * d * d);
+    std::memcpy(&modb[(size_t)l * 4 * d], &w[n.lay[l].mod_b], sizeof(float) * 4 * d);
+  }
+  int rc;
+  if (!n.blob) {
+    if ((rc = dev_alloc(c, &n.blob, n.n_floats))) return rc;
+    if ((rc = dev_alloc(c, &n.temb, temb.size()))) return rc;
+    if ((rc = dev_alloc(c, &n.modw, modw.size()))) return rc;
+    if ((rc = dev_alloc(c, &n.modb, modb.size()))) return rc;
+    if (cf.cond_mode == 0) {
+      if ((rc = dev_alloc(c, &n.cemb, (size_t)cf.B_max * d))) return rc;
+    } else {
+      const size_t cnt = (size_t)L * cf.B_max * cf.cond_tokens * d;
+      if ((rc = dev_alloc(c, &n.kc, cnt))) return rc;
+      if ((rc = dev_alloc(c, &n.vc, cnt))) return rc;
+    }
+  }
+  HIPCHK(c, hipDeviceSynchronize());
+  HIPCHK(c, hipMemcpy(n.blob, w.data(), w.size() * sizeof(float), hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(n.temb, temb.data(), temb.size() * sizeof(float), hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(n.modw, modw.data(), modw.size() * sizeof(float), hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(n.modb, modb.data(), modb.size() * sizeof(float), hipMemcpyHostToDevice));
+  n.loaded = true;
+  c->cond_set = false;
+  return TSDP_OK;
+}
+
+int tsdp_set_cond(tsdp_ctx* c, const float* d_cond, int B, void* stream) {
+  if (!c) return TSDP_E_INVAL;
+  if (!d_cond) return fail(c, TSDP_E_INVAL, "d_cond is null");
+  if (B < 1 || B > c->cfg.B_max) return fail(c, TSDP_E_SHAPE, "B outside 1..B_max");
+  if (!c->net[0].loaded || !c->net[1].loaded) return fail(c, TSDP_E_STATE, "weights of both networks must be loaded");
+  hipStream_t s = (hipStream_t)stream;
+  const tsdp_config& cf = c->cfg;
+  for (int which = 0; which < 2; ++which) {
+    Net& n = c->net[which];
+    const float* w = n.blob;
+    if (cf.cond_mode == 0) {
+      linear<0>(s, d_cond, w + n.c_w, w + n.c_b, n.cemb, B, 1, n.d, cf.cond_dim, nullptr);
+    } else {
+      const int S = cf.cond_tokens;
+      const size_t per_layer = (size_t)cf.B_max * S * n.d;
+      for (int l = 0; l < n.L; ++l) {
+        linear<0>(s, d_cond, w + n.lay[l].ck_w, w + n.lay[l].ck_b, n.kc + l * per_layer, B * S, 1, n.d, cf.cond_dim, nullptr);
+        linear<0>(s, d_cond, w + n.lay[l].cv_w, w + n.lay[l].cv_b, n.vc + l * per_layer, B * S, 1, n.d, cf.cond_dim, nullptr);
+      }
+    }
+  }
+  HIPCHK(c, hipGetLastError());
+  c->cond_set = true;
+  c->cond_B = B;
+  return TSDP_OK;
+}
+
+int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const int32_t* d_K,
+               const float* d_sigma_scale, const int32_t* d_env_id, int32_t* d_row_ptr, int32_t* d_row_t,
+               int32_t* d_row_env, float* d_states, float* d_eps_p, float* d_xi, float* d_y_last, void* stream) {
+  int rc = check_ready(c, B, true);
+  if (rc) return rc;
+  if (!d_x || !d_t0 || !d_K || !d_sigma_scale || !d_row_ptr || !d_row_t || !d_row_env || !d_states || !d_eps_p ||
+      !d_xi || !d_y_last)
+    return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_draft");
+  if (B == 0) return TSDP_OK;
+  if ((rc = ensure_workspace(c))) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  const tsdp_config& cf = c->cfg;
+  const int D = c->D;
+  hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, d_t0, d_K, B, cf.K_max, cf.T, c->K_eff, d_row_ptr, c->status);
+  hipLaunchKernelGGL(k_rows, dim3(B), dim3(128), 0, s, d_x, d_t0, (const int32_t*)d_row_ptr, cf.T, D, d_row_t,
+                     d_row_env, d_y_last, d_states, d_eps_p, d_xi);
+  for (int k = 1; k <= cf.K_max; ++k) {
+    // every environment runs the drafter at step k; the DDPM step masks those with K_eff < k
+    forward_f32(c, c->net[1], d_y_last, B, nullptr, d_t0, k - 1, nullptr, c->eps_tmp, s);
+    hipLaunchKernelGGL(k_draft_step, grid1((long long)B * (D / 4), 256), dim3(256), 0, s, k, (const float*)c->eps_tmp,
+                       d_t0, (const int32_t*)c->K_eff, (const int32_t*)d_row_ptr, d_sigma_scale, d_env_id, c->tb,
+                       cf.clip_x0, cf.clip_val, cf.seed, B, D, d_y_last, d_states, d_eps_p, d_xi);
+  }
+  HIPCHK(c, hipGetLastError());
+  return TSDP_OK;
+}
+
+int tsdp_verify(tsdp_ctx* c, int B, int R_cap, const int32_t* d_row_ptr, const int32_t* d_row_t,
+                const int32_t* d_row_env, const float* d_states, float* d_eps_q, void* stream) {
+  int rc = check_ready(c, B, true);
+  if (rc) return rc;
+  if (!d_row_ptr || !d_row_t || !d_row_env || !d_states || !d_eps_q)
+    return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_verify");
+  if (R_cap < 0 || (long long)R_cap > (long long)c->cfg.B_max * c->cfg.K_max)
+    return fail(c, TSDP_E_SHAPE, "R_cap outside 0..B_max*K_max");
+  if (B == 0 || R_cap == 0) return TSDP_OK;
+  if ((rc = ensure_workspace(c))) return rc;
+  forward_f32(c, c->net[0], d_states, R_cap, d_row_ptr + B, d_row_t, 0, d_row_env, d_eps_q, (hipStream_t)stream);
+  HIPCHK(c, hipGetLastError());
+  return TSDP_OK;
+}
+
+int tsdp_accept(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32_t* d_row_t, const int32_t* d_env_id,
+                const float* d_sigma_scale, const float* d_states, const float* d_eps_p, const float* d_eps_q,
+                const float* d_xi, const float* d_y_last, float* d_x_out, int32_t* d_t_next, int32_t* d_n_accept,
+                int32_t* d_n_adv, uint8_t* d_flags, float* d_logratio, float* d_logu, void* stream) {
+  int rc = check_ready(c, B, false);
+  if (rc) return rc;
+  if (!d_row_ptr || !d_row_t || !d_sigma_scale || !d_states || !d_eps_p || !d_eps_q || !d_xi || !d_y_last || !d_x_out ||
+      !d_t_next || !d_n_accept)
+    return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_accept");
+  if (B == 0) return TSDP_OK;
+  hipStream_t s = (hipStream_t)stream;
+  const tsdp_config& cf = c->cfg;
+  const dim3 g((B + 3) / 4), blk(256);
+  if (cf.clip_x0)
+    hipLaunchKernelGGL(k_accept<true>, g, blk, 0, s, B, c->D, d_row_ptr, d_row_t, d_env_id, d_sigma_scale, d_states,
+                       d_eps_p, d_eps_q, d_xi, d_y_last, c->tb, cf.clip_val, cf.seed, d_x_out, d_t_next, d_n_accept,
+                       d_n_adv, d_flags, d_logratio, d_logu);
+  else
+    hipLaunchKernelGGL(k_accept<false>, g, blk, 0, s, B, c->D, d_row_ptr, d_row_t, d_env_id, d_sigma_scale, d_states,
+                       d_eps_p, d_eps_q, d_xi, d_y_last, c->tb, cf.clip_val, cf.seed, d_x_out, d_t_next, d_n_accept,
+                       d_n_adv, d_flags, d_logratio, d_logu);
+  HIPCHK(c, hipGetLastError());
+  return TSDP_OK;
+}
+
+int tsdp_round(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
+               const int32_t* d_env_id, int32_t* d_n_accept, int32_t* d_n_advanced, void* stream) {
+  int rc = check_ready(c, B, true);
+  if (rc) return rc;
+  if (!d_x || !d_t || !d_K || !d_sigma_scale) return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_round");
+  if (B == 0) return TSDP_OK;
+  if ((rc = ensure_round_buffers(c))) return rc;
+  if ((rc = tsdp_draft(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, c->row_ptr, c->row_t, c->row_env, c->states,
+                       c->eps_p, c->xi, c->y_last, stream)))
+    return rc;
+  if ((rc = tsdp_verify(c, B, B * c->cfg.K_max, c->row_ptr, c->row_t, c->row_env, c->states, c->eps_q, stream)))
+    return rc;
+  // x and t are overwritten in place: the acceptance kernel reads only the round's own buffers
+  return tsdp_accept(c, B, c->row_ptr, c->row_t, d_env_id, d_sigma_scale, c->states, c->eps_p, c->eps_q, c->xi,
+                     c->y_last, d_x, d_t, d_n_accept ? d_n_accept : c->n_acc, d_n_advanced ? d_n_advanced : c->n_adv,
+                     nullptr, nullptr, nullptr, stream);
+}
+
+int tsdp_status(tsdp_ctx* c, void* stream, int32_t* h_status) {
+  if (!c || !h_status) return TSDP_E_INVAL;
+  hipStream_t s = (hipStream_t)stream;
+  HIPCHK(c, hipMemcpyAsync(h_status, c->status, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  HIPCHK(c, hipStreamSynchronize(s));
+  // cleared with a tiny fill kernel-free path: a synchronous memset outside any capture
+  HIPCHK(c, hipMemset(c->status, 0, sizeof(int32_t)));
+  return TSDP_OK;
+}
+
+const char* tsdp_path_name(const tsdp_ctx* c, int which) {
+  if (!c || which < 0 || which > 1) return "";
+  return c->net[which].path;
+}
+
+const char* tsdp_last_error(const tsdp_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+}  // extern "C"

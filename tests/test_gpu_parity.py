@@ -1,0 +1,215 @@
+"""GPU parity: every C entry point against the CPU oracle on the same seeded inputs (needs an MI355X)."""
+import numpy as np
+import pytest
+
+import tsdp_inputs as ti
+from oracle import philox, spec_round as sr
+from tests.helpers import gpu_side, oracle_side, scaled_err, to_dev
+
+pytestmark = pytest.mark.gpu
+
+# Tolerances.  fp32 networks: the GPU accumulates dot products of length <= 4d in fp32 through L
+# residual layers, the oracle in fp64; the bound used is 1e-5 of the tensor scale plus rtol 1e-5.
+# bf16 networks: matrix-multiply inputs are rounded to bfloat16 (2^-9 relative), bound 2e-2 of scale.
+TOL = {"fp32": 1e-5, "bf16": 2e-2}
+TIE = 1e-5          # accept flags may differ only where |log U - log alpha| is below this (fp32 nets)
+
+
+def _setup(wl, B, clip=None, K_max=None, b_std=0.02, head_scale=1.0, seed=None):
+    wb = ti.make_weights(wl, "base", b_std=b_std, head_scale=head_scale)
+    wd = ti.make_weights(wl, "draft", b_std=b_std, head_scale=head_scale)
+    cond = ti.make_cond(wl, B)
+    x = ti.make_latents(wl, B)
+    base, drafter, sched = oracle_side(wl, wb, wd)
+    ctx = gpu_side(wl, wb, wd, cond, clip=clip, B_max=B, K_max=K_max, seed=seed)
+    return dict(wl=wl, B=B, cond=cond, x=x, base=base, drafter=drafter, sched=sched, ctx=ctx, clip=clip,
+                seed=wl.philox_seed if seed is None else seed)
+
+
+def _gpu_draft(S, t0, K, s, env):
+    ctx, B = S["ctx"], S["B"]
+    rows = ctx.alloc_rows(B)
+    ctx.tsdp_draft(to_dev(S["x"]), to_dev(t0.astype(np.int32)), to_dev(K.astype(np.int32)), to_dev(s.astype(np.float32)),
+                   None if env is None else to_dev(env.astype(np.int32)), rows)
+    return rows
+
+
+def _check_draft(S, rows, t0, K, s, env, tol):
+    o = sr.draft(S["drafter"], S["sched"], S["x"], t0, K, s, env, S["seed"], S["cond"], S["clip"])
+    R = int(o["row_ptr"][-1])
+    np.testing.assert_array_equal(rows["row_ptr"].cpu().numpy(), o["row_ptr"])
+    np.testing.assert_array_equal(rows["row_t"].cpu().numpy()[:R], o["row_t"])
+    np.testing.assert_array_equal(rows["row_env"].cpu().numpy()[:R], o["row_env"])
+    xi = rows["xi"].cpu().numpy()[:R]
+    np.testing.assert_allclose(xi, o["xi"], rtol=1e-5, atol=2e-6)      # fp32 Box-Muller vs fp64
+    for name in ("states", "eps_p"):
+        e = scaled_err(rows[name].cpu().numpy()[:R], o[name])
+        assert e < tol, (name, e)
+    e = scaled_err(rows["y_last"].cpu().numpy(), o["y_last"])
+    assert e < tol, ("y_last", e)
+    return o
+
+
+def _check_verify(S, rows, o, tol):
+    ctx, B = S["ctx"], S["B"]
+    ctx.tsdp_verify(B, rows)
+    R = int(o["row_ptr"][-1])
+    st = rows["states"].cpu().numpy()[:R]
+    ref = sr.verify(S["base"], o["row_env"], o["row_t"], st, S["cond"])   # oracle on the GPU's own states
+    got = rows["eps_q"].cpu().numpy()[:R]
+    e = scaled_err(got, ref)
+    assert e < tol, ("eps_q", e)
+    return ref
+
+
+def _check_accept(S, rows, o, s, env, window):
+    """tsdp_accept against the oracle on the identical tensors: indices exact outside the near-tie
+    window, latents to fp32 rounding."""
+    ctx, B = S["ctx"], S["B"]
+    out = ctx.tsdp_accept(B, to_dev(s.astype(np.float32)), None if env is None else to_dev(env.astype(np.int32)), rows)
+    R = int(o["row_ptr"][-1])
+    g = {k: v.cpu().numpy() for k, v in out.items()}
+    ref = sr.accept(S["sched"], o["row_ptr"], o["row_t"], s.astype(np.float32), env, S["seed"],
+                    rows["states"].cpu().numpy()[:R], rows["eps_p"].cpu().numpy()[:R], rows["eps_q"].cpu().numpy()[:R],
+                    rows["xi"].cpu().numpy()[:R], rows["y_last"].cpu().numpy(), S["clip"])
+    np.testing.assert_allclose(g["logu"][:R], ref["logu"], rtol=1e-6, atol=1e-7)
+    np.testing.assert_allclose(g["logratio"][:R], ref["logratio"], rtol=1e-6, atol=1e-6)
+    near = np.abs(ref["logu"] - ref["logratio"]) < window
+    diff = g["flags"][:R] != ref["flags"]
+    assert not np.any(diff & ~near), "accept flag differs outside the near-tie window"
+    env_ok = np.array([not np.any(diff[o["row_ptr"][b]:o["row_ptr"][b + 1]]) for b in range(B)])
+    for k in ("n_accept", "n_adv", "t_next"):
+        np.testing.assert_array_equal(g[k][env_ok], ref[k][env_ok])
+    np.testing.assert_allclose(g["x_out"][env_ok], ref["x_out"][env_ok], rtol=1e-5, atol=1e-6)
+    return g, ref, env_ok
+
+
+def _stage_parity(wl, B, t0, K, s, env=None, clip=None, b_std=0.02):
+    S = _setup(wl, B, clip=clip, b_std=b_std)
+    tol = TOL[wl.dtype]
+    rows = _gpu_draft(S, t0, K, s, env)
+    o = _check_draft(S, rows, t0, K, s, env, tol)
+    _check_verify(S, rows, o, tol)
+    g, ref, _ = _check_accept(S, rows, o, s, env, 1e-9)
+    S["ctx"].close()
+    return g, ref
+
+
+def test_c1_stages():
+    wl = ti.C1
+    g, ref = _stage_parity(wl, 1, np.array([9]), np.array([4]), np.array([1.0]))
+    assert ref["n_adv"][0] >= 1
+
+
+def test_c1_ragged_edges_with_clip():
+    # K_eff = 0 (t0 = 0), finished env, t0 < K, K = 0 and K = 1, per-env sigma scale, env ids, clamped x0
+    wl = ti.small_variant(ti.C1, B=8)
+    t0 = np.array([9, 0, -1, 2, 5, 7, 1, 9]); K = np.array([4, 4, 4, 4, 0, 1, 3, 2])
+    s = np.array([1.0, 1.0, 1.0, 1.3, 1.0, 1.5, 1.2, 1.1]); env = np.array([5, 900, 3, 77, 1, 0, 12345678, 42])
+    for clip in (None, 1.0):
+        g, ref = _stage_parity(wl, 8, t0, K, s, env, clip=clip)
+        np.testing.assert_array_equal(ref["n_adv"][[1, 2, 4]], [1, 0, 1])
+
+
+def test_c2_stages():
+    wl = ti.C2
+    _stage_parity(wl, 1, np.array([99]), np.array([8]), np.array([1.0]))
+    _stage_parity(wl, 1, np.array([50]), np.array([8]), np.array([1.0]))
+
+
+@pytest.mark.parametrize("name,B", [("C3", 3), ("C5", 6)])
+def test_bf16_vector_cond_stages(name, B):
+    wl = ti.small_variant(ti.WORKLOADS[name], B=B)
+    t0, K, s = ti.make_schedule_inputs(wl, B, t0=None if wl.ragged else 60)
+    _stage_parity(wl, B, t0, K, s)
+
+
+def test_c4_cross_attention_stages():
+    wl = ti.small_variant(ti.C4, B=2, base=ti.NetShape(3, 512, 8))
+    t0, K, s = ti.make_schedule_inputs(wl, 2, t0=40)
+    _stage_parity(wl, 2, t0, K, s)
+
+
+def _round_parity(wl, B, t0, K, s, env, window, head_scale=1.0):
+    import torch
+    S = _setup(wl, B, head_scale=head_scale)
+    ctx = S["ctx"]
+    x = to_dev(S["x"]); t = to_dev(t0.astype(np.int32))
+    nacc = torch.zeros(B, dtype=torch.int32, device="cuda"); nadv = torch.zeros_like(nacc)
+    ctx.tsdp_round(x, t, to_dev(K.astype(np.int32)), to_dev(s.astype(np.float32)),
+                   None if env is None else to_dev(env.astype(np.int32)), nacc, nadv)
+    ref = sr.spec_round(S["base"], S["drafter"], S["sched"], S["x"], t0, K, s, env, S["seed"], S["cond"])
+    d = ref["draft"]
+    near_env = np.array([np.any(np.abs(ref["logu"][d["row_ptr"][b]:d["row_ptr"][b + 1]] -
+                                       ref["logratio"][d["row_ptr"][b]:d["row_ptr"][b + 1]]) < window) for b in range(B)])
+    ok = ~near_env
+    np.testing.assert_array_equal(nacc.cpu().numpy()[ok], ref["n_accept"][ok])
+    np.testing.assert_array_equal(nadv.cpu().numpy()[ok], ref["n_adv"][ok])
+    np.testing.assert_array_equal(t.cpu().numpy()[ok], ref["t_next"][ok])
+    e = scaled_err(x.cpu().numpy()[ok], ref["x_out"][ok])
+    assert e < TOL[wl.dtype], e
+    assert ctx.tsdp_status() == 0
+    ctx.close()
+    return ref, near_env
+
+
+def test_c1_round():
+    ref, near = _round_parity(ti.C1, 1, np.array([9]), np.array([4]), np.array([1.0]), None, 1e-4)
+    assert not near.any()
+
+
+def test_c2_round_and_chain():
+    wl = ti.C2
+    for t0 in (99, 50, 8, 3):
+        _round_parity(wl, 1, np.array([t0]), np.array([8]), np.array([1.0]), None, 1e-4)
+
+
+def test_round_ragged_batch_fp32():
+    wl = ti.small_variant(ti.C2, B=12, base=ti.NetShape(3, 256, 4))
+    rng = np.random.default_rng(3)
+    t0 = rng.integers(-1, 100, 12); K = rng.integers(0, 9, 12); s = rng.uniform(1, 1.5, 12)
+    t0[:3] = [0, -1, 2]
+    ref, near = _round_parity(wl, 12, t0, K, s, np.arange(12) + 1000, 1e-4, head_scale=0.5)
+    assert near.sum() <= 2
+    assert (ref["n_accept"] > 0).any() and (ref["n_accept"] < ref["draft"]["K_eff"]).any()
+
+
+def test_device_status_reports_clamped_inputs():
+    wl = ti.C1
+    S = _setup(wl, 1)
+    rows = S["ctx"].alloc_rows(1)
+    S["ctx"].tsdp_draft(to_dev(S["x"]), to_dev(np.array([50], np.int32)), to_dev(np.array([9], np.int32)),
+                        to_dev(np.array([1.0], np.float32)), None, rows)
+    assert S["ctx"].tsdp_status() == 3                                # K > K_max and t0 >= T, both clamped
+    assert rows["row_ptr"].cpu().numpy().tolist() == [0, 4]
+    assert rows["row_t"].cpu().numpy()[:4].tolist() == [9, 8, 7, 6]
+    assert S["ctx"].tsdp_status() == 0
+    S["ctx"].close()
+
+
+def test_error_paths_return_codes():
+    import torch
+    from paper_2512_15773_amd import Tsdp, TsdpError
+    wl = ti.C1
+    ctx = Tsdp.from_workload(wl)
+    x = torch.zeros(1, wl.H, wl.A, device="cuda"); i = torch.zeros(1, dtype=torch.int32, device="cuda")
+    f = torch.ones(1, device="cuda")
+    with pytest.raises(TsdpError) as e:
+        ctx.tsdp_round(x, i, i, f, None)
+    assert e.value.code == -5                                          # weights not loaded
+    with pytest.raises(TsdpError) as e:
+        ctx.tsdp_load_weights(0, np.zeros(7, np.float32))
+    assert e.value.code == -2
+    ctx.tsdp_load_weights(0, ti.pack_blob(ti.make_weights(wl, "base")))
+    ctx.tsdp_load_weights(1, ti.pack_blob(ti.make_weights(wl, "draft")))
+    with pytest.raises(TsdpError) as e:
+        ctx.tsdp_round(x, i, i, f, None)
+    assert e.value.code == -5                                          # conditioning not set
+    ctx.tsdp_set_cond(torch.zeros(1, wl.cond_dim, device="cuda"))
+    x2 = torch.zeros(2, wl.H, wl.A, device="cuda")
+    with pytest.raises(TsdpError) as e:
+        ctx.tsdp_round(x2, torch.zeros(2, dtype=torch.int32, device="cuda"), torch.zeros(2, dtype=torch.int32, device="cuda"),
+                       torch.ones(2, device="cuda"), None)
+    assert e.value.code == -2                                          # B > B_max
+    ctx.tsdp_round(x, i, i, f, None)
+    ctx.close()
