@@ -1,0 +1,417 @@
+// Fused bf16 MFMA forward of the denoiser: one workgroup carries a tile of NT tokens (NT/H rows)
+// through ALL layers in a single launch.  The fp32 residual stream lives in MFMA accumulator
+// registers, bf16 activations are staged in LDS, and the weights stream from L2 straight into
+// registers in a fragment order prepared at load time.  Every product is computed transposed
+// (output features on the MFMA M axis, tokens on the N axis), so that an accumulator holds four
+// consecutive features of one token and can be stored to LDS as one 8-byte bf16 vector.
+//
+// mfma_f32_16x16x32_bf16 operand layout (checked on hardware): lane l supplies row (l%16) and the
+// eight K entries (l/16)*8.. of A and of B^T; it receives column (l%16), rows (l/16)*4.. of C.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tsdp {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+struct FusedLayer {            // device pointers of one layer
+  const bf16x8* qkv;           // [3D/16][D/32][64] fragments, rows grouped per head group as q|k|v per head
+  const bf16x8* o;             // [D/16][D/32][64]
+  const bf16x8* up;            // [M/16][D/32][64]
+  const bf16x8* dn;            // [D/16][M/32][64]
+  const bf16x8* cq;            // [D/16][D/32][64]   (cross-attention only)
+  const bf16x8* co;            // [D/16][D/32][64]
+  const float* qkv_b;          // [3D] in the same row order as qkv
+  const float* o_b; const float* up_b; const float* dn_b; const float* cq_b; const float* co_b;
+};
+
+constexpr int FUSED_MAX_LAYERS = 16;
+
+struct FusedNet {
+  FusedLayer layer[FUSED_MAX_LAYERS];
+  int L;
+  const float* tok_w; const float* tok_b; const float* pos;   // fp32 [D,A], [D], [H,D]
+  const bf16x8* head;          // [1][D/32][64] fragments of head_w padded to 16 rows
+  const float* head_b;         // [A]
+  // cross-attention operands of every (env, layer, head), prepared by tsdp_set_cond:
+  const bf16x8* kc;            // [B][L][HEADS][S/16][DH/32][64]  keys as MFMA A fragments
+  const bf16x4* vct;           // [B][L][HEADS][DH/16][S/16][64]  values transposed as 16x16x16 A fragments
+  int S;                       // observation tokens
+};
+
+struct FusedIO {
+  const float* x_rows;         // [R,H,A]
+  const float* mod;            // [R, L*4*D] FiLM vectors (g1,b1,g2,b2 per layer)
+  const int32_t* row_env;      // [R] or null (row index is the environment)
+  const int32_t* d_R;          // live rows on the device, or null
+  int R_cap;
+  float* eps_out;              // [R,H,A]
+};
+
+__device__ __forceinline__ float gelu_fast(float x) {
+  // x * sigmoid(2 sqrt(2/pi) (x + 0.044715 x^3)) == tanh form of GELU
+  const float u = 1.5957691216057308f * (x + 0.044715f * x * x * x);
+  return x / (1.0f + __expf(-u));
+}
+
+__device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
+  bf16x4 r;
+  r[0] = (__bf16)v[0]; r[1] = (__bf16)v[1]; r[2] = (__bf16)v[2]; r[3] = (__bf16)v[3];
+  return r;
+}
+
+// acc[mb][nb] += W(frag rows mf0+mb, k-steps ks0..ks0+nks) . act^T ; act is LDS bf16 [token][stride]
+template <int MB, int NB>
+__device__ __forceinline__ void gemm_frag(const bf16x8* __restrict__ wp, int ks_total, int mf0, int ks0, int nks,
+                                          const __bf16* act, int stride, f32x4 (&acc)[MB][NB], int lane) {
+  constexpr int PF = 2;                               // k-steps of weights in flight ahead of the MFMAs
+  const bf16x8* wl = wp + ((size_t)mf0 * ks_total + ks0) * 64 + lane;
+  const __bf16* al = act + (lane & 15) * stride + (lane >> 4) * 8;
+  bf16x8 a[PF + 1][MB];
+#pragma unroll
+  for (int p = 0; p < PF; ++p)
+    if (p < nks) {
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) a[p][mb] = wl[((size_t)mb * ks_total + p) * 64];
+    }
+#pragma unroll 1
+  for (int ks = 0; ks < nks; ks += PF + 1) {
+#pragma unroll
+    for (int u = 0; u < PF + 1; ++u) {
+      const int k = ks + u;
+      if (k < nks) {
+        const int slot_n = (u + PF) % (PF + 1);
+        if (k + PF < nks) {
+#pragma unroll
+          for (int mb = 0; mb < MB; ++mb) a[slot_n][mb] = wl[((size_t)mb * ks_total + k + PF) * 64];
+        }
+        bf16x8 b[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) b[nb] = *reinterpret_cast<const bf16x8*>(al + nb * 16 * stride + k * 32);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+            acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][mb], b[nb], acc[mb][nb], 0, 0, 0);
+      }
+    }
+  }
+}
+
+// Per-token LayerNorm statistics of the register-resident residual h (features split over 4 waves).
+template <int MBH, int NB, int D>
+__device__ __forceinline__ void ln_stats(const f32x4 (&h)[MBH][NB], float* red1, float* red2, int NT, int wave, int lane,
+                                         float (&mean)[NB], float (&rstd)[NB]) {
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    float s = 0.0f;
+#pragma unroll
+    for (int mb = 0; mb < MBH; ++mb) s += h[mb][nb][0] + h[mb][nb][1] + h[mb][nb][2] + h[mb][nb][3];
+    s += __shfl_xor(s, 16); s += __shfl_xor(s, 32);
+    if (lane < 16) red1[wave * NT + nb * 16 + lane] = s;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int t = nb * 16 + (lane & 15);
+    mean[nb] = (red1[t] + red1[NT + t] + red1[2 * NT + t] + red1[3 * NT + t]) * (1.0f / D);
+    float q = 0.0f;
+#pragma unroll
+    for (int mb = 0; mb < MBH; ++mb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { const float e = h[mb][nb][i] - mean[nb]; q += e * e; }
+    q += __shfl_xor(q, 16); q += __shfl_xor(q, 32);
+    if (lane < 16) red2[wave * NT + nb * 16 + lane] = q;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int t = nb * 16 + (lane & 15);
+    rstd[nb] = rsqrtf((red2[t] + red2[NT + t] + red2[2 * NT + t] + red2[3 * NT + t]) * (1.0f / D) + 1e-5f);
+  }
+}
+
+// D model width, NT tokens per workgroup, H tokens per row, HEADS attention heads, CM conditioning mode,
+// CH hidden-chunk width of the MLP.  256 threads = 4 wavefronts, each owning D/4 residual features.
+template <int D, int NT, int H, int HEADS, int CM, int CH>
+struct FusedCfg {
+  static constexpr int DH = D / HEADS;
+  static constexpr int HP = DH >= 64 ? 1 : 64 / DH;     // heads per attention phase
+  static constexpr int NB = NT / 16;                    // token fragments
+  static constexpr int MBH = D / 64;                    // residual feature fragments per wave
+  static constexpr int MBQ = HP * 3 * DH / 64;          // q|k|v feature fragments per wave and phase
+  static constexpr int MBU = CH / 64;
+  static constexpr int RPT = NT / H;                    // rows per tile
+  static constexpr int NKF = H / 16;                    // key / query fragments of self-attention
+  static constexpr int AS = D + 8;                      // LDS strides (bf16 elements), +8 against bank conflicts
+  static constexpr int QS = DH + 8;
+  static constexpr int VS = H + 4;
+  static constexpr int US = CH + 8;
+  static constexpr int ACT_B = NT * AS * 2;
+  static constexpr int Q_B = HP * NT * QS * 2;
+  static constexpr int VT_B = HP * RPT * DH * VS * 2;
+  static constexpr int QKV_B = 2 * Q_B + VT_B;
+  static constexpr int U_B = NT * US * 2;
+  static constexpr int SCR_B = QKV_B > U_B ? QKV_B : U_B;
+  static constexpr int RED_B = 2 * 4 * NT * 4;
+  static constexpr int XT_B = NT * 16 * 4;              // latent tile, fp32, up to 16 action dims... see embed
+  static constexpr int LDS_B = ACT_B + SCR_B + RED_B;
+  static_assert(D % 64 == 0 && NT % 16 == 0 && H % 16 == 0 && NT % H == 0 && DH % 32 == 0, "shape");
+  static_assert((HEADS % HP) == 0 && (HP * 3 * DH) % 64 == 0 && CH % 64 == 0 && (4 * D) % CH == 0, "shape");
+};
+
+template <int D, int NT, int H, int HEADS, int CM, int CH>
+__global__ __launch_bounds__(256) void k_fused_forward(FusedNet net, FusedIO io, int A) {
+  using C = FusedCfg<D, NT, H, HEADS, CM, CH>;
+  constexpr int DH = C::DH, HP = C::HP, NB = C::NB, MBH = C::MBH, MBQ = C::MBQ, MBU = C::MBU, RPT = C::RPT,
+                NKF = C::NKF, AS = C::AS, QS = C::QS, VS = C::VS, US = C::US;
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  __bf16* act = reinterpret_cast<__bf16*>(lds);
+  __bf16* qbuf = reinterpret_cast<__bf16*>(lds + C::ACT_B);
+  __bf16* kbuf = qbuf + HP * NT * QS;
+  __bf16* vtb = kbuf + HP * NT * QS;
+  __bf16* ubuf = qbuf;
+  float* red1 = reinterpret_cast<float*>(lds + C::ACT_B + C::SCR_B);
+  float* red2 = red1 + 4 * NT;
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l16 = lane & 15, lg = lane >> 4;
+  const int R = io.d_R ? min(*io.d_R, io.R_cap) : io.R_cap;
+  const int row0 = blockIdx.x * RPT;
+  if (row0 >= R) return;
+  const long long tok0 = (long long)row0 * H;
+  const int ntok_live = min(NT, (R - row0) * H);
+
+  // ---- token embedding in fp32: h = tok_w x + tok_b + pos -------------------------------------------------
+  f32x4 h[MBH][NB];
+  {
+    float* xt = reinterpret_cast<float*>(qbuf);        // [NT][A] fp32 staging
+    for (int i = threadIdx.x; i < NT * A; i += 256)
+      xt[i] = i < ntok_live * A ? io.x_rows[tok0 * A + i] : 0.0f;
+    __syncthreads();
+#pragma unroll
+    for (int mb = 0; mb < MBH; ++mb) {
+      const int f0 = (wave * MBH + mb) * 16 + lg * 4;
+      const f32x4 tb = *reinterpret_cast<const f32x4*>(net.tok_b + f0);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const int t = nb * 16 + l16;
+        const f32x4 pe = *reinterpret_cast<const f32x4*>(net.pos + (t % H) * D + f0);
+        h[mb][nb] = tb + pe;
+      }
+      for (int a = 0; a < A; ++a) {
+        f32x4 wv;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) wv[i] = net.tok_w[(f0 + i) * A + a];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          const float xv = xt[(nb * 16 + l16) * A + a];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) h[mb][nb][i] = fmaf(xv, wv[i], h[mb][nb][i]);
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  const int mod_stride = net.L * 4 * D;
+  float mean[NB], rstd[NB];
+
+  // writes LN(h) (1 + g) + b as bf16 into act; which = 0 (attention) / 2 (MLP) selects the FiLM pair, -1 = none
+  auto write_ln = [&](int layer, int which) {
+    ln_stats<MBH, NB, D>(h, red1, red2, NT, wave, lane, mean, rstd);
+#pragma unroll
+    for (int mb = 0; mb < MBH; ++mb) {
+      const int f0 = (wave * MBH + mb) * 16 + lg * 4;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        f32x4 v = (h[mb][nb] - mean[nb]) * rstd[nb];
+        if (which >= 0) {
+          const int row = min(row0 + (nb * 16) / H, R - 1);
+          const float* mp = io.mod + (size_t)row * mod_stride + (size_t)layer * 4 * D + which * D + f0;
+          const f32x4 g = *reinterpret_cast<const f32x4*>(mp);
+          const f32x4 b = *reinterpret_cast<const f32x4*>(mp + D);
+          v = v * (1.0f + g) + b;
+        }
+        *reinterpret_cast<bf16x4*>(act + (nb * 16 + l16) * AS + f0) = to_bf16x4(v);
+      }
+    }
+    __syncthreads();
+  };
+
+  // softmax(q k^T) v for one (row, head) held in LDS; result overwrites the q rows of that (row, head)
+  auto self_attention = [&](int r, int hh) {
+    const __bf16* qp = qbuf + (hh * NT + r * H) * QS;
+    const __bf16* kp = kbuf + (hh * NT + r * H) * QS;
+    f32x4 s[NKF][NKF];                                  // [key frag][query frag], lane: query l16, keys lg*4..
+#pragma unroll
+    for (int kf = 0; kf < NKF; ++kf)
+#pragma unroll
+      for (int qf = 0; qf < NKF; ++qf) s[kf][qf] = f32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int ks = 0; ks < DH / 32; ++ks) {
+      bf16x8 ka[NKF], qb[NKF];
+#pragma unroll
+      for (int f = 0; f < NKF; ++f) {
+        ka[f] = *reinterpret_cast<const bf16x8*>(kp + (f * 16 + l16) * QS + ks * 32 + lg * 8);
+        qb[f] = *reinterpret_cast<const bf16x8*>(qp + (f * 16 + l16) * QS + ks * 32 + lg * 8);
+      }
+#pragma unroll
+      for (int kf = 0; kf < NKF; ++kf)
+#pragma unroll
+        for (int qf = 0; qf < NKF; ++qf)
+          s[kf][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kf], qb[qf], s[kf][qf], 0, 0, 0);
+    }
+    const float scale = rsqrtf((float)DH);
+    bf16x4 p[NKF][NKF];
+#pragma unroll
+    for (int qf = 0; qf < NKF; ++qf) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kf = 0; kf < NKF; ++kf)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { s[kf][qf][i] *= scale; mx = fmaxf(mx, s[kf][qf][i]); }
+      mx = fmaxf(mx, __shfl_xor(mx, 16)); mx = fmaxf(mx, __shfl_xor(mx, 32));
+      float sum = 0.0f;
+#pragma unroll
+      for (int kf = 0; kf < NKF; ++kf)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { s[kf][qf][i] = __expf(s[kf][qf][i] - mx); sum += s[kf][qf][i]; }
+      sum += __shfl_xor(sum, 16); sum += __shfl_xor(sum, 32);
+      const float inv = 1.0f / sum;
+#pragma unroll
+      for (int kf = 0; kf < NKF; ++kf) p[kf][qf] = to_bf16x4(s[kf][qf] * inv);
+    }
+    const __bf16* vp = vtb + (size_t)(hh * RPT + r) * DH * VS;
+    __bf16* op = qbuf + (hh * NT + r * H) * QS;
+#pragma unroll
+    for (int cf = 0; cf < DH / 16; ++cf) {
+      f32x4 o[NKF];
+#pragma unroll
+      for (int qf = 0; qf < NKF; ++qf) o[qf] = f32x4{0, 0, 0, 0};
+#pragma unroll
+      for (int kf = 0; kf < NKF; ++kf) {
+        const s16x4 va = *reinterpret_cast<const s16x4*>(vp + (cf * 16 + l16) * VS + kf * 16 + lg * 4);
+#pragma unroll
+        for (int qf = 0; qf < NKF; ++qf)
+          o[qf] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, __builtin_bit_cast(s16x4, p[kf][qf]), o[qf], 0, 0, 0);
+      }
+#pragma unroll
+      for (int qf = 0; qf < NKF; ++qf)
+        *reinterpret_cast<bf16x4*>(op + (qf * 16 + l16) * QS + cf * 16 + lg * 4) = to_bf16x4(o[qf]);
+    }
+  };
+
+  for (int layer = 0; layer < net.L; ++layer) {
+    const FusedLayer& W = net.layer[layer];
+    // ================= self-attention block =================
+    write_ln(layer, 0);
+    for (int g = 0; g < HEADS / HP; ++g) {
+      {
+        f32x4 acc[MBQ][NB];
+#pragma unroll
+        for (int mb = 0; mb < MBQ; ++mb)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
+        const int mf0 = g * (HP * 3 * DH / 16) + wave * MBQ;
+        gemm_frag<MBQ, NB>(W.qkv, D / 32, mf0, 0, D / 32, act, AS, acc, lane);
+        if (g > 0) __syncthreads();                     // previous group's O-projection has read qbuf
+#pragma unroll
+        for (int mb = 0; mb < MBQ; ++mb) {
+          const int lr = (wave * MBQ + mb) * 16;        // first logical row of this fragment inside the group
+          const int hh = lr / (3 * DH), cls = (lr / DH) % 3, c0 = lr % DH + lg * 4;
+          const f32x4 bias = *reinterpret_cast<const f32x4*>(W.qkv_b + g * (HP * 3 * DH) + lr + lg * 4);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) {
+            const f32x4 v = acc[mb][nb] + bias;
+            const int t = nb * 16 + l16;
+            if (cls == 0) {
+              *reinterpret_cast<bf16x4*>(qbuf + (hh * NT + t) * QS + c0) = to_bf16x4(v);
+            } else if (cls == 1) {
+              *reinterpret_cast<bf16x4*>(kbuf + (hh * NT + t) * QS + c0) = to_bf16x4(v);
+            } else {
+              __bf16* vp = vtb + ((size_t)(hh * RPT + t / H) * DH + c0) * VS + (t % H);
+#pragma unroll
+              for (int i = 0; i < 4; ++i) vp[i * VS] = (__bf16)v[i];
+            }
+          }
+        }
+      }
+      __syncthreads();
+      for (int task = wave; task < RPT * HP; task += 4) self_attention(task % RPT, task / RPT);
+      __syncthreads();
+#pragma unroll
+      for (int hh = 0; hh < HP; ++hh)
+        gemm_frag<MBH, NB>(W.o, D / 32, wave * MBH, (g * HP + hh) * DH / 32, DH / 32, qbuf + hh * NT * QS, QS, h, lane);
+    }
+#pragma unroll
+    for (int mb = 0; mb < MBH; ++mb) {
+      const f32x4 b = *reinterpret_cast<const f32x4*>(W.o_b + (wave * MBH + mb) * 16 + lg * 4);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) h[mb][nb] += b;
+    }
+    // ================= MLP block =================
+    write_ln(layer, 2);                                  // its barriers also order the O-projection reads before ubuf writes
+    for (int c = 0; c < 4 * D / CH; ++c) {
+      {
+        f32x4 acc[MBU][NB];
+#pragma unroll
+        for (int mb = 0; mb < MBU; ++mb)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
+        gemm_frag<MBU, NB>(W.up, D / 32, c * (CH / 16) + wave * MBU, 0, D / 32, act, AS, acc, lane);
+        if (c > 0) __syncthreads();                     // previous chunk's down-projection has read ubuf
+#pragma unroll
+        for (int mb = 0; mb < MBU; ++mb) {
+          const int f0 = (wave * MBU + mb) * 16 + lg * 4;
+          const f32x4 bias = *reinterpret_cast<const f32x4*>(W.up_b + c * CH + f0);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) {
+            f32x4 v = acc[mb][nb] + bias;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = gelu_fast(v[i]);
+            *reinterpret_cast<bf16x4*>(ubuf + (nb * 16 + l16) * US + f0) = to_bf16x4(v);
+          }
+        }
+      }
+      __syncthreads();
+      gemm_frag<MBH, NB>(W.dn, 4 * D / 32, wave * MBH, c * (CH / 32), CH / 32, ubuf, US, h, lane);
+    }
+#pragma unroll
+    for (int mb = 0; mb < MBH; ++mb) {
+      const f32x4 b = *reinterpret_cast<const f32x4*>(W.dn_b + (wave * MBH + mb) * 16 + lg * 4);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) h[mb][nb] += b;
+    }
+  }
+
+  // ---- output head: eps = head_w LN(h) + head_b ---------------------------------------------------------
+  write_ln(0, -1);
+  {
+    constexpr int NBW = (NB + 3) / 4;                   // token fragments per wave
+    f32x4 e[1][NBW];
+#pragma unroll
+    for (int j = 0; j < NBW; ++j) e[0][j] = f32x4{0, 0, 0, 0};
+    const int nb0 = wave * NBW;
+    if (nb0 < NB) {
+      gemm_frag<1, NBW>(net.head, D / 32, 0, 0, D / 32, act + nb0 * 16 * AS, AS, e, lane);
+#pragma unroll
+      for (int j = 0; j < NBW; ++j) {
+        const int t = (nb0 + j) * 16 + l16;
+        if (nb0 + j < NB && t < ntok_live) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int a = lg * 4 + i;
+            if (a < A) io.eps_out[(tok0 + t) * A + a] = e[0][j][i] + net.head_b[a];
+          }
+        }
+      }
+    }
+  }
+}
+
+}  // namespace tsdp

@@ -5,12 +5,14 @@
 #include <stdint.h>
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
 
 #include "../../include/tsdp.h"
 #include "kernels_f32.hpp"
+#include "fused_mfma.hpp"
 #include "round_kernels.hpp"
 
 using namespace tsdp;
@@ -35,6 +37,10 @@ struct Net {
   float* vc = nullptr;          // [L, B_max*S, d] cross-attention values (mode 1)
   bool loaded = false;
   const char* path = "f32-ops";
+  // fused bf16 MFMA path (bf16 networks of supported shape)
+  bool fused = false;
+  FusedNet fnet;
+  void (*fused_launch)(const FusedNet&, const FusedIO&, int A, int R_cap, hipStream_t) = nullptr;
 };
 
 }  // namespace
@@ -95,6 +101,59 @@ float bf16_round(float f) {
   return f;
 }
 
+
+uint16_t bf16_bits(float f) {
+  uint32_t b;
+  std::memcpy(&b, &f, 4);
+  b = (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+  return (uint16_t)b;
+}
+
+// Fragment order of a logical [rows, K] matrix for mfma 16x16x32 A operands: [rows/16][Kpad/32][64 lanes][8];
+// lane l of fragment (mf, ks) holds row mf*16 + l%16, columns ks*32 + (l/16)*8 .. +7.  src_row(lr) maps a
+// logical row to a row of W (or -1 for a zero row).
+template <typename RowMap>
+void pack_frags(std::vector<uint16_t>& out, const float* W, int K, int rows, RowMap src_row) {
+  const int mfs = (rows + 15) / 16, kss = (K + 31) / 32;
+  const size_t base = out.size();
+  out.resize(base + (size_t)mfs * kss * 64 * 8, 0);
+  for (int mf = 0; mf < mfs; ++mf)
+    for (int ks = 0; ks < kss; ++ks)
+      for (int l = 0; l < 64; ++l) {
+        const int lr = mf * 16 + (l & 15);
+        const int sr = lr < rows ? src_row(lr) : -1;
+        for (int i = 0; i < 8; ++i) {
+          const int col = ks * 32 + (l >> 4) * 8 + i;
+          if (sr >= 0 && col < K) out[base + (((size_t)mf * kss + ks) * 64 + l) * 8 + i] = bf16_bits(W[(size_t)sr * K + col]);
+        }
+      }
+}
+
+template <int D, int NT, int H, int HEADS, int CM, int CH>
+void launch_fused(const FusedNet& n, const FusedIO& io, int A, int R_cap, hipStream_t s) {
+  using C = FusedCfg<D, NT, H, HEADS, CM, CH>;
+  auto kern = k_fused_forward<D, NT, H, HEADS, CM, CH>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_B);
+    attr_set = true;
+  }
+  const int tiles = (R_cap + C::RPT - 1) / C::RPT;
+  hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), C::LDS_B, s, n, io, A);
+}
+
+typedef void (*fused_fn)(const FusedNet&, const FusedIO&, int, int, hipStream_t);
+
+// shapes with a compiled fused kernel: (D, H, HEADS, cond_mode) -> launcher
+fused_fn find_fused(int D, int H, int heads, int cm, int mlp_ratio, int L) {
+  if (mlp_ratio != 4 || L > FUSED_MAX_LAYERS) return nullptr;
+  if (cm == 0 && H == 16) {
+    if (D == 256 && heads == 4) return launch_fused<256, 128, 16, 4, 0, 256>;
+    if (D == 384 && heads == 6) return launch_fused<384, 128, 16, 6, 0, 128>;
+  }
+  return nullptr;
+}
+
 size_t layout_net(const tsdp_config& cf, int which, Net& n) {
   n.L = which == 0 ? cf.base_layers : cf.draft_layers;
   n.d = which == 0 ? cf.base_d : cf.draft_d;
@@ -124,6 +183,68 @@ size_t layout_net(const tsdp_config& cf, int which, Net& n) {
   n.head_w = take(A * d); n.head_b = take(A);
   n.n_floats = o;
   return o;
+}
+
+
+// Packs one network for the fused kernel (weights as bf16 MFMA fragments, q|k|v rows grouped per head
+// group) and fills n.fnet.  `w` is the host copy of the bf16-rounded canonical blob.
+int build_fused(tsdp_ctx* c, Net& n, const std::vector<float>& w, fused_fn fn) {
+  const tsdp_config& cf = c->cfg;
+  const int d = n.d, m = n.m, L = n.L, DH = d / n.heads, HP = DH >= 64 ? 1 : 64 / DH;
+  std::vector<uint16_t> pk;
+  std::vector<float> qb((size_t)L * 3 * d);
+  struct Off { size_t qkv, o, up, dn, cq, co; };
+  std::vector<Off> off(L);
+  auto ident = [](int r) { return r; };
+  for (int l = 0; l < L; ++l) {
+    const LayerOff& o = n.lay[l];
+    // logical row lr of the q|k|v matrix: groups of HP heads, inside a group per head [q(DH) k(DH) v(DH)]
+    auto qkv_row = [&](int lr) {
+      const int g = lr / (HP * 3 * DH), r = lr % (HP * 3 * DH);
+      const int head = g * HP + r / (3 * DH), cls = (r / DH) % 3, cdim = r % DH;
+      return cls * d + head * DH + cdim;
+    };
+    off[l].qkv = pk.size(); pack_frags(pk, &w[o.qkv_w], d, 3 * d, qkv_row);
+    for (int lr = 0; lr < 3 * d; ++lr) qb[(size_t)l * 3 * d + lr] = w[o.qkv_b + qkv_row(lr)];
+    off[l].o = pk.size(); pack_frags(pk, &w[o.o_w], d, d, ident);
+    off[l].up = pk.size(); pack_frags(pk, &w[o.up_w], d, m, ident);
+    off[l].dn = pk.size(); pack_frags(pk, &w[o.dn_w], m, d, ident);
+    if (cf.cond_mode == 1) {
+      off[l].cq = pk.size(); pack_frags(pk, &w[o.cq_w], d, d, ident);
+      off[l].co = pk.size(); pack_frags(pk, &w[o.co_w], d, d, ident);
+    }
+  }
+  const size_t head_off = pk.size();
+  pack_frags(pk, &w[n.head_w], d, 16, [&](int r) { return r < cf.A ? r : -1; });
+  uint16_t* dpk = nullptr;
+  float* dqb = nullptr;
+  int rc;
+  if ((rc = dev_alloc(c, &dpk, pk.size()))) return rc;
+  if ((rc = dev_alloc(c, &dqb, qb.size()))) return rc;
+  HIPCHK(c, hipMemcpy(dpk, pk.data(), pk.size() * sizeof(uint16_t), hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(dqb, qb.data(), qb.size() * sizeof(float), hipMemcpyHostToDevice));
+  FusedNet& f = n.fnet;
+  std::memset(&f, 0, sizeof(f));
+  f.L = L;
+  auto P = [&](size_t o) { return reinterpret_cast<const bf16x8*>(dpk + o); };
+  for (int l = 0; l < L; ++l) {
+    const LayerOff& o = n.lay[l];
+    FusedLayer& fl = f.layer[l];
+    fl.qkv = P(off[l].qkv); fl.o = P(off[l].o); fl.up = P(off[l].up); fl.dn = P(off[l].dn);
+    fl.qkv_b = dqb + (size_t)l * 3 * d;
+    fl.o_b = n.blob + o.o_b; fl.up_b = n.blob + o.up_b; fl.dn_b = n.blob + o.dn_b;
+    if (cf.cond_mode == 1) {
+      fl.cq = P(off[l].cq); fl.co = P(off[l].co);
+      fl.cq_b = n.blob + o.cq_b; fl.co_b = n.blob + o.co_b;
+    }
+  }
+  f.tok_w = n.blob + n.tok_w; f.tok_b = n.blob + n.tok_b; f.pos = n.blob + n.pos;
+  f.head = P(head_off); f.head_b = n.blob + n.head_b;
+  f.S = cf.cond_tokens;
+  n.fused = true;
+  n.fused_launch = fn;
+  n.path = "bf16-mfma-fused";
+  return TSDP_OK;
 }
 
 inline dim3 grid1(long long n, int bs) { return dim3((unsigned)((n + bs - 1) / bs)); }
@@ -175,6 +296,23 @@ void forward_f32(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int3
   hipLaunchKernelGGL(k_lnmod, lng, dim3(256), 0, s, c->h, (const float*)nullptr, (const float*)nullptr, 0, c->a, H, d,
                      d_R, R_cap);
   linear<0>(s, c->a, w + n.head_w, w + n.head_b, eps_out, R_cap, H, A, d, d_R);
+}
+
+// eps[R,H,A] = network(x_rows; t, cond): fused bf16 MFMA kernel where the shape has one, fp32 operators otherwise.
+void forward(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t* d_R, const int32_t* t_arr,
+             int t_sub, const int32_t* env_arr, float* eps_out, hipStream_t s) {
+  if (!n.fused) {
+    forward_f32(c, n, x_rows, R_cap, d_R, t_arr, t_sub, env_arr, eps_out, s);
+    return;
+  }
+  const tsdp_config& cf = c->cfg;
+  const int d = n.d;
+  hipLaunchKernelGGL(k_gvec, grid1((long long)R_cap * d, 256), dim3(256), 0, s, t_arr, t_sub, env_arr, n.temb,
+                     cf.cond_mode == 0 ? n.cemb : nullptr, c->sg, d, cf.T, d_R, R_cap);
+  linear<0>(s, c->sg, n.modw, n.modb, c->mod, R_cap, 1, n.L * 4 * d, d, d_R);
+  FusedIO io;
+  io.x_rows = x_rows; io.mod = c->mod; io.row_env = env_arr; io.d_R = d_R; io.R_cap = R_cap; io.eps_out = eps_out;
+  n.fused_launch(n.fnet, io, cf.A, R_cap, s);
 }
 
 int ensure_workspace(tsdp_ctx* c) {
@@ -355,6 +493,12 @@ int tsdp_load_weights(tsdp_ctx* c, int which, const float* h_blob, size_t nbytes
   HIPCHK(c, hipMemcpy(n.modb, modb.data(), modb.size() * sizeof(float), hipMemcpyHostToDevice));
   n.loaded = true;
   c->cond_set = false;
+  n.fused = false;
+  n.path = "f32-ops";
+  if (cf.dtype == 1 && !std::getenv("TSDP_DISABLE_FUSED")) {
+    fused_fn fn = find_fused(n.d, cf.H, n.heads, cf.cond_mode, n.m / n.d, n.L);
+    if (fn && (rc = build_fused(c, n, w, fn))) return rc;
+  }
   return TSDP_OK;
 }
 
@@ -403,7 +547,7 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
                      d_row_env, d_y_last, d_states, d_eps_p, d_xi);
   for (int k = 1; k <= cf.K_max; ++k) {
     // every environment runs the drafter at step k; the DDPM step masks those with K_eff < k
-    forward_f32(c, c->net[1], d_y_last, B, nullptr, d_t0, k - 1, nullptr, c->eps_tmp, s);
+    forward(c, c->net[1], d_y_last, B, nullptr, d_t0, k - 1, nullptr, c->eps_tmp, s);
     hipLaunchKernelGGL(k_draft_step, grid1((long long)B * (D / 4), 256), dim3(256), 0, s, k, (const float*)c->eps_tmp,
                        d_t0, (const int32_t*)c->K_eff, (const int32_t*)d_row_ptr, d_sigma_scale, d_env_id, c->tb,
                        cf.clip_x0, cf.clip_val, cf.seed, B, D, d_y_last, d_states, d_eps_p, d_xi);
@@ -422,7 +566,7 @@ int tsdp_verify(tsdp_ctx* c, int B, int R_cap, const int32_t* d_row_ptr, const i
     return fail(c, TSDP_E_SHAPE, "R_cap outside 0..B_max*K_max");
   if (B == 0 || R_cap == 0) return TSDP_OK;
   if ((rc = ensure_workspace(c))) return rc;
-  forward_f32(c, c->net[0], d_states, R_cap, d_row_ptr + B, d_row_t, 0, d_row_env, d_eps_q, (hipStream_t)stream);
+  forward(c, c->net[0], d_states, R_cap, d_row_ptr + B, d_row_t, 0, d_row_env, d_eps_q, (hipStream_t)stream);
   HIPCHK(c, hipGetLastError());
   return TSDP_OK;
 }
