@@ -40,7 +40,12 @@ struct Net {
   // fused bf16 MFMA path (bf16 networks of supported shape)
   bool fused = false;
   FusedNet fnet;
-  void (*fused_launch)(const FusedNet&, const FusedIO&, int A, int R_cap, hipStream_t) = nullptr;
+  void (*fused_verify)(const FusedNet&, const FusedIO&, int A, int R_cap, hipStream_t) = nullptr;
+  void (*fused_draft_small)(const FusedNet&, const DraftIO&, int A, hipStream_t) = nullptr;   // few environments per workgroup
+  void (*fused_draft_big)(const FusedNet&, const DraftIO&, int A, hipStream_t) = nullptr;     // many environments per workgroup
+  int draft_rpt_small = 0, draft_rpt_big = 0;
+  uint16_t* kc_pk = nullptr;    // fragment-ordered bf16 keys / transposed values of every (env, layer, head)
+  uint16_t* vct_pk = nullptr;
 };
 
 }  // namespace
@@ -129,10 +134,10 @@ void pack_frags(std::vector<uint16_t>& out, const float* W, int K, int rows, Row
       }
 }
 
-template <int D, int NT, int H, int HEADS, int CM, int CH>
-void launch_fused(const FusedNet& n, const FusedIO& io, int A, int R_cap, hipStream_t s) {
-  using C = FusedCfg<D, NT, H, HEADS, CM, CH>;
-  auto kern = k_fused_forward<D, NT, H, HEADS, CM, CH>;
+template <int D, int NT, int H, int HEADS, int CM, int CH, int SX>
+void launch_verify(const FusedNet& n, const FusedIO& io, int A, int R_cap, hipStream_t s) {
+  using C = FusedCfg<D, NT, H, HEADS, CM, CH, SX>;
+  auto kern = k_fused_forward<D, NT, H, HEADS, CM, CH, SX>;
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_B);
@@ -142,16 +147,46 @@ void launch_fused(const FusedNet& n, const FusedIO& io, int A, int R_cap, hipStr
   hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), C::LDS_B, s, n, io, A);
 }
 
-typedef void (*fused_fn)(const FusedNet&, const FusedIO&, int, int, hipStream_t);
-
-// shapes with a compiled fused kernel: (D, H, HEADS, cond_mode) -> launcher
-fused_fn find_fused(int D, int H, int heads, int cm, int mlp_ratio, int L) {
-  if (mlp_ratio != 4 || L > FUSED_MAX_LAYERS) return nullptr;
-  if (cm == 0 && H == 16) {
-    if (D == 256 && heads == 4) return launch_fused<256, 128, 16, 4, 0, 256>;
-    if (D == 384 && heads == 6) return launch_fused<384, 128, 16, 6, 0, 128>;
+template <int D, int NT, int H, int HEADS, int CM, int CH, int SX>
+void launch_draft(const FusedNet& n, const DraftIO& io, int A, hipStream_t s) {
+  using C = FusedCfg<D, NT, H, HEADS, CM, CH, SX>;
+  auto kern = k_fused_draft<D, NT, H, HEADS, CM, CH, SX>;
+  const int lds = C::LDS_B + 2 * NT * A * 4 + C::RPT * n.L * 4 * D * 4 + 16 * (D + 8) * 2;
+  static int attr_lds = 0;
+  if (lds > attr_lds) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    attr_lds = lds;
   }
-  return nullptr;
+  const int tiles = (io.B + C::RPT - 1) / C::RPT;
+  hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), lds, s, n, io, A);
+}
+
+struct FusedKernels {
+  void (*verify)(const FusedNet&, const FusedIO&, int, int, hipStream_t) = nullptr;
+  void (*draft_small)(const FusedNet&, const DraftIO&, int, hipStream_t) = nullptr;
+  void (*draft_big)(const FusedNet&, const DraftIO&, int, hipStream_t) = nullptr;
+  int rpt_small = 0, rpt_big = 0;
+};
+
+// shapes with compiled fused kernels
+bool find_fused(int D, int H, int heads, int cm, int S, int mlp_ratio, int L, FusedKernels& k) {
+  if (mlp_ratio != 4 || L > FUSED_MAX_LAYERS) return false;
+#define TSDP_SHAPE(D_, H_, HD_, CM_, SX_, NTV, CHV, NTS, NTB, CHD)                                   \
+  if (D == D_ && H == H_ && heads == HD_ && cm == CM_ && (CM_ == 0 || S == SX_)) {                 \
+    k.verify = launch_verify<D_, NTV, H_, HD_, CM_, CHV, SX_>;                                     \
+    k.draft_small = launch_draft<D_, NTS, H_, HD_, CM_, CHD, SX_>; k.rpt_small = NTS / H_;         \
+    k.draft_big = launch_draft<D_, NTB, H_, HD_, CM_, CHD, SX_>;   k.rpt_big = NTB / H_;           \
+    return true;                                                                                   \
+  }
+  //          D   H  heads cm  S  verify NT/CH  draft NT small/big, CH
+  TSDP_SHAPE(256, 16, 4, 0, 0, 128, 128, 16, 64, 128)
+  TSDP_SHAPE(384, 16, 6, 0, 0, 128, 128, 16, 64, 128)
+  TSDP_SHAPE(128, 16, 4, 0, 0, 128, 128, 16, 64, 128)
+  TSDP_SHAPE(192, 16, 6, 0, 0, 128, 128, 16, 64, 128)
+  TSDP_SHAPE(512, 32, 8, 1, 64, 64, 256, 32, 64, 128)
+  TSDP_SHAPE(256, 32, 8, 1, 64, 64, 256, 32, 64, 128)
+#undef TSDP_SHAPE
+  return false;
 }
 
 size_t layout_net(const tsdp_config& cf, int which, Net& n) {
@@ -188,7 +223,7 @@ size_t layout_net(const tsdp_config& cf, int which, Net& n) {
 
 // Packs one network for the fused kernel (weights as bf16 MFMA fragments, q|k|v rows grouped per head
 // group) and fills n.fnet.  `w` is the host copy of the bf16-rounded canonical blob.
-int build_fused(tsdp_ctx* c, Net& n, const std::vector<float>& w, fused_fn fn) {
+int build_fused(tsdp_ctx* c, Net& n, const std::vector<float>& w, const std::vector<float>& modw_cat, const FusedKernels& fk) {
   const tsdp_config& cf = c->cfg;
   const int d = n.d, m = n.m, L = n.L, DH = d / n.heads, HP = DH >= 64 ? 1 : 64 / DH;
   std::vector<uint16_t> pk;
@@ -216,6 +251,8 @@ int build_fused(tsdp_ctx* c, Net& n, const std::vector<float>& w, fused_fn fn) {
   }
   const size_t head_off = pk.size();
   pack_frags(pk, &w[n.head_w], d, 16, [&](int r) { return r < cf.A ? r : -1; });
+  const size_t mod_off = pk.size();
+  pack_frags(pk, modw_cat.data(), d, L * 4 * d, ident);
   uint16_t* dpk = nullptr;
   float* dqb = nullptr;
   int rc;
@@ -240,9 +277,18 @@ int build_fused(tsdp_ctx* c, Net& n, const std::vector<float>& w, fused_fn fn) {
   }
   f.tok_w = n.blob + n.tok_w; f.tok_b = n.blob + n.tok_b; f.pos = n.blob + n.pos;
   f.head = P(head_off); f.head_b = n.blob + n.head_b;
-  f.S = cf.cond_tokens;
+  f.modw = P(mod_off); f.modb = n.modb; f.temb = n.temb; f.cemb = cf.cond_mode == 0 ? n.cemb : nullptr;
+  if (cf.cond_mode == 1) {
+    const size_t S = cf.cond_tokens, cnt = (size_t)cf.B_max * L * S * d;
+    if ((rc = dev_alloc(c, &n.kc_pk, cnt))) return rc;
+    if ((rc = dev_alloc(c, &n.vct_pk, cnt))) return rc;
+    f.kc = reinterpret_cast<const bf16x8*>(n.kc_pk);
+    f.vct = reinterpret_cast<const bf16x4*>(n.vct_pk);
+  }
   n.fused = true;
-  n.fused_launch = fn;
+  n.fused_verify = fk.verify;
+  n.fused_draft_small = fk.draft_small; n.fused_draft_big = fk.draft_big;
+  n.draft_rpt_small = fk.rpt_small; n.draft_rpt_big = fk.rpt_big;
   n.path = "bf16-mfma-fused";
   return TSDP_OK;
 }
@@ -312,7 +358,15 @@ void forward(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t*
   linear<0>(s, c->sg, n.modw, n.modb, c->mod, R_cap, 1, n.L * 4 * d, d, d_R);
   FusedIO io;
   io.x_rows = x_rows; io.mod = c->mod; io.row_env = env_arr; io.d_R = d_R; io.R_cap = R_cap; io.eps_out = eps_out;
-  n.fused_launch(n.fnet, io, cf.A, R_cap, s);
+  n.fused_verify(n.fnet, io, cf.A, R_cap, s);
+}
+
+// dynamic LDS of the persistent drafter kernel for `rpt` environments per workgroup (mirrors launch_draft)
+size_t fused_draft_lds(const Net& n, const tsdp_config& cf, int rpt) {
+  const size_t D = n.d, NT = (size_t)rpt * cf.H, DH = D / n.heads, HP = DH >= 64 ? 1 : 64 / DH, CH = 128;
+  const size_t act = NT * (D + 8) * 2, q = HP * NT * (DH + 8) * 2, vt = HP * rpt * DH * (cf.H + 4) * 2;
+  const size_t scr = std::max(std::max(2 * q + vt, NT * (CH + 8) * 2), NT * 64 * 4);
+  return act + scr + 2 * 4 * NT * 4 + 2 * NT * cf.A * 4 + (size_t)rpt * n.L * 4 * D * 4 + 16 * (D + 8) * 2;
 }
 
 int ensure_workspace(tsdp_ctx* c) {
@@ -496,8 +550,10 @@ int tsdp_load_weights(tsdp_ctx* c, int which, const float* h_blob, size_t nbytes
   n.fused = false;
   n.path = "f32-ops";
   if (cf.dtype == 1 && !std::getenv("TSDP_DISABLE_FUSED")) {
-    fused_fn fn = find_fused(n.d, cf.H, n.heads, cf.cond_mode, n.m / n.d, n.L);
-    if (fn && (rc = build_fused(c, n, w, fn))) return rc;
+    FusedKernels fk;
+    if (find_fused(n.d, cf.H, n.heads, cf.cond_mode, cf.cond_tokens, n.m / n.d, n.L, fk) &&
+        (rc = build_fused(c, n, w, modw, fk)))
+      return rc;
   }
   return TSDP_OK;
 }
@@ -520,6 +576,13 @@ int tsdp_set_cond(tsdp_ctx* c, const float* d_cond, int B, void* stream) {
       for (int l = 0; l < n.L; ++l) {
         linear<0>(s, d_cond, w + n.lay[l].ck_w, w + n.lay[l].ck_b, n.kc + l * per_layer, B * S, 1, n.d, cf.cond_dim, nullptr);
         linear<0>(s, d_cond, w + n.lay[l].cv_w, w + n.lay[l].cv_b, n.vc + l * per_layer, B * S, 1, n.d, cf.cond_dim, nullptr);
+        if (n.fused) {
+          const long long cnt = (long long)B * S * n.d / 8;
+          hipLaunchKernelGGL(k_pack_kc, grid1(cnt, 256), dim3(256), 0, s, (const float*)(n.kc + l * per_layer),
+                             reinterpret_cast<__bf16*>(n.kc_pk), B, S, n.d, n.heads, n.L, l);
+          hipLaunchKernelGGL(k_pack_vct, grid1(2 * cnt, 256), dim3(256), 0, s, (const float*)(n.vc + l * per_layer),
+                             reinterpret_cast<__bf16*>(n.vct_pk), B, S, n.d, n.heads, n.L, l);
+        }
       }
     }
   }
@@ -545,6 +608,24 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
   hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, d_t0, d_K, B, cf.K_max, cf.T, c->K_eff, d_row_ptr, c->status);
   hipLaunchKernelGGL(k_rows, dim3(B), dim3(128), 0, s, d_x, d_t0, (const int32_t*)d_row_ptr, cf.T, D, d_row_t,
                      d_row_env, d_y_last, d_states, d_eps_p, d_xi);
+  Net& dn = c->net[1];
+  if (dn.fused) {
+    // persistent drafter kernel: pick the tile (environments per workgroup) that fills the chip best
+    const bool big = (B + dn.draft_rpt_big - 1) / dn.draft_rpt_big >= 192;
+    const int rpt = big ? dn.draft_rpt_big : dn.draft_rpt_small;
+    const size_t lds = fused_draft_lds(dn, cf, rpt);
+    if (lds <= 160 * 1024) {
+      DraftIO io;
+      io.B = B; io.t0 = d_t0; io.K_eff = c->K_eff; io.row_ptr = d_row_ptr; io.sigma_scale = d_sigma_scale;
+      io.env_id = d_env_id;
+      io.tb = {c->tb.sqrt_abar, c->tb.sqrt_1m, c->tb.c0, c->tb.cx, c->tb.sigma, c->tb.T};
+      io.clip = cf.clip_x0; io.clip_val = cf.clip_val; io.seed = cf.seed;
+      io.y = d_y_last; io.states = d_states; io.eps_p = d_eps_p; io.xi = d_xi;
+      (big ? dn.fused_draft_big : dn.fused_draft_small)(dn.fnet, io, cf.A, s);
+      HIPCHK(c, hipGetLastError());
+      return TSDP_OK;
+    }
+  }
   for (int k = 1; k <= cf.K_max; ++k) {
     // every environment runs the drafter at step k; the DDPM step masks those with K_eff < k
     forward(c, c->net[1], d_y_last, B, nullptr, d_t0, k - 1, nullptr, c->eps_tmp, s);
