@@ -84,41 +84,57 @@ __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
   return r;
 }
 
-// acc[mb][nb] += W(frag rows mf0+mb, k-steps ks0..ks0+nks) . act^T ; act is LDS bf16 [token][stride]
-template <int MB, int NB>
-__device__ __forceinline__ void gemm_frag(const bf16x8* __restrict__ wp, int ks_total, int mf0, int ks0, int nks,
+#ifndef TSDP_ABL
+#define TSDP_ABL 0
+#endif
+#ifndef TSDP_INFLIGHT_CLK
+#define TSDP_INFLIGHT_CLK 512
+#endif
+// acc[mb][nb] += W(frag rows mf0+mb, k-steps ks0..ks0+NKS) . act^T ; act is LDS bf16 [token][stride].
+// Fully unrolled with compile-time trip counts.  The weight fragments of k-step k+PF are requested from L2
+// before the MFMAs of k-step k issue, and the LDS operands of k-step k+1 are read while those of k-step k
+// are multiplied; scheduling barriers keep the compiler from collapsing that software pipeline, and with no
+// branch inside, the hardware wait counters stay exact.  PF is sized so that about TSDP_INFLIGHT_CLK cycles
+// of MFMA work separate a request from its use (one L2 round trip) without flooding the 32 KB vector L1.
+template <int MB, int NB, int NKS>
+__device__ __forceinline__ void gemm_frag(const bf16x8* __restrict__ wp, int ks_total, int mf0, int ks0,
                                           const __bf16* act, int stride, f32x4 (&acc)[MB][NB], int lane) {
-  constexpr int PF = 2;                               // k-steps of weights in flight ahead of the MFMAs
+  constexpr int STEP_CLK = MB * NB * 16;              // MFMA cycles of one k-step
+  constexpr int PFW = (TSDP_INFLIGHT_CLK + STEP_CLK - 1) / STEP_CLK;
+  constexpr int PF0 = PFW < 1 ? 1 : (PFW > 4 ? 4 : PFW);
+  constexpr int PF = PF0 > NKS ? NKS : PF0;
   const bf16x8* wl = wp + ((size_t)mf0 * ks_total + ks0) * 64 + lane;
   const __bf16* al = act + (lane & 15) * stride + (lane >> 4) * 8;
   bf16x8 a[PF + 1][MB];
+  bf16x8 b[2][NB];
 #pragma unroll
   for (int p = 0; p < PF; ++p)
-    if (p < nks) {
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) a[p][mb] = wl[((size_t)mb * ks_total + p) * 64];
+    for (int mb = 0; mb < MB; ++mb) a[p][mb] = wl[((size_t)mb * ks_total + p) * 64];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) b[0][nb] = *reinterpret_cast<const bf16x8*>(al + nb * 16 * stride);
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int k = 0; k < NKS; ++k) {
+    if (k + PF < NKS) {
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+        a[(k + PF) % (PF + 1)][mb] = (TSDP_ABL & 1) ? a[0][mb] : wl[((size_t)mb * ks_total + k + PF) * 64];
     }
-#pragma unroll 1
-  for (int ks = 0; ks < nks; ks += PF + 1) {
+    if (k + 1 < NKS) {
 #pragma unroll
-    for (int u = 0; u < PF + 1; ++u) {
-      const int k = ks + u;
-      if (k < nks) {
-        const int slot_n = (u + PF) % (PF + 1);
-        if (k + PF < nks) {
-#pragma unroll
-          for (int mb = 0; mb < MB; ++mb) a[slot_n][mb] = wl[((size_t)mb * ks_total + k + PF) * 64];
-        }
-        bf16x8 b[NB];
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) b[nb] = *reinterpret_cast<const bf16x8*>(al + nb * 16 * stride + k * 32);
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-          for (int nb = 0; nb < NB; ++nb)
-            acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u][mb], b[nb], acc[mb][nb], 0, 0, 0);
-      }
+      for (int nb = 0; nb < NB; ++nb)
+        b[(k + 1) & 1][nb] = (TSDP_ABL & 2) ? b[0][nb] : *reinterpret_cast<const bf16x8*>(al + nb * 16 * stride + (k + 1) * 32);
     }
+    __builtin_amdgcn_sched_barrier(0);
+    if (!(TSDP_ABL & 4)) {
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+          acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[k % (PF + 1)][mb], b[k & 1][nb], acc[mb][nb], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
   }
 }
 
@@ -387,7 +403,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
         const int mf0 = g * (HP * 3 * DH / 16) + wave * MBQ;
-        gemm_frag<MBQ, NB>(W.qkv, D / 32, mf0, 0, D / 32, act, AS, acc, lane);
+        gemm_frag<MBQ, NB, D / 32>(W.qkv, D / 32, mf0, 0, act, AS, acc, lane);
         if (g > 0) __syncthreads();                     // previous group's O-projection has read qbuf
 #pragma unroll
         for (int mb = 0; mb < MBQ; ++mb) {
@@ -411,11 +427,11 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         }
       }
       __syncthreads();
-      for (int task = wave; task < RPT * HP; task += 4) self_attention(task % RPT, task / RPT);
+      if (!(TSDP_ABL & 8)) for (int task = wave; task < RPT * HP; task += 4) self_attention(task % RPT, task / RPT);
       __syncthreads();
 #pragma unroll
       for (int hh = 0; hh < HP; ++hh)
-        gemm_frag<MBH, NB>(W.o, D / 32, wave * MBH, (g * HP + hh) * DH / 32, DH / 32, qbuf + hh * NT * QS, QS, h, lane);
+        gemm_frag<MBH, NB, DH / 32>(W.o, D / 32, wave * MBH, (g * HP + hh) * DH / 32, qbuf + hh * NT * QS, QS, h, lane);
     }
     add_bias_h(W.o_b);
     // ================= cross-attention block (observation tokens) =================
@@ -426,7 +442,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
           f32x4 acc[1][NB];
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) acc[0][nb] = f32x4{0, 0, 0, 0};
-          gemm_frag<1, NB>(W.cq, D / 32, g * (HP * DH / 16) + wave, 0, D / 32, act, AS, acc, lane);
+          gemm_frag<1, NB, D / 32>(W.cq, D / 32, g * (HP * DH / 16) + wave, 0, act, AS, acc, lane);
           if (g > 0) __syncthreads();
           const int lr = wave * 16, hh = lr / DH, c0 = lr % DH + lg * 4;
           const f32x4 bias = *reinterpret_cast<const f32x4*>(W.cq_b + g * (HP * DH) + lr + lg * 4);
@@ -435,11 +451,11 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
             *reinterpret_cast<bf16x4*>(qbuf + (hh * NT + nb * 16 + l16) * QS + c0) = to_bf16x4(acc[0][nb] + bias);
         }
         __syncthreads();
-        for (int task = wave; task < RPT * HP; task += 4) cross_attention(task % RPT, task / RPT, layer, g * HP + task / RPT);
+        if (!(TSDP_ABL & 8)) for (int task = wave; task < RPT * HP; task += 4) cross_attention(task % RPT, task / RPT, layer, g * HP + task / RPT);
         __syncthreads();
 #pragma unroll
         for (int hh = 0; hh < HP; ++hh)
-          gemm_frag<MBH, NB>(W.co, D / 32, wave * MBH, (g * HP + hh) * DH / 32, DH / 32, qbuf + hh * NT * QS, QS, h, lane);
+          gemm_frag<MBH, NB, DH / 32>(W.co, D / 32, wave * MBH, (g * HP + hh) * DH / 32, qbuf + hh * NT * QS, QS, h, lane);
       }
       add_bias_h(W.co_b);
     }
@@ -452,7 +468,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         for (int mb = 0; mb < MBU; ++mb)
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
-        gemm_frag<MBU, NB>(W.up, D / 32, c * (CH / 16) + wave * MBU, 0, D / 32, act, AS, acc, lane);
+        gemm_frag<MBU, NB, D / 32>(W.up, D / 32, c * (CH / 16) + wave * MBU, 0, act, AS, acc, lane);
         if (c > 0) __syncthreads();                     // previous chunk's down-projection has read ubuf
 #pragma unroll
         for (int mb = 0; mb < MBU; ++mb) {
@@ -462,13 +478,13 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
           for (int nb = 0; nb < NB; ++nb) {
             f32x4 v = acc[mb][nb] + bias;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) v[i] = gelu_fast(v[i]);
+            for (int i = 0; i < 4; ++i) v[i] = (TSDP_ABL & 16) ? v[i] : gelu_fast(v[i]);
             *reinterpret_cast<bf16x4*>(ubuf + (nb * 16 + l16) * US + f0) = to_bf16x4(v);
           }
         }
       }
       __syncthreads();
-      gemm_frag<MBH, NB>(W.dn, 4 * D / 32, wave * MBH, c * (CH / 32), CH / 32, ubuf, US, h, lane);
+      gemm_frag<MBH, NB, CH / 32>(W.dn, 4 * D / 32, wave * MBH, c * (CH / 32), ubuf, US, h, lane);
     }
     add_bias_h(W.dn_b);
   }
@@ -482,7 +498,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
     for (int j = 0; j < NBW; ++j) e[0][j] = f32x4{0, 0, 0, 0};
     const int nb0 = wave * NBW;
     if (nb0 < NB) {
-      gemm_frag<1, NBW>(net.head, D / 32, 0, 0, D / 32, act + nb0 * 16 * AS, AS, e, lane);
+      gemm_frag<1, NBW, D / 32>(net.head, D / 32, 0, 0, act + nb0 * 16 * AS, AS, e, lane);
 #pragma unroll
       for (int j = 0; j < NBW; ++j) {
         const int t = (nb0 + j) * 16 + l16;
@@ -500,7 +516,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
 
 // Batched verification: tile b of the grid takes rows b*RPT .. of the ragged batch.
 template <int D, int NT, int H, int HEADS, int CM, int CH, int SX>
-__global__ __launch_bounds__(256) void k_fused_forward(FusedNet net, FusedIO io, int A) {
+__global__ __launch_bounds__(256, (FusedCfg<D, NT, H, HEADS, CM, CH, SX>::LDS_B <= 80 * 1024 ? 2 : 1)) void k_fused_forward(FusedNet net, FusedIO io, int A) {
   using C = FusedCfg<D, NT, H, HEADS, CM, CH, SX>;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   __shared__ int32_t envs[C::RPT];
@@ -578,7 +594,7 @@ __global__ __launch_bounds__(256) void k_fused_draft(FusedNet net, DraftIO io, i
         f32x4 acc[MBM][1];
 #pragma unroll
         for (int mb = 0; mb < MBM; ++mb) acc[mb][0] = f32x4{0, 0, 0, 0};
-        gemm_frag<MBM, 1>(net.modw, D / 32, wave * fpw + f, 0, D / 32, sgbuf, D + 8, acc, lane);
+        gemm_frag<MBM, 1, D / 32>(net.modw, D / 32, wave * fpw + f, 0, sgbuf, D + 8, acc, lane);
         if (l16 < RPT) {
 #pragma unroll
           for (int mb = 0; mb < MBM; ++mb) {

@@ -179,8 +179,8 @@ bool find_fused(int D, int H, int heads, int cm, int S, int mlp_ratio, int L, Fu
     return true;                                                                                   \
   }
   //          D   H  heads cm  S  verify NT/CH  draft NT small/big, CH
-  TSDP_SHAPE(256, 16, 4, 0, 0, 128, 128, 16, 64, 128)
-  TSDP_SHAPE(384, 16, 6, 0, 0, 128, 128, 16, 64, 128)
+  TSDP_SHAPE(256, 16, 4, 0, 0, 64, 128, 16, 64, 128)
+  TSDP_SHAPE(384, 16, 6, 0, 0, 64, 128, 16, 64, 128)
   TSDP_SHAPE(128, 16, 4, 0, 0, 128, 128, 16, 64, 128)
   TSDP_SHAPE(192, 16, 6, 0, 0, 128, 128, 16, 64, 128)
   TSDP_SHAPE(512, 32, 8, 1, 64, 64, 256, 32, 64, 128)
