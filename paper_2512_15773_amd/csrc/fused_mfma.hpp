@@ -51,6 +51,7 @@ struct FusedNet {
   // cross-attention operands of every (env, layer, head), prepared by tsdp_set_cond:
   const bf16x8* kc;            // [B][L][HEADS][S/16][DH/32][64]  keys as 16x16x32 A fragments
   const bf16x4* vct;           // [B][L][HEADS][DH/16][S/16][64]  values transposed as 16x16x16 A fragments
+  long long* trace;            // tuning builds only: per-wave phase cycle totals of one workgroup, else null
 };
 
 struct FusedIO {               // batched verification
@@ -74,8 +75,10 @@ struct DraftIO {               // drafter rollout
 
 __device__ __forceinline__ float gelu_fast(float x) {
   // x * sigmoid(2 sqrt(2/pi) (x + 0.044715 x^3)) == tanh form of GELU
-  const float u = 1.5957691216057308f * (x + 0.044715f * x * x * x);
-  return x / (1.0f + __expf(-u));
+  // exp(-u) as 2^(-u log2 e) and an approximate reciprocal: one v_exp_f32 and one v_rcp_f32 per element
+  const float x2 = x * x;
+  const float w = x * fmaf(x2, -0.044715f * 1.5957691216057308f * 1.4426950408889634f, -1.5957691216057308f * 1.4426950408889634f);
+  return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(w));
 }
 
 __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
@@ -87,68 +90,97 @@ __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
 #ifndef TSDP_ABL
 #define TSDP_ABL 0
 #endif
-#ifndef TSDP_INFLIGHT_CLK
-#define TSDP_INFLIGHT_CLK 512
+// Optional phase timing for tuning builds (-DTSDP_TRACE): per-wave cycle totals per phase category.
+#ifdef TSDP_TRACE
+#define TSDP_TICK(cat) { const long long now_ = clock64(); tacc_[cat] += now_ - tprev_; tprev_ = now_; }
+#else
+#define TSDP_TICK(cat)
 #endif
-// acc[mb][nb] += W(frag rows mf0+mb, k-steps ks0..ks0+NKS) . act^T ; act is LDS bf16 [token][stride].
-// Fully unrolled with compile-time trip counts.  The weight fragments of k-step k+PF are requested from L2
-// before the MFMAs of k-step k issue, and the LDS operands of k-step k+1 are read while those of k-step k
-// are multiplied; scheduling barriers keep the compiler from collapsing that software pipeline, and with no
-// branch inside, the hardware wait counters stay exact.  PF is sized so that about TSDP_INFLIGHT_CLK cycles
-// of MFMA work separate a request from its use (one L2 round trip) without flooding the 32 KB vector L1.
-template <int MB, int NB, int NKS>
-__device__ __forceinline__ void gemm_frag(const bf16x8* __restrict__ wp, int ks_total, int mf0, int ks0,
-                                          const __bf16* act, int stride, f32x4 (&acc)[MB][NB], int lane) {
-  constexpr int STEP_CLK = MB * NB * 16;              // MFMA cycles of one k-step
-  constexpr int PFW = (TSDP_INFLIGHT_CLK + STEP_CLK - 1) / STEP_CLK;
-  constexpr int PF0 = PFW < 1 ? 1 : (PFW > 4 ? 4 : PFW);
-  constexpr int PF = PF0 > NKS ? NKS : PF0;
-  const bf16x8* wl = wp + ((size_t)mf0 * ks_total + ks0) * 64 + lane;
-  const __bf16* al = act + (lane & 15) * stride + (lane >> 4) * 8;
+#ifndef TSDP_INFLIGHT_CLK
+#define TSDP_INFLIGHT_CLK 384
+#endif
+#ifndef TSDP_PFMAX
+#define TSDP_PFMAX 4
+#endif
+
+// Weight-streaming GEMM on fragments:  acc[mb][nb] += W(frag rows mf0+mb, k-steps ks0..ks0+NKS) . act^T,
+// act = LDS bf16 [token][stride].  Fully unrolled with compile-time trip counts.  The weight fragments of
+// k-step k+PF are requested from L2 before the MFMAs of k-step k issue and the LDS operands of k-step k+1
+// are read while those of k-step k are multiplied; scheduling barriers keep the compiler from collapsing
+// that software pipeline, and with no branch inside, the hardware wait counters stay exact.  PF is sized so
+// that about TSDP_INFLIGHT_CLK cycles of MFMA work separate a request from its use (one L2 round trip)
+// without flooding the small vector L1.  issue() requests k-step 0 only and may be called a whole phase
+// early (before an epilogue, a barrier or the attention of the previous phase); run() does the rest.
+template <int MB, int NB, int NKS, int BD = 2>
+struct FragGemm {
+  static constexpr int STEP_CLK = MB * NB * 16;
+  static constexpr int PFW = (TSDP_INFLIGHT_CLK + STEP_CLK - 1) / STEP_CLK;
+  static constexpr int PF0 = PFW < 1 ? 1 : (PFW > TSDP_PFMAX ? TSDP_PFMAX : PFW);
+  static constexpr int PF = PF0 > NKS ? NKS : PF0;
   bf16x8 a[PF + 1][MB];
-  bf16x8 b[2][NB];
+  const bf16x8* wl;
+  int kst;                     // elements between the fragment rows of consecutive mb (in k-steps)
+
+  // fragment row of index mb is mf0 + mb*mfs
+  __device__ __forceinline__ void issue(const bf16x8* __restrict__ wp, int ks_total, int mf0, int ks0, int lane, int mfs = 1) {
+    wl = wp + ((size_t)mf0 * ks_total + ks0) * 64 + lane;
+    kst = ks_total * mfs;
 #pragma unroll
-  for (int p = 0; p < PF; ++p)
+    for (int mb = 0; mb < MB; ++mb) a[0][mb] = wl[(size_t)mb * kst * 64];
+  }
+
+  __device__ __forceinline__ void run(const __bf16* act, int stride, f32x4 (&acc)[MB][NB], int lane) {
+    const __bf16* al = act + (lane & 15) * stride + (lane >> 4) * 8;
+    bf16x8 b[BD][NB];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) a[p][mb] = wl[((size_t)mb * ks_total + p) * 64];
+    for (int p = 1; p < PF; ++p)
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) b[0][nb] = *reinterpret_cast<const bf16x8*>(al + nb * 16 * stride);
-  __builtin_amdgcn_sched_barrier(0);
+      for (int mb = 0; mb < MB; ++mb) a[p][mb] = wl[((size_t)mb * kst + p) * 64];
 #pragma unroll
-  for (int k = 0; k < NKS; ++k) {
-    if (k + PF < NKS) {
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
-        a[(k + PF) % (PF + 1)][mb] = (TSDP_ABL & 1) ? a[0][mb] : wl[((size_t)mb * ks_total + k + PF) * 64];
-    }
-    if (k + 1 < NKS) {
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-        b[(k + 1) & 1][nb] = (TSDP_ABL & 2) ? b[0][nb] : *reinterpret_cast<const bf16x8*>(al + nb * 16 * stride + (k + 1) * 32);
-    }
+    for (int nb = 0; nb < NB; ++nb) b[0][nb] = *reinterpret_cast<const bf16x8*>(al + nb * 16 * stride);
     __builtin_amdgcn_sched_barrier(0);
-    if (!(TSDP_ABL & 4)) {
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
+    for (int k = 0; k < NKS; ++k) {
+      if (k + PF < NKS) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+          a[(k + PF) % (PF + 1)][mb] = (TSDP_ABL & 1) ? a[0][mb] : wl[((size_t)mb * kst + k + PF) * 64];
+      }
+      if (BD == 2 && k + 1 < NKS) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
-          acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[k % (PF + 1)][mb], b[k & 1][nb], acc[mb][nb], 0, 0, 0);
+          b[(k + 1) & 1][nb] = (TSDP_ABL & 2) ? b[0][nb] : *reinterpret_cast<const bf16x8*>(al + nb * 16 * stride + (k + 1) * 32);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (!(TSDP_ABL & 4)) {
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+            acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[k % (PF + 1)][mb], b[k % BD][nb], acc[mb][nb], 0, 0, 0);
+      }
+      if (BD == 1 && k + 1 < NKS) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) b[0][nb] = *reinterpret_cast<const bf16x8*>(al + nb * 16 * stride + (k + 1) * 32);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_sched_barrier(0);
   }
-}
+};
 
 // D model width, NT tokens per workgroup, H tokens per row, HEADS attention heads, CM conditioning mode,
-// CH hidden-chunk width of the MLP, SX observation tokens (cross-attention).  256 threads = 4 wavefronts,
-// each owning D/4 residual features of every token of the tile.
-template <int D, int NT, int H, int HEADS, int CM, int CH, int SX>
+// CH hidden-chunk width of the MLP, SX observation tokens (cross-attention), HP heads per attention phase,
+// NW wavefronts per workgroup; every wavefront owns D/NW residual features of every token of the tile.
+template <int D_, int NT_, int H_, int HEADS_, int CM_, int CH_, int SX_, int HP_, int NW_>
 struct FusedCfg {
+  static constexpr int D = D_, NT = NT_, H = H_, HEADS = HEADS_, CM = CM_, CH = CH_, SX = SX_, HP = HP_, NW = NW_;
+  static constexpr int THREADS = NW * 64;
   static constexpr int DH = D / HEADS;
-  static constexpr int HP = DH >= 64 ? 1 : 64 / DH;     // heads per attention phase (64 features per phase)
   static constexpr int NB = NT / 16;                    // token fragments
-  static constexpr int MBH = D / 64;                    // residual feature fragments per wave
-  static constexpr int MBQ = HP * 3 * DH / 64;          // q|k|v feature fragments per wave and phase
-  static constexpr int MBU = CH / 64;
+  static constexpr int MBH = D / 16 / NW;               // residual feature fragments per wave
+  static constexpr int MBQ = HP * 3 * DH / 16 / NW;     // q|k|v feature fragments per wave and phase
+  static constexpr int MBC = HP * DH / 16 / NW;         // cross-attention query fragments per wave and phase
+  static constexpr int MBU = CH / 16 / NW;
   static constexpr int RPT = NT / H;                    // rows per tile
   static constexpr int NKF = H / 16;                    // key / query fragments of self-attention
   static constexpr int SF = SX / 16;                    // key fragments of cross-attention
@@ -164,10 +196,22 @@ struct FusedCfg {
   static constexpr int XT_B = NT * 64 * 4;              // fp32 latent staging of the verify kernel (A <= 64)
   static constexpr int SCR0_B = QKV_B > U_B ? QKV_B : U_B;
   static constexpr int SCR_B = SCR0_B > XT_B ? SCR0_B : XT_B;
-  static constexpr int RED_B = 2 * 4 * NT * 4;
+  static constexpr int RED_B = 2 * NW * NT * 4;
   static constexpr int LDS_B = ACT_B + SCR_B + RED_B;   // body; the drafter kernel appends its own regions
-  static_assert(D % 64 == 0 && NT % 16 == 0 && H % 16 == 0 && NT % H == 0 && DH % 32 == 0, "shape");
-  static_assert((HEADS % HP) == 0 && (HP * 3 * DH) % 64 == 0 && CH % 64 == 0 && (4 * D) % CH == 0, "shape");
+  static constexpr int WG_PER_CU = LDS_B <= 80 * 1024 && NW == 4 ? 2 : 1;
+#ifdef TSDP_FORCE_BD
+  static constexpr int BD = TSDP_FORCE_BD;
+#else
+  static constexpr int BD = WG_PER_CU == 2 ? 1 : 2;     // LDS operand buffers: the second workgroup hides LDS latency
+#endif
+#ifdef TSDP_FORCE_XPF
+  static constexpr bool XPF = TSDP_FORCE_XPF;
+#else
+  static constexpr bool XPF = WG_PER_CU == 1;           // request the first weight fragments of a phase one phase early
+#endif
+  static_assert(D % (16 * NW) == 0 && NT % 16 == 0 && H % 16 == 0 && NT % H == 0 && DH % 32 == 0, "shape");
+  static_assert((HEADS % HP) == 0 && (HP * 3 * DH) % (16 * NW) == 0 && (HP * DH) % (16 * NW) == 0, "shape");
+  static_assert(CH % (16 * NW) == 0 && (4 * D) % CH == 0, "shape");
   static_assert(CM == 0 || (SX % 16 == 0 && SX >= 16), "observation tokens must be a multiple of 16");
 };
 
@@ -175,24 +219,40 @@ struct FusedCfg {
 // consumed before the first barrier-protected write).  modp: FiLM vectors of local row r at
 // modp + min(r, mod_rows-1)*mod_stride (global or LDS).  env_of_row: environment of local row r (cross-attention).
 // eps is written to eo[t*A + a] for local tokens t < ntok_live.
-template <int D, int NT, int H, int HEADS, int CM, int CH, int SX>
+template <class C>
 __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* lds, const float* xt, int A,
                                            const float* modp, int mod_stride, int mod_rows,
                                            const int32_t* env_of_row, float* eo, int ntok_live) {
-  using C = FusedCfg<D, NT, H, HEADS, CM, CH, SX>;
-  constexpr int DH = C::DH, HP = C::HP, NB = C::NB, MBH = C::MBH, MBQ = C::MBQ, MBU = C::MBU, RPT = C::RPT,
-                NKF = C::NKF, AS = C::AS, QS = C::QS, VS = C::VS, US = C::US, SF = C::SF;
+  constexpr int D = C::D, NT = C::NT, H = C::H, HEADS = C::HEADS, CM = C::CM, CH = C::CH, NW = C::NW;
+  constexpr int DH = C::DH, HP = C::HP, NB = C::NB, MBH = C::MBH, MBQ = C::MBQ, MBU = C::MBU, MBC = C::MBC,
+                RPT = C::RPT, NKF = C::NKF, AS = C::AS, QS = C::QS, VS = C::VS, US = C::US, SF = C::SF;
+  constexpr int NG = HEADS / HP, NC = 4 * D / CH;
   __bf16* act = reinterpret_cast<__bf16*>(lds);
   __bf16* qbuf = reinterpret_cast<__bf16*>(lds + C::ACT_B);
   __bf16* kbuf = qbuf + HP * NT * QS;
   __bf16* vtb = kbuf + HP * NT * QS;
   __bf16* ubuf = qbuf;
   float* red1 = reinterpret_cast<float*>(lds + C::ACT_B + C::SCR_B);
-  float* red2 = red1 + 4 * NT;
+  float* red2 = red1 + NW * NT;
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int l16 = lane & 15, lg = lane >> 4;
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int l16 = lane & 15, lg = lane >> 4;
+  // Makes the lane coordinates opaque at phase boundaries: addresses derived from them are then recomputed
+  // where they are used instead of being hoisted out of the layer loop and spilled to scratch.
+#define TSDP_FENCE_IDS() asm volatile("" : "+v"(lane), "+v"(l16), "+v"(lg))
 
+  constexpr int BD = C::BD;
+  constexpr bool XPF = C::XPF;
+  typedef FragGemm<MBQ, NB, D / 32, BD> GQ;             // q|k|v projection of one head group
+  typedef FragGemm<MBH, NB, DH / 32, BD> GO;            // output projection, one head's slice of K
+  typedef FragGemm<MBU, NB, D / 32, BD> GU;             // MLP up, one hidden chunk
+  typedef FragGemm<MBH, NB, CH / 32, BD> GD;            // MLP down, one hidden chunk of K
+  typedef FragGemm<MBC, NB, D / 32, BD> GC;             // cross-attention query projection
+
+#ifdef TSDP_TRACE
+  long long tacc_[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+  long long tprev_ = clock64();
+#endif
   // ---- token embedding in fp32: h = tok_w x + tok_b + pos -------------------------------------------------
   f32x4 h[MBH][NB];
 #pragma unroll
@@ -218,35 +278,31 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   }
   __syncthreads();
 
-  // writes LN(h) (1 + g) + b as bf16 into act; which = 0 (attention) / 2 (MLP) selects the FiLM pair, -1 = none
+  // writes LN(h) (1 + g) + b as bf16 into act; which = 0 (attention) / 2 (MLP) selects the FiLM pair, -1 = none.
+  // Statistics: per-wave partial sums of x and x^2 (fp32) exchanged through LDS, one barrier.
   auto write_ln = [&](int layer, int which) {
+    TSDP_FENCE_IDS();
     float mean[NB], rstd[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
-      float s = 0.0f;
-#pragma unroll
-      for (int mb = 0; mb < MBH; ++mb) s += h[mb][nb][0] + h[mb][nb][1] + h[mb][nb][2] + h[mb][nb][3];
-      s += __shfl_xor(s, 16); s += __shfl_xor(s, 32);
-      if (lane < 16) red1[wave * NT + nb * 16 + lane] = s;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const int t = nb * 16 + l16;
-      mean[nb] = (red1[t] + red1[NT + t] + red1[2 * NT + t] + red1[3 * NT + t]) * (1.0f / D);
-      float q = 0.0f;
+      float s = 0.0f, q = 0.0f;
 #pragma unroll
       for (int mb = 0; mb < MBH; ++mb)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { const float e = h[mb][nb][i] - mean[nb]; q += e * e; }
+        for (int i = 0; i < 4; ++i) { s += h[mb][nb][i]; q = fmaf(h[mb][nb][i], h[mb][nb][i], q); }
+      s += __shfl_xor(s, 16); s += __shfl_xor(s, 32);
       q += __shfl_xor(q, 16); q += __shfl_xor(q, 32);
-      if (lane < 16) red2[wave * NT + nb * 16 + lane] = q;
+      if (lane < 16) { red1[wave * NT + nb * 16 + lane] = s; red2[wave * NT + nb * 16 + lane] = q; }
     }
     __syncthreads();
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       const int t = nb * 16 + l16;
-      rstd[nb] = rsqrtf((red2[t] + red2[NT + t] + red2[2 * NT + t] + red2[3 * NT + t]) * (1.0f / D) + 1e-5f);
+      float s = 0.0f, q = 0.0f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) { s += red1[w * NT + t]; q += red2[w * NT + t]; }
+      mean[nb] = s * (1.0f / D);
+      rstd[nb] = rsqrtf(fmaxf(q * (1.0f / D) - mean[nb] * mean[nb], 0.0f) + 1e-5f);
     }
 #pragma unroll
     for (int mb = 0; mb < MBH; ++mb) {
@@ -263,121 +319,100 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         }
         *reinterpret_cast<bf16x4*>(act + (nb * 16 + l16) * AS + f0) = to_bf16x4(v);
       }
+      __builtin_amdgcn_sched_barrier(0);                // keep the FiLM loads of one fragment row in flight, not all
     }
     __syncthreads();
   };
 
-  // softmax over keys for every query column of s (scores transposed: keys on rows), probabilities as bf16
-  auto softmax_cols = [&](auto& s, auto& p, auto KF) {
+  // softmax over the keys (rows of s, NK key fragments) for the 16 queries of one fragment
+  auto softmax_col = [&](auto& s, auto& p, auto KF) {
     constexpr int NK = decltype(KF)::value;
     const float scale = rsqrtf((float)DH);
+    float mx = -INFINITY;
 #pragma unroll
-    for (int qf = 0; qf < NKF; ++qf) {
-      float mx = -INFINITY;
+    for (int kf = 0; kf < NK; ++kf)
 #pragma unroll
-      for (int kf = 0; kf < NK; ++kf)
+      for (int i = 0; i < 4; ++i) { s[kf][i] *= scale; mx = fmaxf(mx, s[kf][i]); }
+    mx = fmaxf(mx, __shfl_xor(mx, 16)); mx = fmaxf(mx, __shfl_xor(mx, 32));
+    float sum = 0.0f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { s[kf][qf][i] *= scale; mx = fmaxf(mx, s[kf][qf][i]); }
-      mx = fmaxf(mx, __shfl_xor(mx, 16)); mx = fmaxf(mx, __shfl_xor(mx, 32));
-      float sum = 0.0f;
+    for (int kf = 0; kf < NK; ++kf)
 #pragma unroll
-      for (int kf = 0; kf < NK; ++kf)
+      for (int i = 0; i < 4; ++i) { s[kf][i] = __expf(s[kf][i] - mx); sum += s[kf][i]; }
+    sum += __shfl_xor(sum, 16); sum += __shfl_xor(sum, 32);
+    const float inv = 1.0f / sum;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { s[kf][qf][i] = __expf(s[kf][qf][i] - mx); sum += s[kf][qf][i]; }
-      sum += __shfl_xor(sum, 16); sum += __shfl_xor(sum, 32);
-      const float inv = 1.0f / sum;
-#pragma unroll
-      for (int kf = 0; kf < NK; ++kf) p[kf][qf] = to_bf16x4(s[kf][qf] * inv);
-    }
+    for (int kf = 0; kf < NK; ++kf) p[kf] = to_bf16x4(s[kf] * inv);
   };
 
-  // softmax(q k^T) v for one (row, head) held in LDS; the result overwrites the q rows of that (row, head)
-  auto self_attention = [&](int r, int hh) {
-    __bf16* qp = qbuf + (hh * NT + r * H) * QS;
+  // softmax(q k^T) v for query fragment qf of (row, head) held in LDS; the result overwrites those q rows
+  auto self_attention = [&](int r, int hh, int qf) {
+    __bf16* qp = qbuf + (hh * NT + r * H + qf * 16) * QS;
     const __bf16* kp = kbuf + (hh * NT + r * H) * QS;
-    f32x4 s[NKF][NKF];                                  // [key frag][query frag]; lane: query l16, keys lg*4..
+    f32x4 s[NKF];                                       // [key frag]; lane: query l16, keys lg*4..
 #pragma unroll
-    for (int kf = 0; kf < NKF; ++kf)
-#pragma unroll
-      for (int qf = 0; qf < NKF; ++qf) s[kf][qf] = f32x4{0, 0, 0, 0};
+    for (int kf = 0; kf < NKF; ++kf) s[kf] = f32x4{0, 0, 0, 0};
 #pragma unroll
     for (int ks = 0; ks < DH / 32; ++ks) {
-      bf16x8 ka[NKF], qb[NKF];
+      const bf16x8 qb = *reinterpret_cast<const bf16x8*>(qp + l16 * QS + ks * 32 + lg * 8);
 #pragma unroll
-      for (int f = 0; f < NKF; ++f) {
-        ka[f] = *reinterpret_cast<const bf16x8*>(kp + (f * 16 + l16) * QS + ks * 32 + lg * 8);
-        qb[f] = *reinterpret_cast<const bf16x8*>(qp + (f * 16 + l16) * QS + ks * 32 + lg * 8);
+      for (int kf = 0; kf < NKF; ++kf) {
+        const bf16x8 ka = *reinterpret_cast<const bf16x8*>(kp + (kf * 16 + l16) * QS + ks * 32 + lg * 8);
+        s[kf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qb, s[kf], 0, 0, 0);
       }
-#pragma unroll
-      for (int kf = 0; kf < NKF; ++kf)
-#pragma unroll
-        for (int qf = 0; qf < NKF; ++qf)
-          s[kf][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[kf], qb[qf], s[kf][qf], 0, 0, 0);
     }
-    bf16x4 p[NKF][NKF];
-    softmax_cols(s, p, std::integral_constant<int, NKF>{});
+    bf16x4 p[NKF];
+    softmax_col(s, p, std::integral_constant<int, NKF>{});
     const __bf16* vp = vtb + (size_t)(hh * RPT + r) * DH * VS;
 #pragma unroll
     for (int cf = 0; cf < DH / 16; ++cf) {
-      f32x4 o[NKF];
-#pragma unroll
-      for (int qf = 0; qf < NKF; ++qf) o[qf] = f32x4{0, 0, 0, 0};
+      f32x4 o = f32x4{0, 0, 0, 0};
 #pragma unroll
       for (int kf = 0; kf < NKF; ++kf) {
         const s16x4 va = *reinterpret_cast<const s16x4*>(vp + (cf * 16 + l16) * VS + kf * 16 + lg * 4);
-#pragma unroll
-        for (int qf = 0; qf < NKF; ++qf)
-          o[qf] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, __builtin_bit_cast(s16x4, p[kf][qf]), o[qf], 0, 0, 0);
+        o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, __builtin_bit_cast(s16x4, p[kf]), o, 0, 0, 0);
       }
-#pragma unroll
-      for (int qf = 0; qf < NKF; ++qf)
-        *reinterpret_cast<bf16x4*>(qp + (qf * 16 + l16) * QS + cf * 16 + lg * 4) = to_bf16x4(o[qf]);
+      *reinterpret_cast<bf16x4*>(qp + l16 * QS + cf * 16 + lg * 4) = to_bf16x4(o);
     }
   };
 
-  // attention of the H query tokens of (row, head) over the SX observation tokens of the row's environment;
+  // attention of query fragment qf of (row, head) over the SX observation tokens of the row's environment;
   // keys and transposed values come from global memory already in MFMA fragment order
-  auto cross_attention = [&](int r, int hh, int layer, int head) {
+  auto cross_attention = [&](int r, int hh, int qf, int layer, int head) {
     if constexpr (CM == 1) {
-      __bf16* qp = qbuf + (hh * NT + r * H) * QS;
+      __bf16* qp = qbuf + (hh * NT + r * H + qf * 16) * QS;
       const size_t eh = ((size_t)env_of_row[r] * net.L + layer) * HEADS + head;
       const bf16x8* kcp = net.kc + eh * (SF * (DH / 32)) * 64 + lane;
       const bf16x4* vcp = net.vct + eh * ((DH / 16) * SF) * 64 + lane;
-      f32x4 s[SF][NKF];
+      bf16x8 ka[DH / 32][SF];
 #pragma unroll
-      for (int kf = 0; kf < SF; ++kf)
+      for (int ks = 0; ks < DH / 32; ++ks)
 #pragma unroll
-        for (int qf = 0; qf < NKF; ++qf) s[kf][qf] = f32x4{0, 0, 0, 0};
+        for (int kf = 0; kf < SF; ++kf) ka[ks][kf] = kcp[(kf * (DH / 32) + ks) * 64];
+      f32x4 s[SF];
+#pragma unroll
+      for (int kf = 0; kf < SF; ++kf) s[kf] = f32x4{0, 0, 0, 0};
+      bf16x4 va[DH / 16][SF];
+#pragma unroll
+      for (int cf = 0; cf < DH / 16; ++cf)
+#pragma unroll
+        for (int kf = 0; kf < SF; ++kf) va[cf][kf] = vcp[(cf * SF + kf) * 64];
 #pragma unroll
       for (int ks = 0; ks < DH / 32; ++ks) {
-        bf16x8 qb[NKF];
+        const bf16x8 qb = *reinterpret_cast<const bf16x8*>(qp + l16 * QS + ks * 32 + lg * 8);
 #pragma unroll
-        for (int f = 0; f < NKF; ++f) qb[f] = *reinterpret_cast<const bf16x8*>(qp + (f * 16 + l16) * QS + ks * 32 + lg * 8);
-#pragma unroll
-        for (int kf = 0; kf < SF; ++kf) {
-          const bf16x8 ka = kcp[(kf * (DH / 32) + ks) * 64];
-#pragma unroll
-          for (int qf = 0; qf < NKF; ++qf)
-            s[kf][qf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qb[qf], s[kf][qf], 0, 0, 0);
-        }
+        for (int kf = 0; kf < SF; ++kf) s[kf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks][kf], qb, s[kf], 0, 0, 0);
       }
-      bf16x4 p[SF][NKF];
-      softmax_cols(s, p, std::integral_constant<int, SF>{});
+      bf16x4 p[SF];
+      softmax_col(s, p, std::integral_constant<int, SF>{});
 #pragma unroll
       for (int cf = 0; cf < DH / 16; ++cf) {
-        f32x4 o[NKF];
+        f32x4 o = f32x4{0, 0, 0, 0};
 #pragma unroll
-        for (int qf = 0; qf < NKF; ++qf) o[qf] = f32x4{0, 0, 0, 0};
-#pragma unroll
-        for (int kf = 0; kf < SF; ++kf) {
-          const s16x4 va = __builtin_bit_cast(s16x4, vcp[(cf * SF + kf) * 64]);
-#pragma unroll
-          for (int qf = 0; qf < NKF; ++qf)
-            o[qf] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, __builtin_bit_cast(s16x4, p[kf][qf]), o[qf], 0, 0, 0);
-        }
-#pragma unroll
-        for (int qf = 0; qf < NKF; ++qf)
-          *reinterpret_cast<bf16x4*>(qp + (qf * 16 + l16) * QS + cf * 16 + lg * 4) = to_bf16x4(o[qf]);
+        for (int kf = 0; kf < SF; ++kf)
+          o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, va[cf][kf]),
+                                                        __builtin_bit_cast(s16x4, p[kf]), o, 0, 0, 0);
+        *reinterpret_cast<bf16x4*>(qp + l16 * QS + cf * 16 + lg * 4) = to_bf16x4(o);
       }
     }
   };
@@ -391,28 +426,40 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
     }
   };
 
+  GQ gq;
+  if (XPF) gq.issue(net.layer[0].qkv, D / 32, wave, 0, lane, NW);
   for (int layer = 0; layer < net.L; ++layer) {
     const FusedLayer& W = net.layer[layer];
     // ================= self-attention block =================
+    TSDP_TICK(11)
     write_ln(layer, 0);
-    for (int g = 0; g < HEADS / HP; ++g) {
+    TSDP_TICK(0)
+    for (int g = 0; g < NG; ++g) {
+      TSDP_FENCE_IDS();
+      GO go;
       {
         f32x4 acc[MBQ][NB];
-#pragma unroll
-        for (int mb = 0; mb < MBQ; ++mb)
-#pragma unroll
-          for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
-        const int mf0 = g * (HP * 3 * DH / 16) + wave * MBQ;
-        gemm_frag<MBQ, NB, D / 32>(W.qkv, D / 32, mf0, 0, act, AS, acc, lane);
-        if (g > 0) __syncthreads();                     // previous group's O-projection has read qbuf
+        f32x4 bias[MBQ];
 #pragma unroll
         for (int mb = 0; mb < MBQ; ++mb) {
-          const int lr = (wave * MBQ + mb) * 16;        // first logical row of this fragment inside the group
+          bias[mb] = *reinterpret_cast<const f32x4*>(W.qkv_b + g * (HP * 3 * DH) + (mb * NW + wave) * 16 + lg * 4);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
+        }
+        if (!XPF) gq.issue(W.qkv, D / 32, g * (HP * 3 * DH / 16) + wave, 0, lane, NW);
+        gq.run(act, AS, acc, lane);
+        TSDP_TICK(1)
+        if (XPF) go.issue(W.o, D / 32, wave * MBH, g * HP * DH / 32, lane);      // needed only after the attention
+        if (g > 0) __syncthreads();                     // previous group's O-projection has read qbuf
+        TSDP_TICK(2)
+#pragma unroll
+        for (int mb = 0; mb < MBQ; ++mb) {
+          const int lr = (mb * NW + wave) * 16;         // first logical row of this fragment inside the group (rows are
+                                                        // dealt round-robin so every wave gets q, k and v rows)
           const int hh = lr / (3 * DH), cls = (lr / DH) % 3, c0 = lr % DH + lg * 4;
-          const f32x4 bias = *reinterpret_cast<const f32x4*>(W.qkv_b + g * (HP * 3 * DH) + lr + lg * 4);
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) {
-            const f32x4 v = acc[mb][nb] + bias;
+            const f32x4 v = acc[mb][nb] + bias[mb];
             const int t = nb * 16 + l16;
             if (cls == 0) {
               *reinterpret_cast<bf16x4*>(qbuf + (hh * NT + t) * QS + c0) = to_bf16x4(v);
@@ -426,65 +473,120 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
           }
         }
       }
+      TSDP_TICK(3)
       __syncthreads();
-      if (!(TSDP_ABL & 8)) for (int task = wave; task < RPT * HP; task += 4) self_attention(task % RPT, task / RPT);
+      TSDP_TICK(2)
+      if (!(TSDP_ABL & 8))
+        for (int task = wave; task < RPT * HP * NKF; task += NW)
+          self_attention((task / NKF) % RPT, task / (NKF * RPT), task % NKF);
+      TSDP_TICK(4)
       __syncthreads();
+      TSDP_TICK(2)
+      if (XPF && g + 1 < NG) gq.issue(W.qkv, D / 32, (g + 1) * (HP * 3 * DH / 16) + wave, 0, lane, NW);
+      if (!XPF) go.issue(W.o, D / 32, wave * MBH, g * HP * DH / 32, lane);
+      go.run(qbuf, QS, h, lane);
 #pragma unroll
-      for (int hh = 0; hh < HP; ++hh)
-        gemm_frag<MBH, NB, DH / 32>(W.o, D / 32, wave * MBH, (g * HP + hh) * DH / 32, qbuf + hh * NT * QS, QS, h, lane);
+      for (int hh = 1; hh < HP; ++hh) {
+        go.issue(W.o, D / 32, wave * MBH, (g * HP + hh) * DH / 32, lane);
+        go.run(qbuf + hh * NT * QS, QS, h, lane);
+      }
+      TSDP_TICK(5)
     }
     add_bias_h(W.o_b);
     // ================= cross-attention block (observation tokens) =================
     if constexpr (CM == 1) {
+      GC gc;
+      if (XPF) gc.issue(W.cq, D / 32, wave * MBC, 0, lane);
       write_ln(layer, -1);                               // its barriers order the O-projection reads before qbuf writes
-      for (int g = 0; g < HEADS / HP; ++g) {
+      for (int g = 0; g < NG; ++g) {
+        TSDP_FENCE_IDS();
+        GO go;
         {
-          f32x4 acc[1][NB];
+          f32x4 acc[MBC][NB];
+          f32x4 bias[MBC];
 #pragma unroll
-          for (int nb = 0; nb < NB; ++nb) acc[0][nb] = f32x4{0, 0, 0, 0};
-          gemm_frag<1, NB, D / 32>(W.cq, D / 32, g * (HP * DH / 16) + wave, 0, act, AS, acc, lane);
+          for (int mb = 0; mb < MBC; ++mb) {
+            bias[mb] = *reinterpret_cast<const f32x4*>(W.cq_b + g * (HP * DH) + (wave * MBC + mb) * 16 + lg * 4);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
+          }
+          if (!XPF) gc.issue(W.cq, D / 32, g * (HP * DH / 16) + wave * MBC, 0, lane);
+          gc.run(act, AS, acc, lane);
+          if (XPF) go.issue(W.co, D / 32, wave * MBH, g * HP * DH / 32, lane);
           if (g > 0) __syncthreads();
-          const int lr = wave * 16, hh = lr / DH, c0 = lr % DH + lg * 4;
-          const f32x4 bias = *reinterpret_cast<const f32x4*>(W.cq_b + g * (HP * DH) + lr + lg * 4);
 #pragma unroll
-          for (int nb = 0; nb < NB; ++nb)
-            *reinterpret_cast<bf16x4*>(qbuf + (hh * NT + nb * 16 + l16) * QS + c0) = to_bf16x4(acc[0][nb] + bias);
+          for (int mb = 0; mb < MBC; ++mb) {
+            const int lr = (wave * MBC + mb) * 16, hh = lr / DH, c0 = lr % DH + lg * 4;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+              *reinterpret_cast<bf16x4*>(qbuf + (hh * NT + nb * 16 + l16) * QS + c0) = to_bf16x4(acc[mb][nb] + bias[mb]);
+          }
         }
         __syncthreads();
-        if (!(TSDP_ABL & 8)) for (int task = wave; task < RPT * HP; task += 4) cross_attention(task % RPT, task / RPT, layer, g * HP + task / RPT);
+        if (!(TSDP_ABL & 8))
+          for (int task = wave; task < RPT * HP * NKF; task += NW) {
+            const int hh = task / (NKF * RPT);
+            cross_attention((task / NKF) % RPT, hh, task % NKF, layer, g * HP + hh);
+          }
         __syncthreads();
+        if (XPF && g + 1 < NG) gc.issue(W.cq, D / 32, (g + 1) * (HP * DH / 16) + wave * MBC, 0, lane);
+        if (!XPF) go.issue(W.co, D / 32, wave * MBH, g * HP * DH / 32, lane);
+        go.run(qbuf, QS, h, lane);
 #pragma unroll
-        for (int hh = 0; hh < HP; ++hh)
-          gemm_frag<MBH, NB, DH / 32>(W.co, D / 32, wave * MBH, (g * HP + hh) * DH / 32, qbuf + hh * NT * QS, QS, h, lane);
+        for (int hh = 1; hh < HP; ++hh) {
+          go.issue(W.co, D / 32, wave * MBH, (g * HP + hh) * DH / 32, lane);
+          go.run(qbuf + hh * NT * QS, QS, h, lane);
+        }
       }
       add_bias_h(W.co_b);
     }
     // ================= MLP block =================
+    GU gu;
+    if (XPF) gu.issue(W.up, D / 32, wave * MBU, 0, lane);
+    TSDP_TICK(11)
     write_ln(layer, 2);                                  // its barriers also order the projection reads before ubuf writes
-    for (int c = 0; c < 4 * D / CH; ++c) {
+    TSDP_TICK(0)
+    for (int c = 0; c < NC; ++c) {
+      TSDP_FENCE_IDS();
+      GD gd;
       {
         f32x4 acc[MBU][NB];
+        f32x4 bias[MBU];
 #pragma unroll
-        for (int mb = 0; mb < MBU; ++mb)
+        for (int mb = 0; mb < MBU; ++mb) {
+          bias[mb] = *reinterpret_cast<const f32x4*>(W.up_b + c * CH + (wave * MBU + mb) * 16 + lg * 4);
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
-        gemm_frag<MBU, NB, D / 32>(W.up, D / 32, c * (CH / 16) + wave * MBU, 0, act, AS, acc, lane);
+        }
+        if (!XPF) gu.issue(W.up, D / 32, c * (CH / 16) + wave * MBU, 0, lane);
+        gu.run(act, AS, acc, lane);
+        TSDP_TICK(6)
+        if (XPF) gd.issue(W.dn, 4 * D / 32, wave * MBH, c * (CH / 32), lane);
         if (c > 0) __syncthreads();                     // previous chunk's down-projection has read ubuf
+        TSDP_TICK(7)
 #pragma unroll
         for (int mb = 0; mb < MBU; ++mb) {
           const int f0 = (wave * MBU + mb) * 16 + lg * 4;
-          const f32x4 bias = *reinterpret_cast<const f32x4*>(W.up_b + c * CH + f0);
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) {
-            f32x4 v = acc[mb][nb] + bias;
+            f32x4 v = acc[mb][nb] + bias[mb];
 #pragma unroll
             for (int i = 0; i < 4; ++i) v[i] = (TSDP_ABL & 16) ? v[i] : gelu_fast(v[i]);
             *reinterpret_cast<bf16x4*>(ubuf + (nb * 16 + l16) * US + f0) = to_bf16x4(v);
           }
         }
       }
+      TSDP_TICK(8)
       __syncthreads();
-      gemm_frag<MBH, NB, CH / 32>(W.dn, 4 * D / 32, wave * MBH, c * (CH / 32), ubuf, US, h, lane);
+      TSDP_TICK(7)
+      if (XPF) {
+        if (c + 1 < NC) gu.issue(W.up, D / 32, (c + 1) * (CH / 16) + wave * MBU, 0, lane);
+        else if (layer + 1 < net.L) gq.issue(net.layer[layer + 1].qkv, D / 32, wave, 0, lane, NW);
+      } else {
+        gd.issue(W.dn, 4 * D / 32, wave * MBH, c * (CH / 32), lane);
+      }
+      gd.run(ubuf, US, h, lane);
+      TSDP_TICK(9)
     }
     add_bias_h(W.dn_b);
   }
@@ -492,13 +594,15 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   // ---- output head: eps = head_w LN(h) + head_b ---------------------------------------------------------
   write_ln(0, -1);
   {
-    constexpr int NBW = (NB + 3) / 4;                   // token fragments per wave
+    constexpr int NBW = (NB + NW - 1) / NW;             // token fragments per wave
     f32x4 e[1][NBW];
 #pragma unroll
     for (int j = 0; j < NBW; ++j) e[0][j] = f32x4{0, 0, 0, 0};
     const int nb0 = wave * NBW;
     if (nb0 < NB) {
-      gemm_frag<1, NBW, D / 32>(net.head, D / 32, 0, 0, act + nb0 * 16 * AS, AS, e, lane);
+      FragGemm<1, NBW, D / 32> gh;
+      gh.issue(net.head, D / 32, 0, 0, lane);
+      gh.run(act + nb0 * 16 * AS, AS, e, lane);
 #pragma unroll
       for (int j = 0; j < NBW; ++j) {
         const int t = (nb0 + j) * 16 + l16;
@@ -512,12 +616,17 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       }
     }
   }
+#ifdef TSDP_TRACE
+  TSDP_TICK(10)
+  if (blockIdx.x == 300 && lane == 0 && net.trace)
+    for (int i = 0; i < 12; ++i) net.trace[wave * 12 + i] = tacc_[i];
+#endif
 }
 
 // Batched verification: tile b of the grid takes rows b*RPT .. of the ragged batch.
-template <int D, int NT, int H, int HEADS, int CM, int CH, int SX>
-__global__ __launch_bounds__(256, (FusedCfg<D, NT, H, HEADS, CM, CH, SX>::LDS_B <= 80 * 1024 ? 2 : 1)) void k_fused_forward(FusedNet net, FusedIO io, int A) {
-  using C = FusedCfg<D, NT, H, HEADS, CM, CH, SX>;
+template <class C>
+__global__ __launch_bounds__(C::THREADS, C::WG_PER_CU) void k_fused_forward(FusedNet net, FusedIO io, int A) {
+  constexpr int D = C::D, NT = C::NT, H = C::H;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   __shared__ int32_t envs[C::RPT];
   const int R = io.d_R ? min(*io.d_R, io.R_cap) : io.R_cap;
@@ -526,24 +635,25 @@ __global__ __launch_bounds__(256, (FusedCfg<D, NT, H, HEADS, CM, CH, SX>::LDS_B 
   const long long tok0 = (long long)row0 * H;
   const int ntok_live = min(NT, (R - row0) * H);
   float* xt = reinterpret_cast<float*>(lds + C::ACT_B);
-  for (int i = threadIdx.x; i < NT * A; i += 256) xt[i] = i < ntok_live * A ? io.x_rows[tok0 * A + i] : 0.0f;
+  for (int i = threadIdx.x; i < NT * A; i += C::THREADS) xt[i] = i < ntok_live * A ? io.x_rows[tok0 * A + i] : 0.0f;
   if (threadIdx.x < C::RPT) {
     const int r = min(row0 + (int)threadIdx.x, R - 1);
     envs[threadIdx.x] = io.row_env ? io.row_env[r] : r;
   }
   __syncthreads();
   const int mod_stride = net.L * 4 * D;
-  fused_body<D, NT, H, HEADS, CM, CH, SX>(net, lds, xt, A, io.mod + (size_t)row0 * mod_stride, mod_stride, R - row0, envs,
-                                          io.eps_out + tok0 * A, ntok_live);
+  fused_body<C>(net, lds, xt, A, io.mod + (size_t)row0 * mod_stride, mod_stride, R - row0, envs, io.eps_out + tok0 * A,
+                ntok_live);
 }
 
 // Drafter rollout: the workgroup keeps the latents of RPT environments in LDS and runs their drafted
 // transitions k = 1 .. max K_eff back to back; every step is one forward pass plus the DDPM step
 //   y <- mu_p(y, eps, t_k) + s sigma_{t_k} xi_{env,t_k},   t_k = t0 - k + 1,
 // and stores the input state, the drafter output and the noise of the transition in its ragged row.
-template <int D, int NT, int H, int HEADS, int CM, int CH, int SX>
+template <class C>
 __global__ __launch_bounds__(256) void k_fused_draft(FusedNet net, DraftIO io, int A) {
-  using C = FusedCfg<D, NT, H, HEADS, CM, CH, SX>;
+  static_assert(C::NW == 4, "the drafter kernel runs four wavefronts");
+  constexpr int D = C::D, NT = C::NT, H = C::H;
   constexpr int RPT = C::RPT;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   __shared__ int32_t envs[RPT], s_t0[RPT], s_keff[RPT], s_rowp[RPT], s_kmax;
@@ -594,7 +704,9 @@ __global__ __launch_bounds__(256) void k_fused_draft(FusedNet net, DraftIO io, i
         f32x4 acc[MBM][1];
 #pragma unroll
         for (int mb = 0; mb < MBM; ++mb) acc[mb][0] = f32x4{0, 0, 0, 0};
-        gemm_frag<MBM, 1, D / 32>(net.modw, D / 32, wave * fpw + f, 0, sgbuf, D + 8, acc, lane);
+        FragGemm<MBM, 1, D / 32> gm;
+        gm.issue(net.modw, D / 32, wave * fpw + f, 0, lane);
+        gm.run(sgbuf, D + 8, acc, lane);
         if (l16 < RPT) {
 #pragma unroll
           for (int mb = 0; mb < MBM; ++mb) {
@@ -606,7 +718,7 @@ __global__ __launch_bounds__(256) void k_fused_draft(FusedNet net, DraftIO io, i
       }
     }
     __syncthreads();
-    fused_body<D, NT, H, HEADS, CM, CH, SX>(net, lds, yt, A, modbuf, mod_stride, RPT, envs, et, NT);
+    fused_body<C>(net, lds, yt, A, modbuf, mod_stride, RPT, envs, et, NT);
     __syncthreads();
     // DDPM step of transition k for the environments that still draft
     const int nblk = DE >> 2;

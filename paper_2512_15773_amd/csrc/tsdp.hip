@@ -134,24 +134,22 @@ void pack_frags(std::vector<uint16_t>& out, const float* W, int K, int rows, Row
       }
 }
 
-template <int D, int NT, int H, int HEADS, int CM, int CH, int SX>
+template <class C>
 void launch_verify(const FusedNet& n, const FusedIO& io, int A, int R_cap, hipStream_t s) {
-  using C = FusedCfg<D, NT, H, HEADS, CM, CH, SX>;
-  auto kern = k_fused_forward<D, NT, H, HEADS, CM, CH, SX>;
+  auto kern = k_fused_forward<C>;
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_B);
     attr_set = true;
   }
   const int tiles = (R_cap + C::RPT - 1) / C::RPT;
-  hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), C::LDS_B, s, n, io, A);
+  hipLaunchKernelGGL(kern, dim3(tiles), dim3(C::THREADS), C::LDS_B, s, n, io, A);
 }
 
-template <int D, int NT, int H, int HEADS, int CM, int CH, int SX>
+template <class C>
 void launch_draft(const FusedNet& n, const DraftIO& io, int A, hipStream_t s) {
-  using C = FusedCfg<D, NT, H, HEADS, CM, CH, SX>;
-  auto kern = k_fused_draft<D, NT, H, HEADS, CM, CH, SX>;
-  const int lds = C::LDS_B + 2 * NT * A * 4 + C::RPT * n.L * 4 * D * 4 + 16 * (D + 8) * 2;
+  auto kern = k_fused_draft<C>;
+  const int lds = C::LDS_B + 2 * C::NT * A * 4 + C::RPT * n.L * 4 * C::D * 4 + 16 * (C::D + 8) * 2;
   static int attr_lds = 0;
   if (lds > attr_lds) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -171,20 +169,21 @@ struct FusedKernels {
 // shapes with compiled fused kernels
 bool find_fused(int D, int H, int heads, int cm, int S, int mlp_ratio, int L, FusedKernels& k) {
   if (mlp_ratio != 4 || L > FUSED_MAX_LAYERS) return false;
-#define TSDP_SHAPE(D_, H_, HD_, CM_, SX_, NTV, CHV, NTS, NTB, CHD)                                   \
-  if (D == D_ && H == H_ && heads == HD_ && cm == CM_ && (CM_ == 0 || S == SX_)) {                 \
-    k.verify = launch_verify<D_, NTV, H_, HD_, CM_, CHV, SX_>;                                     \
-    k.draft_small = launch_draft<D_, NTS, H_, HD_, CM_, CHD, SX_>; k.rpt_small = NTS / H_;         \
-    k.draft_big = launch_draft<D_, NTB, H_, HD_, CM_, CHD, SX_>;   k.rpt_big = NTB / H_;           \
-    return true;                                                                                   \
+#define TSDP_SHAPE(D_, H_, HD_, CM_, SX_, NTV, CHV, HPV, NWV, NTS, NTB, CHD)                               \
+  if (D == D_ && H == H_ && heads == HD_ && cm == CM_ && (CM_ == 0 || S == SX_)) {                     \
+    constexpr int HPD = (D_ / HD_) >= 64 ? 1 : 64 / (D_ / HD_);                                        \
+    k.verify = launch_verify<FusedCfg<D_, NTV, H_, HD_, CM_, CHV, SX_, HPV, NWV>>;                     \
+    k.draft_small = launch_draft<FusedCfg<D_, NTS, H_, HD_, CM_, CHD, SX_, HPD, 4>>; k.rpt_small = NTS / H_; \
+    k.draft_big = launch_draft<FusedCfg<D_, NTB, H_, HD_, CM_, CHD, SX_, HPD, 4>>;   k.rpt_big = NTB / H_;   \
+    return true;                                                                                       \
   }
-  //          D   H  heads cm  S  verify NT/CH  draft NT small/big, CH
-  TSDP_SHAPE(256, 16, 4, 0, 0, 64, 128, 16, 64, 128)
-  TSDP_SHAPE(384, 16, 6, 0, 0, 64, 128, 16, 64, 128)
-  TSDP_SHAPE(128, 16, 4, 0, 0, 128, 128, 16, 64, 128)
-  TSDP_SHAPE(192, 16, 6, 0, 0, 128, 128, 16, 64, 128)
-  TSDP_SHAPE(512, 32, 8, 1, 64, 64, 256, 32, 64, 128)
-  TSDP_SHAPE(256, 32, 8, 1, 64, 64, 256, 32, 64, 128)
+  //          D   H  heads cm  S | verify: NT  CH  HP NW | draft: NT small, big, CH
+  TSDP_SHAPE(256, 16, 4, 0, 0, 64, 128, 1, 4, 16, 64, 128)
+  TSDP_SHAPE(384, 16, 6, 0, 0, 64, 192, 1, 4, 16, 64, 128)
+  TSDP_SHAPE(128, 16, 4, 0, 0, 128, 128, 2, 4, 16, 64, 128)
+  TSDP_SHAPE(192, 16, 6, 0, 0, 128, 128, 2, 4, 16, 64, 128)
+  TSDP_SHAPE(512, 32, 8, 1, 64, 64, 256, 1, 4, 32, 64, 128)
+  TSDP_SHAPE(256, 32, 8, 1, 64, 64, 256, 2, 4, 32, 64, 128)
 #undef TSDP_SHAPE
   return false;
 }
@@ -285,6 +284,9 @@ int build_fused(tsdp_ctx* c, Net& n, const std::vector<float>& w, const std::vec
     f.kc = reinterpret_cast<const bf16x8*>(n.kc_pk);
     f.vct = reinterpret_cast<const bf16x4*>(n.vct_pk);
   }
+#ifdef TSDP_TRACE
+  if ((rc = dev_alloc(c, &f.trace, 8 * 12))) return rc;
+#endif
   n.fused = true;
   n.fused_verify = fk.verify;
   n.fused_draft_small = fk.draft_small; n.fused_draft_big = fk.draft_big;
@@ -711,5 +713,11 @@ const char* tsdp_path_name(const tsdp_ctx* c, int which) {
 }
 
 const char* tsdp_last_error(const tsdp_ctx* c) { return c ? c->err.c_str() : "null context"; }
+
+#ifdef TSDP_TRACE
+int tsdp_debug_trace(tsdp_ctx* c, int which, long long* h_out) {   // tuning builds only
+  return hipMemcpy(h_out, c->net[which].fnet.trace, 8 * 12 * sizeof(long long), hipMemcpyDeviceToHost) == hipSuccess ? 0 : -4;
+}
+#endif
 
 }  // extern "C"
