@@ -202,12 +202,13 @@ struct FusedCfg {
 #ifdef TSDP_FORCE_BD
   static constexpr int BD = TSDP_FORCE_BD;
 #else
-  static constexpr int BD = WG_PER_CU == 2 ? 1 : 2;     // LDS operand buffers: the second workgroup hides LDS latency
+  static constexpr int WAVES_PER_SIMD = WG_PER_CU * NW / 4;
+  static constexpr int BD = WAVES_PER_SIMD >= 2 ? 1 : 2; // LDS operand buffers: a second wave on the SIMD hides LDS latency
 #endif
 #ifdef TSDP_FORCE_XPF
   static constexpr bool XPF = TSDP_FORCE_XPF;
 #else
-  static constexpr bool XPF = WG_PER_CU == 1;           // request the first weight fragments of a phase one phase early
+  static constexpr bool XPF = WAVES_PER_SIMD == 1;      // request the first weight fragments of a phase one phase early
 #endif
   static_assert(D % (16 * NW) == 0 && NT % 16 == 0 && H % 16 == 0 && NT % H == 0 && DH % 32 == 0, "shape");
   static_assert((HEADS % HP) == 0 && (HP * 3 * DH) % (16 * NW) == 0 && (HP * DH) % (16 * NW) == 0, "shape");
@@ -753,6 +754,57 @@ __global__ __launch_bounds__(256) void k_fused_draft(FusedNet net, DraftIO io, i
   for (int i = threadIdx.x; i < NT * A; i += 256) {
     const int b = env0 + i / DE;
     if (b < io.B) io.y[(size_t)env0 * DE + i] = yt[i];
+  }
+}
+
+// FiLM vectors of a ragged batch with the matrix cores: mod[r, :] = W_mod SiLU(temb[t_r] + cemb[env_r]) + b_mod
+// for all layers at once.  Tile: 128 rows x 256 outputs per workgroup; the SiLU input rows are built in LDS as
+// bf16 and the weights stream as fragments (FusedNet::modw).
+template <int D>
+__global__ __launch_bounds__(256) void k_mod_gemm(const bf16x8* __restrict__ modw, const float* __restrict__ modb,
+                                                  const float* __restrict__ temb, const float* __restrict__ cemb,
+                                                  const int32_t* __restrict__ t_arr, int t_sub,
+                                                  const int32_t* __restrict__ env_arr, int T, int Nm,
+                                                  const int32_t* d_R, int R_cap, float* __restrict__ mod) {
+  constexpr int NR = 128, NB = NR / 16, MB = 4, AS = D + 8;
+  __shared__ __attribute__((aligned(16))) __bf16 sg[NR * AS];
+  const int R = d_R ? min(*d_R, R_cap) : R_cap;
+  const int row0 = blockIdx.y * NR;
+  if (row0 >= R) return;
+  int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  for (int i = threadIdx.x; i < NR * (D / 4); i += 256) {
+    const int r = i / (D / 4), c = (i % (D / 4)) * 4;
+    const int row = min(row0 + r, R - 1);
+    int t = t_arr[row] - t_sub;
+    t = t < 0 ? 0 : (t >= T ? T - 1 : t);
+    f32x4 g = *reinterpret_cast<const f32x4*>(temb + (size_t)t * D + c);
+    if (cemb) g += *reinterpret_cast<const f32x4*>(cemb + (size_t)(env_arr ? env_arr[row] : row) * D + c);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) g[j] = g[j] * __builtin_amdgcn_rcpf(1.0f + __expf(-g[j]));
+    *reinterpret_cast<bf16x4*>(sg + r * AS + c) = to_bf16x4(g);
+  }
+  __syncthreads();
+  const int mf0 = blockIdx.x * 16 + wave * MB;          // 16 fragment rows (256 outputs) per workgroup
+  if (mf0 * 16 >= Nm) return;
+  f32x4 acc[MB][NB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
+  FragGemm<MB, NB, D / 32> gm;
+  gm.issue(modw, D / 32, mf0, 0, lane);
+  gm.run(sg, AS, acc, lane);
+  const int l16 = lane & 15, lg = lane >> 4;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+    const int f0 = (mf0 + mb) * 16 + lg * 4;
+    const f32x4 b = *reinterpret_cast<const f32x4*>(modb + f0);
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int row = row0 + nb * 16 + l16;
+      if (row < R) *reinterpret_cast<f32x4*>(mod + (size_t)row * Nm + f0) = acc[mb][nb] + b;
+    }
   }
 }
 

@@ -41,6 +41,7 @@ struct Net {
   bool fused = false;
   FusedNet fnet;
   void (*fused_verify)(const FusedNet&, const FusedIO&, int A, int R_cap, hipStream_t) = nullptr;
+  void (*fused_mod)(const FusedNet&, const int32_t*, int, const int32_t*, int, const int32_t*, int, float*, hipStream_t) = nullptr;
   void (*fused_draft_small)(const FusedNet&, const DraftIO&, int A, hipStream_t) = nullptr;   // few environments per workgroup
   void (*fused_draft_big)(const FusedNet&, const DraftIO&, int A, hipStream_t) = nullptr;     // many environments per workgroup
   int draft_rpt_small = 0, draft_rpt_big = 0;
@@ -159,7 +160,17 @@ void launch_draft(const FusedNet& n, const DraftIO& io, int A, hipStream_t s) {
   hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), lds, s, n, io, A);
 }
 
+template <int D>
+void launch_mod(const FusedNet& n, const int32_t* t_arr, int t_sub, const int32_t* env_arr, int T, const int32_t* d_R,
+                int R_cap, float* mod, hipStream_t s) {
+  const int Nm = n.L * 4 * D;                           // a multiple of 256 because D is a multiple of 64
+  dim3 g(Nm / 256, (R_cap + 127) / 128);
+  hipLaunchKernelGGL(k_mod_gemm<D>, g, dim3(256), 0, s, n.modw, n.modb, n.temb, n.cemb, t_arr, t_sub, env_arr, T, Nm, d_R,
+                     R_cap, mod);
+}
+
 struct FusedKernels {
+  void (*mod)(const FusedNet&, const int32_t*, int, const int32_t*, int, const int32_t*, int, float*, hipStream_t) = nullptr;
   void (*verify)(const FusedNet&, const FusedIO&, int, int, hipStream_t) = nullptr;
   void (*draft_small)(const FusedNet&, const DraftIO&, int, hipStream_t) = nullptr;
   void (*draft_big)(const FusedNet&, const DraftIO&, int, hipStream_t) = nullptr;
@@ -173,6 +184,7 @@ bool find_fused(int D, int H, int heads, int cm, int S, int mlp_ratio, int L, Fu
   if (D == D_ && H == H_ && heads == HD_ && cm == CM_ && (CM_ == 0 || S == SX_)) {                     \
     constexpr int HPD = (D_ / HD_) >= 64 ? 1 : 64 / (D_ / HD_);                                        \
     k.verify = launch_verify<FusedCfg<D_, NTV, H_, HD_, CM_, CHV, SX_, HPV, NWV>>;                     \
+    k.mod = launch_mod<D_>;                                                                            \
     k.draft_small = launch_draft<FusedCfg<D_, NTS, H_, HD_, CM_, CHD, SX_, HPD, 4>>; k.rpt_small = NTS / H_; \
     k.draft_big = launch_draft<FusedCfg<D_, NTB, H_, HD_, CM_, CHD, SX_, HPD, 4>>;   k.rpt_big = NTB / H_;   \
     return true;                                                                                       \
@@ -182,7 +194,7 @@ bool find_fused(int D, int H, int heads, int cm, int S, int mlp_ratio, int L, Fu
   TSDP_SHAPE(384, 16, 6, 0, 0, 64, 192, 1, 4, 16, 64, 128)
   TSDP_SHAPE(128, 16, 4, 0, 0, 128, 128, 2, 4, 16, 64, 128)
   TSDP_SHAPE(192, 16, 6, 0, 0, 128, 128, 2, 4, 16, 64, 128)
-  TSDP_SHAPE(512, 32, 8, 1, 64, 64, 256, 1, 4, 32, 64, 128)
+  TSDP_SHAPE(512, 32, 8, 1, 64, 64, 256, 2, 8, 32, 64, 128)
   TSDP_SHAPE(256, 32, 8, 1, 64, 64, 256, 2, 4, 32, 64, 128)
 #undef TSDP_SHAPE
   return false;
@@ -289,6 +301,7 @@ int build_fused(tsdp_ctx* c, Net& n, const std::vector<float>& w, const std::vec
 #endif
   n.fused = true;
   n.fused_verify = fk.verify;
+  n.fused_mod = fk.mod;
   n.fused_draft_small = fk.draft_small; n.fused_draft_big = fk.draft_big;
   n.draft_rpt_small = fk.rpt_small; n.draft_rpt_big = fk.rpt_big;
   n.path = "bf16-mfma-fused";
@@ -354,10 +367,7 @@ void forward(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t*
     return;
   }
   const tsdp_config& cf = c->cfg;
-  const int d = n.d;
-  hipLaunchKernelGGL(k_gvec, grid1((long long)R_cap * d, 256), dim3(256), 0, s, t_arr, t_sub, env_arr, n.temb,
-                     cf.cond_mode == 0 ? n.cemb : nullptr, c->sg, d, cf.T, d_R, R_cap);
-  linear<0>(s, c->sg, n.modw, n.modb, c->mod, R_cap, 1, n.L * 4 * d, d, d_R);
+  n.fused_mod(n.fnet, t_arr, t_sub, env_arr, cf.T, d_R, R_cap, c->mod, s);
   FusedIO io;
   io.x_rows = x_rows; io.mod = c->mod; io.row_env = env_arr; io.d_R = d_R; io.R_cap = R_cap; io.eps_out = eps_out;
   n.fused_verify(n.fnet, io, cf.A, R_cap, s);
