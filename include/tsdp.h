@@ -123,6 +123,13 @@ int tsdp_round(tsdp_ctx* ctx, int B, float* d_x, int32_t* d_t, const int32_t* d_
  * bit 0 = some K was outside 0..K_max (clamped), bit 1 = some t0 was >= T (treated as T-1). */
 int tsdp_status(tsdp_ctx* ctx, void* stream, int32_t* h_status);
 
+/* Measurement aid.  tsdp_kernel_timing(ctx, 1) makes the following calls record a pair of HIP events on the
+ * caller's stream around the dominant kernel of each stage (0 = drafter rollout kernel, 1 = verify forward
+ * kernel, 2 = acceptance kernel); tsdp_kernel_ms waits for the last such pair of a stage and returns its
+ * elapsed time in milliseconds.  Stages that run as a sequence of operator kernels are not timed. */
+int tsdp_kernel_timing(tsdp_ctx* ctx, int enable);
+int tsdp_kernel_ms(tsdp_ctx* ctx, int stage, float* h_ms);
+
 /* Name of the kernel path used for a network ("f32-ops", "bf16-mfma-fused", ...). which: 0 base, 1 drafter. */
 const char* tsdp_path_name(const tsdp_ctx* ctx, int which);
 

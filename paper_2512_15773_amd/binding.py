@@ -13,7 +13,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtsdp.so")
 
 EXPORTS = ["tsdp_create", "tsdp_destroy", "tsdp_load_weights", "tsdp_set_cond", "tsdp_draft", "tsdp_verify",
-           "tsdp_accept", "tsdp_round", "tsdp_status", "tsdp_path_name", "tsdp_last_error"]
+           "tsdp_accept", "tsdp_round", "tsdp_status", "tsdp_kernel_timing", "tsdp_kernel_ms", "tsdp_path_name",
+           "tsdp_last_error"]
 
 
 class TsdpConfig(C.Structure):
@@ -47,6 +48,8 @@ def load_library():
     lib.tsdp_accept.argtypes = [vp, i32] + [vp] * 16 + [vp]
     lib.tsdp_round.argtypes = [vp, i32] + [vp] * 7 + [vp]
     lib.tsdp_status.argtypes = [vp, vp, C.POINTER(C.c_int32)]
+    lib.tsdp_kernel_timing.argtypes = [vp, i32]
+    lib.tsdp_kernel_ms.argtypes = [vp, i32, C.POINTER(C.c_float)]
     lib.tsdp_path_name.argtypes = [vp, i32]; lib.tsdp_path_name.restype = C.c_char_p
     lib.tsdp_last_error.argtypes = [vp]; lib.tsdp_last_error.restype = C.c_char_p
     for name in EXPORTS:
@@ -178,6 +181,14 @@ class Tsdp:
         self._chk(self.lib.tsdp_round(self.ctx, x.shape[0], _ptr(x, torch.float32), _ptr(t, torch.int32),
                                       _ptr(K, torch.int32), _ptr(sigma_scale, torch.float32), _ptr(env_id, torch.int32),
                                       _ptr(n_accept, torch.int32), _ptr(n_advanced, torch.int32), _stream(stream)))
+
+    def tsdp_kernel_timing(self, enable):
+        self._chk(self.lib.tsdp_kernel_timing(self.ctx, 1 if enable else 0))
+
+    def tsdp_kernel_ms(self, stage):
+        ms = C.c_float(0)
+        self._chk(self.lib.tsdp_kernel_ms(self.ctx, stage, C.byref(ms)))
+        return ms.value
 
     def tsdp_status(self, stream=None):
         st = C.c_int32(0)

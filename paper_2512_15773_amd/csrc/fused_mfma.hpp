@@ -785,26 +785,29 @@ __global__ __launch_bounds__(256) void k_mod_gemm(const bf16x8* __restrict__ mod
     *reinterpret_cast<bf16x4*>(sg + r * AS + c) = to_bf16x4(g);
   }
   __syncthreads();
-  const int mf0 = blockIdx.x * 16 + wave * MB;          // 16 fragment rows (256 outputs) per workgroup
-  if (mf0 * 16 >= Nm) return;
-  f32x4 acc[MB][NB];
-#pragma unroll
-  for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
-  FragGemm<MB, NB, D / 32> gm;
-  gm.issue(modw, D / 32, mf0, 0, lane);
-  gm.run(sg, AS, acc, lane);
   const int l16 = lane & 15, lg = lane >> 4;
+  // output tiles of 256 features (16 fragment rows) are dealt to blockIdx.x round-robin
+  for (int ft = blockIdx.x; ft * 256 < Nm; ft += gridDim.x) {
+    const int mf0 = ft * 16 + wave * MB;
+    f32x4 acc[MB][NB];
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb) {
-    const int f0 = (mf0 + mb) * 16 + lg * 4;
-    const f32x4 b = *reinterpret_cast<const f32x4*>(modb + f0);
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) {
-      const int row = row0 + nb * 16 + l16;
-      if (row < R) *reinterpret_cast<f32x4*>(mod + (size_t)row * Nm + f0) = acc[mb][nb] + b;
+      for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
+    FragGemm<MB, NB, D / 32> gm;
+    gm.issue(modw, D / 32, mf0, 0, lane);
+    gm.run(sg, AS, acc, lane);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const int f0 = (mf0 + mb) * 16 + lg * 4;
+      const f32x4 b = *reinterpret_cast<const f32x4*>(modb + f0);
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const int row = row0 + nb * 16 + l16;
+        if (row < R) *reinterpret_cast<f32x4*>(mod + (size_t)row * Nm + f0) = acc[mb][nb] + b;
+      }
     }
+    asm volatile("" : "+v"(lane));
   }
 }
 

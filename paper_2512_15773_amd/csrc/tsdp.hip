@@ -72,6 +72,10 @@ struct tsdp_ctx {
   int32_t *row_ptr = nullptr, *row_t = nullptr, *row_env = nullptr, *t_next = nullptr, *n_acc = nullptr, *n_adv = nullptr;
   float *states = nullptr, *eps_p = nullptr, *eps_q = nullptr, *xi = nullptr, *y_last = nullptr;
   std::vector<void*> owned;
+  // optional kernel timing: events recorded around the dominant kernel of each stage
+  bool timing = false;
+  hipEvent_t ev[3][2] = {{nullptr, nullptr}, {nullptr, nullptr}, {nullptr, nullptr}};   // draft, verify, accept
+  bool ev_used[3] = {false, false, false};
 };
 
 namespace {
@@ -79,6 +83,13 @@ namespace {
 int fail(tsdp_ctx* c, int code, const std::string& msg) {
   if (c) c->err = msg;
   return code;
+}
+
+inline void tick(tsdp_ctx* c, int stage, int edge, hipStream_t s) {
+  if (c->timing) {
+    (void)hipEventRecord(c->ev[stage][edge], s);
+    c->ev_used[stage] = true;
+  }
 }
 
 #define HIPCHK(c, expr)                                                                         \
@@ -164,7 +175,9 @@ template <int D>
 void launch_mod(const FusedNet& n, const int32_t* t_arr, int t_sub, const int32_t* env_arr, int T, const int32_t* d_R,
                 int R_cap, float* mod, hipStream_t s) {
   const int Nm = n.L * 4 * D;                           // a multiple of 256 because D is a multiple of 64
-  dim3 g(Nm / 256, (R_cap + 127) / 128);
+  const int row_tiles = (R_cap + 127) / 128;
+  const int fx = std::max(1, std::min(Nm / 256, (768 + row_tiles - 1) / row_tiles));   // about three workgroups per CU
+  dim3 g(fx, row_tiles);
   hipLaunchKernelGGL(k_mod_gemm<D>, g, dim3(256), 0, s, n.modw, n.modb, n.temb, n.cemb, t_arr, t_sub, env_arr, T, Nm, d_R,
                      R_cap, mod);
 }
@@ -370,7 +383,10 @@ void forward(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t*
   n.fused_mod(n.fnet, t_arr, t_sub, env_arr, cf.T, d_R, R_cap, c->mod, s);
   FusedIO io;
   io.x_rows = x_rows; io.mod = c->mod; io.row_env = env_arr; io.d_R = d_R; io.R_cap = R_cap; io.eps_out = eps_out;
+  const int stage = (&n == &c->net[0]) ? 1 : -1;          // only the base network's forward is the verify stage
+  if (stage == 1) tick(c, 1, 0, s);
   n.fused_verify(n.fnet, io, cf.A, R_cap, s);
+  if (stage == 1) tick(c, 1, 1, s);
 }
 
 // dynamic LDS of the persistent drafter kernel for `rpt` environments per workgroup (mirrors launch_draft)
@@ -493,6 +509,9 @@ int tsdp_create(const tsdp_config* cfg, tsdp_ctx** out) {
 void tsdp_destroy(tsdp_ctx* c) {
   if (!c) return;
   (void)hipDeviceSynchronize();
+  for (auto& st : c->ev)
+    for (auto& e : st)
+      if (e) (void)hipEventDestroy(e);
   for (void* p : c->owned) (void)hipFree(p);
   delete c;
 }
@@ -633,7 +652,9 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
       io.tb = {c->tb.sqrt_abar, c->tb.sqrt_1m, c->tb.c0, c->tb.cx, c->tb.sigma, c->tb.T};
       io.clip = cf.clip_x0; io.clip_val = cf.clip_val; io.seed = cf.seed;
       io.y = d_y_last; io.states = d_states; io.eps_p = d_eps_p; io.xi = d_xi;
+      tick(c, 0, 0, s);
       (big ? dn.fused_draft_big : dn.fused_draft_small)(dn.fnet, io, cf.A, s);
+      tick(c, 0, 1, s);
       HIPCHK(c, hipGetLastError());
       return TSDP_OK;
     }
@@ -677,6 +698,7 @@ int tsdp_accept(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32_t* d_r
   hipStream_t s = (hipStream_t)stream;
   const tsdp_config& cf = c->cfg;
   const dim3 g((B + 3) / 4), blk(256);
+  tick(c, 2, 0, s);
   if (cf.clip_x0)
     hipLaunchKernelGGL(k_accept<true>, g, blk, 0, s, B, c->D, d_row_ptr, d_row_t, d_env_id, d_sigma_scale, d_states,
                        d_eps_p, d_eps_q, d_xi, d_y_last, c->tb, cf.clip_val, cf.seed, d_x_out, d_t_next, d_n_accept,
@@ -685,6 +707,7 @@ int tsdp_accept(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32_t* d_r
     hipLaunchKernelGGL(k_accept<false>, g, blk, 0, s, B, c->D, d_row_ptr, d_row_t, d_env_id, d_sigma_scale, d_states,
                        d_eps_p, d_eps_q, d_xi, d_y_last, c->tb, cf.clip_val, cf.seed, d_x_out, d_t_next, d_n_accept,
                        d_n_adv, d_flags, d_logratio, d_logu);
+  tick(c, 2, 1, s);
   HIPCHK(c, hipGetLastError());
   return TSDP_OK;
 }
@@ -714,6 +737,25 @@ int tsdp_status(tsdp_ctx* c, void* stream, int32_t* h_status) {
   HIPCHK(c, hipStreamSynchronize(s));
   // cleared with a tiny fill kernel-free path: a synchronous memset outside any capture
   HIPCHK(c, hipMemset(c->status, 0, sizeof(int32_t)));
+  return TSDP_OK;
+}
+
+int tsdp_kernel_timing(tsdp_ctx* c, int enable) {
+  if (!c) return TSDP_E_INVAL;
+  if (enable && !c->ev[0][0]) {
+    for (auto& st : c->ev)
+      for (auto& e : st) HIPCHK(c, hipEventCreate(&e));
+  }
+  c->timing = enable != 0;
+  for (bool& u : c->ev_used) u = false;
+  return TSDP_OK;
+}
+
+int tsdp_kernel_ms(tsdp_ctx* c, int stage, float* h_ms) {
+  if (!c || !h_ms || stage < 0 || stage > 2) return TSDP_E_INVAL;
+  if (!c->ev[0][0] || !c->ev_used[stage]) return fail(c, TSDP_E_STATE, "no timed launch of that stage since timing was enabled");
+  HIPCHK(c, hipEventSynchronize(c->ev[stage][1]));
+  HIPCHK(c, hipEventElapsedTime(h_ms, c->ev[stage][0], c->ev[stage][1]));
   return TSDP_OK;
 }
 
