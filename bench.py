@@ -118,7 +118,8 @@ def accept_xl(torch, Tsdp, dev, iters=20):
                 eps_p=0.3 * torch.randn(R, wl.H, wl.A, device=dev, generator=g),
                 xi=torch.randn(R, wl.H, wl.A, device=dev, generator=g),
                 y_last=torch.randn(B, wl.H, wl.A, device=dev, generator=g))
-    rows["eps_q"] = rows["eps_p"] + 0.02 * torch.randn(R, wl.H, wl.A, device=dev, generator=g)
+    # every draft passes (noise predictions agree to 1e-4): all rows are needed, the kernel's largest traffic
+    rows["eps_q"] = rows["eps_p"] + 1e-4 * torch.randn(R, wl.H, wl.A, device=dev, generator=g)
     t0 = torch.randint(K, wl.T, (B,), device=dev, generator=g, dtype=torch.int32)
     rows["row_t"] = (t0.repeat_interleave(K) - torch.arange(K, device=dev, dtype=torch.int32).repeat(B)).contiguous()
     s = torch.ones(B, device=dev)
@@ -132,11 +133,11 @@ def accept_xl(torch, Tsdp, dev, iters=20):
         ts.append(ctx.tsdp_kernel_ms(2))
     ctx.tsdp_kernel_timing(False)
     ms = float(np.mean(ts))
-    alg = 3 * R * D * 4 + B * (3 * D * 4 + 12)       # eps_p, eps_q, xi per row; one state or y row read, x written per env
+    alg = 3 * R * D * 4 + B * (2 * D * 4 + 12)       # eps_p, eps_q, xi per row; y_last read and x written per env
     acc = float(out["n_accept"].float().mean().item())
     ctx.close()
     del flush
-    return {"kernel": "k_accept", "shape": f"B={B} K={K} D={D} fp32 ({R} rows)", "bound": "hbm",
+    return {"kernel": "k_accept", "shape": f"B={B} K={K} D={D} fp32 ({R} rows), all drafts accepted", "bound": "hbm",
             "achieved": alg / (ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
             "frac": alg / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "traffic": None, "ms": ms,
             "algorithmic_bytes": alg, "mean_accepted_drafts": acc}

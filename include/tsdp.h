@@ -23,7 +23,7 @@
  *  - Ragged row table: environment b owns rows row_ptr[b] .. row_ptr[b+1]-1; row row_ptr[b]+k-1 holds the
  *    input state y_{k-1} of drafted transition k at timestep t0[b]-k+1.  K_eff = min(K, t0).  An
  *    environment at t0 = 0 owns one row (the deterministic last base step); a finished one owns none.
- *  - H*A must be a multiple of 4.  The context owns weights, tables and workspace; calls on one
+ *  - H*A must be a multiple of 4 and at most 512.  The context owns weights, tables and workspace; calls on one
  *    context must not overlap in time (they share the workspace).
  */
 #ifndef TSDP_H

@@ -112,10 +112,18 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
-// Acceptance: one wavefront per environment.  For each of its rows the wave streams eps_p, eps_q, xi
-// (and the state when x0 is clamped), reduces |d|^2 and <d,xi> in fp64, tests log U <= log alpha, keeps
-// the first rejection, then writes the committed or reflected latent.
-template <bool CLIP>
+// sums v over the 16 lanes of a quarter wave
+__device__ __forceinline__ double group16_sum(double v) {
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// Acceptance: one wavefront per environment, four rows at a time (one row per group of 16 lanes).  Each
+// group streams eps_p, eps_q, xi (and the state when x0 is clamped) of its row with 16-byte loads, reduces
+// |d|^2 and <d,xi> in fp64 and tests log U <= log alpha; the wave keeps the first rejection and finally
+// writes the committed or the reflected latent.  All loads of a row are issued before the first use.
+template <bool CLIP, int MAXI>
 __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __restrict__ row_ptr,
                                                 const int32_t* __restrict__ row_t, const int32_t* __restrict__ env_id,
                                                 const float* __restrict__ sigma_scale, const float* __restrict__ states,
@@ -126,7 +134,8 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
                                                 int32_t* __restrict__ n_accept, int32_t* __restrict__ n_adv,
                                                 uint8_t* __restrict__ flags, float* __restrict__ logratio,
                                                 float* __restrict__ logu_out) {
-  const int lane = threadIdx.x & 63;
+  // MAXI = float4 per lane and row: rows of up to 16*MAXI*4 elements
+  const int lane = threadIdx.x & 63, grp = lane >> 4, gl = lane & 15;
   const int b = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (b >= B) return;
   const int r0 = row_ptr[b], r1 = row_ptr[b + 1];
@@ -168,46 +177,108 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
   const int env = env_id ? env_id[b] : b;
   int jstar = 0;                                    // 0 = no rejection yet; else 1-based row index
   double rej_dd = 0.0, rej_dx = 0.0;
-  for (int r = r0; r < r1; ++r) {
-    const int t = row_t[r];
+  for (int rb = r0; rb < r1 && jstar == 0; rb += 4) {
+    const int r = rb + grp;
+    const bool live = r < r1;
+    const int rr = live ? r : r1 - 1;               // idle groups re-read the last row (in bounds), result unused
+    const float4* ep = reinterpret_cast<const float4*>(eps_p + (long long)rr * D);
+    const float4* eq = reinterpret_cast<const float4*>(eps_q + (long long)rr * D);
+    const float4* zz = reinterpret_cast<const float4*>(xi + (long long)rr * D);
+    const float4* st = reinterpret_cast<const float4*>(states + (long long)rr * D);
+    float4 p[MAXI], q[MAXI], z[MAXI], y[MAXI];
+#pragma unroll
+    for (int it = 0; it < MAXI; ++it) {
+      const int i = gl + 16 * it;
+      if (i < nb) {
+        p[it] = ep[i]; q[it] = eq[i]; z[it] = zz[i];
+        if (CLIP) y[it] = st[i];
+      }
+    }
+    const int t = row_t[rr];
     const double sa = tb.sqrt_abar[t], s1 = tb.sqrt_1m[t], c0 = tb.c0[t], sig = s * (double)tb.sigma[t];
-    const float4* ep = reinterpret_cast<const float4*>(eps_p + (long long)r * D);
-    const float4* eq = reinterpret_cast<const float4*>(eps_q + (long long)r * D);
-    const float4* zz = reinterpret_cast<const float4*>(xi + (long long)r * D);
-    const float4* st = reinterpret_cast<const float4*>(states + (long long)r * D);
+    const double lu = log((double)accept_uniform(seed, env, t));
     double dd = 0.0, dx = 0.0;                      // sums of delta^2 and delta*xi, delta = x0_p - x0_q
-    for (int i = lane; i < nb; i += 64) {
-      const float4 p = ep[i], q = eq[i], z = zz[i];
-      const float pp[4] = {p.x, p.y, p.z, p.w}, qq[4] = {q.x, q.y, q.z, q.w}, zv[4] = {z.x, z.y, z.z, z.w};
-      if (CLIP) {
-        const float4 y = st[i];
-        const float yy[4] = {y.x, y.y, y.z, y.w};
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const double xp = fmin(fmax(((double)yy[j] - s1 * (double)pp[j]) / sa, -cv), cv);
-          const double xq = fmin(fmax(((double)yy[j] - s1 * (double)qq[j]) / sa, -cv), cv);
-          const double de = xp - xq;
-          dd = fma(de, de, dd); dx = fma(de, (double)zv[j], dx);
-        }
-      } else {
+    for (int it = 0; it < MAXI; ++it) {
+      if (gl + 16 * it < nb) {
+        const float pp[4] = {p[it].x, p[it].y, p[it].z, p[it].w}, qq[4] = {q[it].x, q[it].y, q[it].z, q[it].w},
+                    zv[4] = {z[it].x, z[it].y, z[it].z, z[it].w};
+        if (CLIP) {
+          const float yy[4] = {y[it].x, y[it].y, y[it].z, y[it].w};
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {               // x0_p - x0_q = -(s1/sa)(eps_p - eps_q)
-          const double de = (double)pp[j] - (double)qq[j];
-          dd = fma(de, de, dd); dx = fma(de, (double)zv[j], dx);
+          for (int j = 0; j < 4; ++j) {
+            const double xp = fmin(fmax(((double)yy[j] - s1 * (double)pp[j]) / sa, -cv), cv);
+            const double xq = fmin(fmax(((double)yy[j] - s1 * (double)qq[j]) / sa, -cv), cv);
+            const double de = xp - xq;
+            dd = fma(de, de, dd); dx = fma(de, (double)zv[j], dx);
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {             // x0_p - x0_q = -(s1/sa)(eps_p - eps_q)
+            const double de = (double)pp[j] - (double)qq[j];
+            dd = fma(de, de, dd); dx = fma(de, (double)zv[j], dx);
+          }
         }
       }
     }
-    dd = wave_sum(dd); dx = wave_sum(dx);
+    dd = group16_sum(dd); dx = group16_sum(dx);
     const double kap = CLIP ? c0 / sig : -(c0 * s1) / (sa * sig);   // d = kap * delta
     const double n2 = kap * kap * dd, ip = kap * dx;                // |d|^2, <d,xi>
     const double l = -0.5 * n2 - ip;
-    const double lu = log((double)accept_uniform(seed, env, t));
     const bool acc = lu <= l;
-    if (!acc && jstar == 0) { jstar = r - r0 + 1; rej_dd = n2; rej_dx = ip; }
-    if (lane == 0) {
+    if (live && gl == 0) {
       if (flags) flags[r] = acc ? 1 : 0;
       if (logratio) logratio[r] = (float)l;
       if (logu_out) logu_out[r] = (float)lu;
+    }
+    // first rejected row among the (up to) four of this pass
+    const unsigned long long rejmask = __ballot(live && !acc);
+    if (rejmask) {
+      const int g = (__ffsll((long long)rejmask) - 1) >> 4;
+      jstar = rb + g - r0 + 1;
+      rej_dd = __shfl(n2, g * 16); rej_dx = __shfl(ip, g * 16);
+      if (flags || logratio || logu_out) {          // diagnostics cover every row: finish the remaining passes
+        for (int r2 = rb + 4; r2 < r1; r2 += 4) {
+          const int q2 = r2 + grp;
+          if (q2 < r1) {
+            const int t2 = row_t[q2];
+            const double sa2 = tb.sqrt_abar[t2], s12 = tb.sqrt_1m[t2], c02 = tb.c0[t2], sig2 = s * (double)tb.sigma[t2];
+            const float4* ep2 = reinterpret_cast<const float4*>(eps_p + (long long)q2 * D);
+            const float4* eq2 = reinterpret_cast<const float4*>(eps_q + (long long)q2 * D);
+            const float4* zz2 = reinterpret_cast<const float4*>(xi + (long long)q2 * D);
+            const float4* st2 = reinterpret_cast<const float4*>(states + (long long)q2 * D);
+            double dd2 = 0.0, dx2 = 0.0;
+            for (int i = gl; i < nb; i += 16) {
+              const float4 a4 = ep2[i], b4 = eq2[i], c4 = zz2[i];
+              const float pp[4] = {a4.x, a4.y, a4.z, a4.w}, qq[4] = {b4.x, b4.y, b4.z, b4.w}, zv[4] = {c4.x, c4.y, c4.z, c4.w};
+              float yy[4] = {0, 0, 0, 0};
+              if (CLIP) { const float4 y4 = st2[i]; yy[0] = y4.x; yy[1] = y4.y; yy[2] = y4.z; yy[3] = y4.w; }
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                double de;
+                if (CLIP) {
+                  const double xp = fmin(fmax(((double)yy[j] - s12 * (double)pp[j]) / sa2, -cv), cv);
+                  const double xq = fmin(fmax(((double)yy[j] - s12 * (double)qq[j]) / sa2, -cv), cv);
+                  de = xp - xq;
+                } else {
+                  de = (double)pp[j] - (double)qq[j];
+                }
+                dd2 = fma(de, de, dd2); dx2 = fma(de, (double)zv[j], dx2);
+              }
+            }
+            // 16-lane reductions below are executed by whole groups only (q2 depends on grp, not on gl)
+            dd2 = group16_sum(dd2); dx2 = group16_sum(dx2);
+            const double kap2 = CLIP ? c02 / sig2 : -(c02 * s12) / (sa2 * sig2);
+            const double l2 = -0.5 * kap2 * kap2 * dd2 - kap2 * dx2;
+            const double lu2 = log((double)accept_uniform(seed, env, t2));
+            if (gl == 0) {
+              if (flags) flags[q2] = lu2 <= l2 ? 1 : 0;
+              if (logratio) logratio[q2] = (float)l2;
+              if (logu_out) logu_out[q2] = (float)lu2;
+            }
+          }
+        }
+      }
     }
   }
   const int K_eff = r1 - r0;

@@ -459,7 +459,7 @@ int tsdp_create(const tsdp_config* cfg, tsdp_ctx** out) {
   auto bad = [&](int d, int heads, int L, int mr) {
     return L < 1 || L > 64 || d < 8 || d > 1024 || d % 4 || heads < 1 || d % heads || (d / heads) > 128 || mr < 1 || mr > 8;
   };
-  if (f.dtype < 0 || f.dtype > 1 || f.H < 1 || f.H > 64 || f.A < 1 || f.A > 64 || (f.H * f.A) % 4 || f.cond_mode < 0 ||
+  if (f.dtype < 0 || f.dtype > 1 || f.H < 1 || f.H > 64 || f.A < 1 || f.A > 64 || (f.H * f.A) % 4 || f.H * f.A > 512 || f.cond_mode < 0 ||
       f.cond_mode > 1 || f.cond_dim < 4 || f.cond_dim % 4 || (f.cond_mode == 1 && (f.cond_tokens < 1 || f.cond_tokens > 256)) ||
       bad(f.base_d, f.base_heads, f.base_layers, f.base_mlp_ratio) ||
       bad(f.draft_d, f.draft_heads, f.draft_layers, f.draft_mlp_ratio) || f.T < 1 || f.T > 4096 || f.schedule < 0 ||
@@ -697,16 +697,23 @@ int tsdp_accept(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32_t* d_r
   if (B == 0) return TSDP_OK;
   hipStream_t s = (hipStream_t)stream;
   const tsdp_config& cf = c->cfg;
-  const dim3 g((B + 3) / 4), blk(256);
+  const int wpb = 4;                                // environments (wavefronts) per workgroup
+  const dim3 g((B + wpb - 1) / wpb), blk(64 * wpb);
   tick(c, 2, 0, s);
-  if (cf.clip_x0)
-    hipLaunchKernelGGL(k_accept<true>, g, blk, 0, s, B, c->D, d_row_ptr, d_row_t, d_env_id, d_sigma_scale, d_states,
-                       d_eps_p, d_eps_q, d_xi, d_y_last, c->tb, cf.clip_val, cf.seed, d_x_out, d_t_next, d_n_accept,
-                       d_n_adv, d_flags, d_logratio, d_logu);
-  else
-    hipLaunchKernelGGL(k_accept<false>, g, blk, 0, s, B, c->D, d_row_ptr, d_row_t, d_env_id, d_sigma_scale, d_states,
-                       d_eps_p, d_eps_q, d_xi, d_y_last, c->tb, cf.clip_val, cf.seed, d_x_out, d_t_next, d_n_accept,
-                       d_n_adv, d_flags, d_logratio, d_logu);
+  const int maxi = (c->D / 4 + 15) / 16;            // float4 per lane and row, 1..8 (H*A <= 512 is checked at create)
+#define TSDP_ACCEPT(CL, MI)                                                                                     \
+  hipLaunchKernelGGL((k_accept<CL, MI>), g, blk, 0, s, B, c->D, d_row_ptr, d_row_t, d_env_id, d_sigma_scale,   \
+                     d_states, d_eps_p, d_eps_q, d_xi, d_y_last, c->tb, cf.clip_val, cf.seed, d_x_out, d_t_next, \
+                     d_n_accept, d_n_adv, d_flags, d_logratio, d_logu)
+#define TSDP_ACCEPT_MI(MI) \
+  case MI: if (cf.clip_x0) TSDP_ACCEPT(true, MI); else TSDP_ACCEPT(false, MI); break;
+  switch (maxi) {
+    TSDP_ACCEPT_MI(1) TSDP_ACCEPT_MI(2) TSDP_ACCEPT_MI(3) TSDP_ACCEPT_MI(4)
+    TSDP_ACCEPT_MI(5) TSDP_ACCEPT_MI(6) TSDP_ACCEPT_MI(7) TSDP_ACCEPT_MI(8)
+    default: return fail(c, TSDP_E_SHAPE, "H*A above 512 is not supported by the acceptance kernel");
+  }
+#undef TSDP_ACCEPT_MI
+#undef TSDP_ACCEPT
   tick(c, 2, 1, s);
   HIPCHK(c, hipGetLastError());
   return TSDP_OK;
