@@ -81,6 +81,8 @@ __device__ __forceinline__ float gelu_fast(float x) {
   return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(w));
 }
 
+__device__ __forceinline__ float silu_fast(float g) { return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)); }
+
 __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
   bf16x4 r;
   r[0] = (__bf16)v[0]; r[1] = (__bf16)v[1]; r[2] = (__bf16)v[2]; r[3] = (__bf16)v[3];
@@ -695,7 +697,7 @@ __global__ __launch_bounds__(256) void k_fused_draft(FusedNet net, DraftIO io, i
       t = t < 0 ? 0 : t;
       float g = net.temb[(size_t)t * D + c];
       if (net.cemb) g += net.cemb[(size_t)envs[r] * D + c];
-      sgbuf[r * (D + 8) + c] = (__bf16)(g / (1.0f + __expf(-g)));
+      sgbuf[r * (D + 8) + c] = (__bf16)silu_fast(g);
     }
     __syncthreads();
     {
@@ -781,7 +783,7 @@ __global__ __launch_bounds__(256) void k_mod_gemm(const bf16x8* __restrict__ mod
     f32x4 g = *reinterpret_cast<const f32x4*>(temb + (size_t)t * D + c);
     if (cemb) g += *reinterpret_cast<const f32x4*>(cemb + (size_t)(env_arr ? env_arr[row] : row) * D + c);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) g[j] = g[j] * __builtin_amdgcn_rcpf(1.0f + __expf(-g[j]));
+    for (int j = 0; j < 4; ++j) g[j] = silu_fast(g[j]);
     *reinterpret_cast<bf16x4*>(sg + r * AS + c) = to_bf16x4(g);
   }
   __syncthreads();

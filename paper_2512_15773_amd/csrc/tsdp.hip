@@ -628,6 +628,7 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
                int32_t* d_row_env, float* d_states, float* d_eps_p, float* d_xi, float* d_y_last, void* stream) {
   int rc = check_ready(c, B, true);
   if (rc) return rc;
+  if (B == 0) return TSDP_OK;                        // an empty batch is valid and touches nothing
   if (!d_x || !d_t0 || !d_K || !d_sigma_scale || !d_row_ptr || !d_row_t || !d_row_env || !d_states || !d_eps_p ||
       !d_xi || !d_y_last)
     return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_draft");
@@ -674,6 +675,7 @@ int tsdp_verify(tsdp_ctx* c, int B, int R_cap, const int32_t* d_row_ptr, const i
                 const int32_t* d_row_env, const float* d_states, float* d_eps_q, void* stream) {
   int rc = check_ready(c, B, true);
   if (rc) return rc;
+  if (B == 0 || R_cap == 0) return TSDP_OK;
   if (!d_row_ptr || !d_row_t || !d_row_env || !d_states || !d_eps_q)
     return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_verify");
   if (R_cap < 0 || (long long)R_cap > (long long)c->cfg.B_max * c->cfg.K_max)
@@ -691,6 +693,7 @@ int tsdp_accept(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32_t* d_r
                 int32_t* d_n_adv, uint8_t* d_flags, float* d_logratio, float* d_logu, void* stream) {
   int rc = check_ready(c, B, false);
   if (rc) return rc;
+  if (B == 0) return TSDP_OK;
   if (!d_row_ptr || !d_row_t || !d_sigma_scale || !d_states || !d_eps_p || !d_eps_q || !d_xi || !d_y_last || !d_x_out ||
       !d_t_next || !d_n_accept)
     return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_accept");
@@ -723,6 +726,7 @@ int tsdp_round(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K,
                const int32_t* d_env_id, int32_t* d_n_accept, int32_t* d_n_advanced, void* stream) {
   int rc = check_ready(c, B, true);
   if (rc) return rc;
+  if (B == 0) return TSDP_OK;
   if (!d_x || !d_t || !d_K || !d_sigma_scale) return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_round");
   if (B == 0) return TSDP_OK;
   if ((rc = ensure_round_buffers(c))) return rc;

@@ -1,0 +1,156 @@
+"""GPU parity at the full BASELINE sizes, in the launch configuration bench.py times: the whole batch runs
+on the GPU, the CPU oracle recomputes a sample of environments / rows one by one (needs an MI355X)."""
+import numpy as np
+import pytest
+
+import bench
+import tsdp_inputs as ti
+from oracle import spec_round as sr
+from tests.helpers import gpu_side, oracle_side, scaled_err, to_dev
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"fp32": 1e-5, "bf16": 2e-2}            # error relative to the tensor scale, as in test_gpu_parity.py
+SAMPLES = {"C2": [0], "C3": [0, 7, 31, 63], "C4": [0, 129, 255], "C5": [0, 3, 500, 777, 1023]}
+
+
+def _full(name, point="calibrated"):
+    wl = ti.WORKLOADS[name]
+    wb, wd, cond, x, t0, K, s = bench.make_problem(wl, point)
+    base, drafter, sched = oracle_side(wl, wb, wd)
+    ctx = gpu_side(wl, wb, wd, cond)
+    return wl, dict(cond=cond, x=x, t0=t0, K=K, s=s, base=base, drafter=drafter, sched=sched, ctx=ctx)
+
+
+@pytest.mark.parametrize("name", ["C2", "C3", "C4", "C5"])
+def test_full_size_stages_on_sampled_environments(name):
+    wl, S = _full(name)
+    ctx, B = S["ctx"], wl.B
+    if wl.dtype == "bf16":
+        assert ctx.path_name(0) == "bf16-mfma-fused" and ctx.path_name(1) == "bf16-mfma-fused"
+    rows = ctx.alloc_rows(B)
+    sd = to_dev(S["s"])
+    ctx.tsdp_draft(to_dev(S["x"]), to_dev(S["t0"]), to_dev(S["K"]), sd, None, rows)
+    ctx.tsdp_verify(B, rows)
+    out = ctx.tsdp_accept(B, sd, None, rows)
+    g = {k: v.cpu().numpy() for k, v in {**rows, **out}.items()}
+    K_eff, row_ptr, row_env, row_t = sr.plan_rows(S["t0"], S["K"])
+    R = int(row_ptr[-1])
+    np.testing.assert_array_equal(g["row_ptr"], row_ptr)               # the row table is exact at any size
+    np.testing.assert_array_equal(g["row_t"][:R], row_t)
+    np.testing.assert_array_equal(g["row_env"][:R], row_env)
+    tol = TOL[wl.dtype]
+    envs = np.array(SAMPLES[name])
+    # drafter rollout of the sampled environments (environments are independent, noise is keyed by env id)
+    o = sr.draft(S["drafter"], S["sched"], S["x"][envs], S["t0"][envs], S["K"][envs], S["s"][envs], envs,
+                 wl.philox_seed, S["cond"][envs])
+    for j, b in enumerate(envs):
+        gs = slice(row_ptr[b], row_ptr[b + 1]); os_ = slice(o["row_ptr"][j], o["row_ptr"][j + 1])
+        np.testing.assert_allclose(g["xi"][gs], o["xi"][os_], rtol=1e-5, atol=2e-6)
+        for nm in ("states", "eps_p"):
+            e = scaled_err(g[nm][gs], o[nm][os_])
+            assert e < tol, (nm, int(b), e)
+        assert scaled_err(g["y_last"][b], o["y_last"][j]) < tol
+        # verification of the GPU's own states of that environment
+        ref = sr.verify(S["base"], np.full(gs.stop - gs.start, b), g["row_t"][gs], g["states"][gs], S["cond"])
+        e = scaled_err(g["eps_q"][gs], ref)
+        print(f"[{name}] env {int(b)}: verify scaled err {e:.3e}")
+        assert e < tol, ("eps_q", int(b), e)
+    # acceptance on the GPU's own tensors, every environment (the oracle's accept is cheap): indices bit-exact
+    ref = sr.accept(S["sched"], row_ptr, row_t, S["s"], None, wl.philox_seed, g["states"][:R], g["eps_p"][:R],
+                    g["eps_q"][:R], g["xi"][:R], g["y_last"])
+    near = np.abs(ref["logu"] - ref["logratio"]) < 1e-9
+    assert not np.any((g["flags"][:R] != ref["flags"]) & ~near)
+    ok = np.array([not np.any(near[row_ptr[b]:row_ptr[b + 1]]) for b in range(B)])
+    for k in ("n_accept", "n_adv", "t_next"):
+        np.testing.assert_array_equal(g[k][ok], ref[k][ok])
+    np.testing.assert_allclose(g["x_out"][ok], ref["x_out"][ok], rtol=1e-5, atol=1e-6)
+    ctx.close()
+
+
+@pytest.mark.parametrize("name", ["C3", "C5"])
+def test_full_size_bf16_round_against_oracle_round(name):
+    """End-to-end bf16 round: accept decisions may differ from the fp64 oracle only on rows whose margin
+    |log U - log alpha| is inside the error the bf16 networks put on log alpha; environments whose first
+    rejection agrees end within the bf16 tolerance."""
+    import torch
+    wl, S = _full(name)
+    ctx, B = S["ctx"], wl.B
+    rows = ctx.alloc_rows(B)
+    sd = to_dev(S["s"])
+    ctx.tsdp_draft(to_dev(S["x"]), to_dev(S["t0"]), to_dev(S["K"]), sd, None, rows)
+    ctx.tsdp_verify(B, rows)
+    out = ctx.tsdp_accept(B, sd, None, rows)
+    x = to_dev(S["x"]); t = to_dev(S["t0"])
+    nacc = torch.zeros(B, dtype=torch.int32, device="cuda"); nadv = torch.zeros_like(nacc)
+    ctx.tsdp_round(x, t, to_dev(S["K"]), sd, None, nacc, nadv)
+    # the fused round is the three stages on context-owned buffers: identical results
+    np.testing.assert_array_equal(nacc.cpu().numpy(), out["n_accept"].cpu().numpy())
+    np.testing.assert_array_equal(t.cpu().numpy(), out["t_next"].cpu().numpy())
+    np.testing.assert_array_equal(x.cpu().numpy(), out["x_out"].cpu().numpy())
+    envs = np.array(SAMPLES[name])
+    ref = sr.spec_round(S["base"], S["drafter"], S["sched"], S["x"][envs], S["t0"][envs], S["K"][envs], S["s"][envs],
+                        envs, wl.philox_seed, S["cond"][envs])
+    row_ptr = rows["row_ptr"].cpu().numpy()
+    gl, gf = out["logratio"].cpu().numpy(), out["flags"].cpu().numpy()
+    agree = 0
+    for j, b in enumerate(envs):
+        gs = slice(row_ptr[b], row_ptr[b + 1]); os_ = slice(ref["draft"]["row_ptr"][j], ref["draft"]["row_ptr"][j + 1])
+        # rows up to the oracle's first rejection saw (nearly) the same states on both sides
+        n = min(int(ref["n_accept"][j]) + 1, os_.stop - os_.start)
+        dl = np.abs(gl[gs][:n] - ref["logratio"][os_][:n])
+        margin = np.abs(ref["logu"][os_][:n] - ref["logratio"][os_][:n])
+        mism = gf[gs][:n] != ref["flags"][os_][:n]
+        assert np.all(margin[mism] <= dl[mism] + 1e-5), (int(b), margin[mism], dl[mism])
+        assert dl.max() < 0.5, (int(b), dl.max())                     # bf16 error on log alpha stays a fraction of a nat
+        if not mism.any():
+            agree += 1
+            assert int(nacc[b]) == ref["n_accept"][j] and int(t[b]) == ref["t_next"][j]
+            assert scaled_err(x[b].cpu().numpy(), ref["x_out"][j]) < TOL["bf16"]
+    print(f"[{name}] sampled envs with identical accept decisions: {agree}/{len(envs)}")
+    assert agree >= len(envs) - 2
+    ctx.close()
+
+
+def test_identity_drafter_accepts_every_draft_on_the_gpu():
+    # drafter == base => mu_p == mu_q => all K_eff drafts pass and the round equals K_eff base DDPM steps
+    import torch
+    wl = ti.small_variant(ti.C3, B=8, draft=ti.C3.base)
+    wb = ti.make_weights(wl, "base", b_std=0.02)
+    cond, x = ti.make_cond(wl, 8), ti.make_latents(wl, 8)
+    ctx = gpu_side(wl, wb, wb, cond)
+    t0 = np.array([99, 50, 20, 16, 15, 3, 0, -1], np.int32); K = np.full(8, 16, np.int32); s = np.ones(8, np.float32)
+    xd, td = to_dev(x), to_dev(t0)
+    nacc = torch.zeros(8, dtype=torch.int32, device="cuda"); nadv = torch.zeros_like(nacc)
+    ctx.tsdp_round(xd, td, to_dev(K), to_dev(s), None, nacc, nadv)
+    keff = np.minimum(K, np.maximum(t0, 0))
+    np.testing.assert_array_equal(nacc.cpu().numpy(), keff)
+    np.testing.assert_array_equal(nadv.cpu().numpy(), [16, 16, 16, 16, 15, 3, 1, 0])
+    np.testing.assert_array_equal(td.cpu().numpy(), [83, 34, 4, 0, 0, 0, -1, -1])
+    ctx.close()
+
+
+def test_round_is_deterministic_and_handles_empty_and_finished_batches():
+    import torch
+    wl = ti.small_variant(ti.C5, B=37)
+    wb, wd = ti.make_weights(wl, "base"), ti.make_weights(wl, "draft")
+    cond, x = ti.make_cond(wl, 37), ti.make_latents(wl, 37)
+    t0, K, s = ti.make_schedule_inputs(wl, 37)
+    ctx = gpu_side(wl, wb, wd, cond)
+    res = []
+    for _ in range(2):
+        xd, td = to_dev(x), to_dev(t0)
+        nacc = torch.zeros(37, dtype=torch.int32, device="cuda"); nadv = torch.zeros_like(nacc)
+        ctx.tsdp_round(xd, td, to_dev(K), to_dev(s), None, nacc, nadv)
+        res.append((xd.cpu().numpy().tobytes(), td.cpu().numpy().tobytes(), nacc.cpu().numpy().tobytes()))
+    assert res[0] == res[1]
+    # all environments finished: nothing runs, latents and counters pass through
+    xd, td = to_dev(x), to_dev(np.full(37, -1, np.int32))
+    nacc = torch.full((37,), 7, dtype=torch.int32, device="cuda"); nadv = torch.full((37,), 7, dtype=torch.int32, device="cuda")
+    ctx.tsdp_round(xd, td, to_dev(K), to_dev(s), None, nacc, nadv)
+    np.testing.assert_array_equal(xd.cpu().numpy(), x)
+    assert int(nacc.sum()) == 0 and int(nadv.sum()) == 0 and (td.cpu().numpy() == -1).all()
+    # B = 0 is accepted and does nothing
+    e = torch.zeros(0, wl.H, wl.A, device="cuda"); ei = torch.zeros(0, dtype=torch.int32, device="cuda")
+    ctx.tsdp_round(e, ei, ei, torch.zeros(0, device="cuda"), None, None, None)
+    ctx.close()
