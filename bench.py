@@ -27,6 +27,9 @@ CALIBRATED_HEAD_SCALE = {"C1": 0.7, "C2": 0.15, "C3": 0.21, "C4": 0.12, "C5": 0.
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3       # MI355X fp32 vector
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+# HBM bytes per launch of the fused verify forward (FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy), from the
+# rocprofv3 --pmc runs summarised in profiles/verify_forward_hbm_traffic_c4_c5.txt
+MEASURED_TRAFFIC_BYTES = {"C4": int((4.328 + 0.003) * 2 ** 30), "C5": int((2.249 + 0.014) * 2 ** 30)}
 
 
 def verify_flops(wl, R):
@@ -256,7 +259,8 @@ def main():
                        "accept": {"mean": t_accept[0], "p50": t_accept[1], "p95": t_accept[2]},
                        "drafter_kernel": kd_ms},
         "roofline": {"kernel": kname, "bound": "mfma" if bf16 else "alu", "achieved": achieved, "peak": peak,
-                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None, "kernel_ms": k_ms,
+                     "unit": "TFLOP/s", "frac": achieved / peak,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if fused else None, "kernel_ms": k_ms,
                      "kernel_ms_median": k_med, "kernel_ms_last_timed_step": last_verify_kernel_ms,
                      "algorithmic_flops_per_launch": flops},
     }
