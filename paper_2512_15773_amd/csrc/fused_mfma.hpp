@@ -196,7 +196,16 @@ struct FusedCfg {
   static constexpr int QKV_B = 2 * Q_B + VT_B;
   static constexpr int U_B = NT * US * 2;
   static constexpr int XT_B = NT * 64 * 4;              // fp32 latent staging of the verify kernel (A <= 64)
-  static constexpr int SCR0_B = QKV_B > U_B ? QKV_B : U_B;
+  // two hidden-chunk buffers (one barrier per chunk instead of two) when a single workgroup owns the CU's LDS
+#ifndef TSDP_UDB_OK
+#define TSDP_UDB_OK 1
+#endif
+#ifndef TSDP_XLOAD_EARLY
+#define TSDP_XLOAD_EARLY 0   /* requesting the cross-attention operands a phase early costs more registers than it hides */
+#endif
+  static constexpr bool UDB = TSDP_UDB_OK && (NW == 8) && (ACT_B + 2 * U_B + 2 * NW * NT * 4 <= 160 * 1024) && (2 * U_B >= QKV_B);
+  static constexpr int UU_B = UDB ? 2 * U_B : U_B;
+  static constexpr int SCR0_B = QKV_B > UU_B ? QKV_B : UU_B;
   static constexpr int SCR_B = SCR0_B > XT_B ? SCR0_B : XT_B;
   static constexpr int RED_B = 2 * NW * NT * 4;
   static constexpr int LDS_B = ACT_B + SCR_B + RED_B;   // body; the drafter kernel appends its own regions
@@ -379,27 +388,31 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
     }
   };
 
-  // attention of query fragment qf of (row, head) over the SX observation tokens of the row's environment;
-  // keys and transposed values come from global memory already in MFMA fragment order
-  auto cross_attention = [&](int r, int hh, int qf, int layer, int head) {
+  // Cross-attention of query fragment qf of (row, head) over the SX observation tokens of the row's environment.
+  // Keys and transposed values come from global memory already in MFMA fragment order; cross_load requests them
+  // (it needs nothing from this phase, so it runs before the query projection) and cross_attend consumes them.
+  constexpr int SFc = SF > 0 ? SF : 1;
+  auto cross_load = [&](int r, int layer, int head, bf16x8 (&ka)[DH / 32][SFc], bf16x4 (&va)[DH / 16][SFc]) {
     if constexpr (CM == 1) {
-      __bf16* qp = qbuf + (hh * NT + r * H + qf * 16) * QS;
       const size_t eh = ((size_t)env_of_row[r] * net.L + layer) * HEADS + head;
       const bf16x8* kcp = net.kc + eh * (SF * (DH / 32)) * 64 + lane;
       const bf16x4* vcp = net.vct + eh * ((DH / 16) * SF) * 64 + lane;
-      bf16x8 ka[DH / 32][SF];
 #pragma unroll
       for (int ks = 0; ks < DH / 32; ++ks)
 #pragma unroll
         for (int kf = 0; kf < SF; ++kf) ka[ks][kf] = kcp[(kf * (DH / 32) + ks) * 64];
-      f32x4 s[SF];
-#pragma unroll
-      for (int kf = 0; kf < SF; ++kf) s[kf] = f32x4{0, 0, 0, 0};
-      bf16x4 va[DH / 16][SF];
 #pragma unroll
       for (int cf = 0; cf < DH / 16; ++cf)
 #pragma unroll
         for (int kf = 0; kf < SF; ++kf) va[cf][kf] = vcp[(cf * SF + kf) * 64];
+    }
+  };
+  auto cross_attend = [&](int r, int hh, int qf, const bf16x8 (&ka)[DH / 32][SFc], const bf16x4 (&va)[DH / 16][SFc]) {
+    if constexpr (CM == 1) {
+      __bf16* qp = qbuf + (hh * NT + r * H + qf * 16) * QS;
+      f32x4 s[SF];
+#pragma unroll
+      for (int kf = 0; kf < SF; ++kf) s[kf] = f32x4{0, 0, 0, 0};
 #pragma unroll
       for (int ks = 0; ks < DH / 32; ++ks) {
         const bf16x8 qb = *reinterpret_cast<const bf16x8*>(qp + l16 * QS + ks * 32 + lg * 8);
@@ -500,10 +513,17 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
     if constexpr (CM == 1) {
       GC gc;
       if (XPF) gc.issue(W.cq, D / 32, wave * MBC, 0, lane);
+      TSDP_TICK(11)
       write_ln(layer, -1);                               // its barriers order the O-projection reads before qbuf writes
+      TSDP_TICK(0)
       for (int g = 0; g < NG; ++g) {
         TSDP_FENCE_IDS();
         GO go;
+        // operands of this wave's first attention task of the group: requested before the query projection
+        bf16x8 ka[DH / 32][SFc];
+        bf16x4 va[DH / 16][SFc];
+        constexpr int NTASK = RPT * HP * NKF;
+        if (TSDP_XLOAD_EARLY && wave < NTASK) cross_load((wave / NKF) % RPT, layer, g * HP + wave / (NKF * RPT), ka, va);
         {
           f32x4 acc[MBC][NB];
           f32x4 bias[MBC];
@@ -515,8 +535,10 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
           }
           if (!XPF) gc.issue(W.cq, D / 32, g * (HP * DH / 16) + wave * MBC, 0, lane);
           gc.run(act, AS, acc, lane);
+          TSDP_TICK(1)
           if (XPF) go.issue(W.co, D / 32, wave * MBH, g * HP * DH / 32, lane);
           if (g > 0) __syncthreads();
+          TSDP_TICK(2)
 #pragma unroll
           for (int mb = 0; mb < MBC; ++mb) {
             const int lr = (wave * MBC + mb) * 16, hh = lr / DH, c0 = lr % DH + lg * 4;
@@ -525,13 +547,18 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
               *reinterpret_cast<bf16x4*>(qbuf + (hh * NT + nb * 16 + l16) * QS + c0) = to_bf16x4(acc[mb][nb] + bias[mb]);
           }
         }
+        TSDP_TICK(3)
         __syncthreads();
+        TSDP_TICK(2)
         if (!(TSDP_ABL & 8))
-          for (int task = wave; task < RPT * HP * NKF; task += NW) {
+          for (int task = wave; task < NTASK; task += NW) {
             const int hh = task / (NKF * RPT);
-            cross_attention((task / NKF) % RPT, hh, task % NKF, layer, g * HP + hh);
+            if (!TSDP_XLOAD_EARLY || task != wave) cross_load((task / NKF) % RPT, layer, g * HP + hh, ka, va);
+            cross_attend((task / NKF) % RPT, hh, task % NKF, ka, va);
           }
+        TSDP_TICK(10)
         __syncthreads();
+        TSDP_TICK(2)
         if (XPF && g + 1 < NG) gc.issue(W.cq, D / 32, (g + 1) * (HP * DH / 16) + wave * MBC, 0, lane);
         if (!XPF) go.issue(W.co, D / 32, wave * MBH, g * HP * DH / 32, lane);
         go.run(qbuf, QS, h, lane);
@@ -540,6 +567,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
           go.issue(W.co, D / 32, wave * MBH, (g * HP + hh) * DH / 32, lane);
           go.run(qbuf + hh * NT * QS, QS, h, lane);
         }
+        TSDP_TICK(5)
       }
       add_bias_h(W.co_b);
     }
@@ -565,8 +593,11 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         gu.run(act, AS, acc, lane);
         TSDP_TICK(6)
         if (XPF) gd.issue(W.dn, 4 * D / 32, wave * MBH, c * (CH / 32), lane);
-        if (c > 0) __syncthreads();                     // previous chunk's down-projection has read ubuf
+        // single buffer: the previous chunk's down-projection has read ubuf; double buffer: the buffer written
+        // now was last read two chunks ago, and every wave has passed a barrier since
+        if (c > 0 && !C::UDB) __syncthreads();
         TSDP_TICK(7)
+        __bf16* ub = ubuf + (C::UDB ? (c & 1) * NT * US : 0);
 #pragma unroll
         for (int mb = 0; mb < MBU; ++mb) {
           const int f0 = (wave * MBU + mb) * 16 + lg * 4;
@@ -575,7 +606,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
             f32x4 v = acc[mb][nb] + bias[mb];
 #pragma unroll
             for (int i = 0; i < 4; ++i) v[i] = (TSDP_ABL & 16) ? v[i] : gelu_fast(v[i]);
-            *reinterpret_cast<bf16x4*>(ubuf + (nb * 16 + l16) * US + f0) = to_bf16x4(v);
+            *reinterpret_cast<bf16x4*>(ub + (nb * 16 + l16) * US + f0) = to_bf16x4(v);
           }
         }
       }
@@ -588,7 +619,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       } else {
         gd.issue(W.dn, 4 * D / 32, wave * MBH, c * (CH / 32), lane);
       }
-      gd.run(ubuf, US, h, lane);
+      gd.run(ubuf + (C::UDB ? (c & 1) * NT * US : 0), US, h, lane);
       TSDP_TICK(9)
     }
     add_bias_h(W.dn_b);
@@ -621,7 +652,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   }
 #ifdef TSDP_TRACE
   TSDP_TICK(10)
-  if (blockIdx.x == 300 && lane == 0 && net.trace)
+  if (blockIdx.x == 300 && lane == 0 && net.trace && wave < 8)
     for (int i = 0; i < 12; ++i) net.trace[wave * 12 + i] = tacc_[i];
 #endif
 }
