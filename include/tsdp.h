@@ -119,6 +119,20 @@ int tsdp_round(tsdp_ctx* ctx, int B, float* d_x, int32_t* d_t, const int32_t* d_
                const float* d_sigma_scale, const int32_t* d_env_id,
                int32_t* d_n_accept, int32_t* d_n_advanced, void* stream);
 
+/* Deterministic threshold rule of Section 3.2 ("accept the draft if p_i >= lambda", p_i = min{1, exp(log alpha_i)},
+ * lambda in (0,1] chosen by the scheduler): the same arithmetic as tsdp_accept / tsdp_round with the comparison
+ * log alpha >= log lambda[b] in place of the uniform draw.  d_lambda[B] holds one threshold per environment.  The
+ * rule is not lossless with respect to the base model; the corrected sample is still the reflection of the first
+ * rejected draft.  No random number is consumed by the test (the noise xi of the drafts is unchanged). */
+int tsdp_accept_threshold(tsdp_ctx* ctx, int B, const int32_t* d_row_ptr, const int32_t* d_row_t,
+                          const float* d_sigma_scale, const float* d_lambda, const float* d_states,
+                          const float* d_eps_p, const float* d_eps_q, const float* d_xi, const float* d_y_last,
+                          float* d_x_out, int32_t* d_t_next, int32_t* d_n_accept, int32_t* d_n_adv,
+                          uint8_t* d_flags, float* d_logratio, void* stream);
+int tsdp_round_threshold(tsdp_ctx* ctx, int B, float* d_x, int32_t* d_t, const int32_t* d_K,
+                         const float* d_sigma_scale, const int32_t* d_env_id, const float* d_lambda,
+                         int32_t* d_n_accept, int32_t* d_n_advanced, void* stream);
+
 /* Synchronises `stream` and returns the device status word accumulated since the last call:
  * bit 0 = some K was outside 0..K_max (clamped), bit 1 = some t0 was >= T (treated as T-1). */
 int tsdp_status(tsdp_ctx* ctx, void* stream, int32_t* h_status);

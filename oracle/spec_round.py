@@ -120,8 +120,12 @@ def reflect(mu_p, mu_q, sig, xi):
     return (mu_q.ravel() + v - 2.0 * e * float(e @ v)).reshape(mu_q.shape)
 
 
-def accept(sched, row_ptr, row_t, sigma_scale, env_id, seed, states, eps_p, eps_q, xi, y_last, clip=None):
+def accept(sched, row_ptr, row_t, sigma_scale, env_id, seed, states, eps_p, eps_q, xi, y_last, clip=None, lam=None):
     """Acceptance test, first-rejection scan and commit / reflection for every environment.
+
+    lam = None: the lossless stochastic test U <= min(1, alpha) (Section 3.1).  lam = per-environment
+    thresholds in (0, 1]: the deterministic rule of Section 3.2, accept iff p = min(1, exp(log alpha)) >= lambda
+    (not lossless; "log U" then reports log lambda).
 
     Returns x_out [B, ...], t_next [B], n_accept [B] (accepted drafts), n_adv [B] (denoising steps
     advanced), and per-row flags / log alpha / log U.
@@ -148,10 +152,16 @@ def accept(sched, row_ptr, row_t, sigma_scale, env_id, seed, states, eps_p, eps_
     dr = np.nonzero(row_t > 0)[0]                    # drafted rows (t = 0 rows are lone base steps)
     if len(dr):
         l, _, _ = log_ratio(mu_p[dr], mu_q[dr], sig[dr], xi[dr])
-        u = philox.uniform(seed, env_id[row_env[dr]], row_t[dr])
         logratio[dr] = l
-        logu[dr] = np.log(u)
-        flags[dr] = (logu[dr] <= l).astype(np.uint8)
+        if lam is None:
+            u = philox.uniform(seed, env_id[row_env[dr]], row_t[dr])
+            logu[dr] = np.log(u)
+            flags[dr] = (logu[dr] <= l).astype(np.uint8)
+        else:
+            lam_row = np.broadcast_to(np.asarray(lam, dtype=np.float64), (B,))[row_env[dr]]
+            p = np.minimum(1.0, np.exp(l))
+            logu[dr] = np.log(lam_row)
+            flags[dr] = (p >= lam_row).astype(np.uint8)
 
     x_out = y_last.copy()
     t_next = np.full(B, -1, dtype=np.int64)
@@ -180,12 +190,12 @@ def accept(sched, row_ptr, row_t, sigma_scale, env_id, seed, states, eps_p, eps_
                 flags=flags, logratio=logratio, logu=logu)
 
 
-def spec_round(base, drafter, sched, x, t0, K, sigma_scale, env_id, seed, cond, clip=None):
+def spec_round(base, drafter, sched, x, t0, K, sigma_scale, env_id, seed, cond, clip=None, lam=None):
     """draft -> verify -> accept for a batch of environments; returns the accept dict plus the draft dict."""
     dr = draft(drafter, sched, x, t0, K, sigma_scale, env_id, seed, cond, clip)
     eps_q = verify(base, dr["row_env"], dr["row_t"], dr["states"], cond)
     ac = accept(sched, dr["row_ptr"], dr["row_t"], sigma_scale, env_id, seed,
-                dr["states"], dr["eps_p"], eps_q, dr["xi"], dr["y_last"], clip)
+                dr["states"], dr["eps_p"], eps_q, dr["xi"], dr["y_last"], clip, lam)
     ac["draft"] = dr
     ac["eps_q"] = eps_q
     return ac

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtsdp.so")
 
 EXPORTS = ["tsdp_create", "tsdp_destroy", "tsdp_load_weights", "tsdp_set_cond", "tsdp_draft", "tsdp_verify",
-           "tsdp_accept", "tsdp_round", "tsdp_status", "tsdp_kernel_timing", "tsdp_kernel_ms", "tsdp_path_name",
+           "tsdp_accept", "tsdp_round", "tsdp_accept_threshold", "tsdp_round_threshold", "tsdp_status", "tsdp_kernel_timing", "tsdp_kernel_ms", "tsdp_path_name",
            "tsdp_last_error"]
 
 
@@ -47,6 +47,8 @@ def load_library():
     lib.tsdp_verify.argtypes = [vp, i32, i32] + [vp] * 5 + [vp]
     lib.tsdp_accept.argtypes = [vp, i32] + [vp] * 16 + [vp]
     lib.tsdp_round.argtypes = [vp, i32] + [vp] * 7 + [vp]
+    lib.tsdp_accept_threshold.argtypes = [vp, i32] + [vp] * 15 + [vp]
+    lib.tsdp_round_threshold.argtypes = [vp, i32] + [vp] * 8 + [vp]
     lib.tsdp_status.argtypes = [vp, vp, C.POINTER(C.c_int32)]
     lib.tsdp_kernel_timing.argtypes = [vp, i32]
     lib.tsdp_kernel_ms.argtypes = [vp, i32, C.POINTER(C.c_float)]
@@ -176,6 +178,28 @@ class Tsdp:
                                        _ptr(rows["y_last"], torch.float32), _ptr(out["x_out"]), _ptr(out["t_next"]),
                                        _ptr(out["n_accept"]), _ptr(out.get("n_adv")), _ptr(out.get("flags")),
                                        _ptr(out.get("logratio")), _ptr(out.get("logu")), _stream(stream)))
+
+    def tsdp_accept_threshold(self, B, sigma_scale, lam, rows, stream=None):
+        dev = rows["states"].device
+        R = rows["row_t"].shape[0]
+        out = dict(x_out=torch.empty(B, self.H, self.A, dtype=torch.float32, device=dev),
+                   t_next=torch.empty(B, dtype=torch.int32, device=dev), n_accept=torch.empty(B, dtype=torch.int32, device=dev),
+                   n_adv=torch.empty(B, dtype=torch.int32, device=dev), flags=torch.zeros(R, dtype=torch.uint8, device=dev),
+                   logratio=torch.zeros(R, dtype=torch.float32, device=dev))
+        self._chk(self.lib.tsdp_accept_threshold(self.ctx, B, _ptr(rows["row_ptr"], torch.int32), _ptr(rows["row_t"], torch.int32),
+                                                 _ptr(sigma_scale, torch.float32), _ptr(lam, torch.float32),
+                                                 _ptr(rows["states"], torch.float32), _ptr(rows["eps_p"], torch.float32),
+                                                 _ptr(rows["eps_q"], torch.float32), _ptr(rows["xi"], torch.float32),
+                                                 _ptr(rows["y_last"], torch.float32), _ptr(out["x_out"]), _ptr(out["t_next"]),
+                                                 _ptr(out["n_accept"]), _ptr(out["n_adv"]), _ptr(out["flags"]),
+                                                 _ptr(out["logratio"]), _stream(stream)))
+        return out
+
+    def tsdp_round_threshold(self, x, t, K, sigma_scale, env_id, lam, n_accept=None, n_advanced=None, stream=None):
+        self._chk(self.lib.tsdp_round_threshold(self.ctx, x.shape[0], _ptr(x, torch.float32), _ptr(t, torch.int32),
+                                                _ptr(K, torch.int32), _ptr(sigma_scale, torch.float32),
+                                                _ptr(env_id, torch.int32), _ptr(lam, torch.float32),
+                                                _ptr(n_accept, torch.int32), _ptr(n_advanced, torch.int32), _stream(stream)))
 
     def tsdp_round(self, x, t, K, sigma_scale, env_id, n_accept=None, n_advanced=None, stream=None):
         self._chk(self.lib.tsdp_round(self.ctx, x.shape[0], _ptr(x, torch.float32), _ptr(t, torch.int32),

@@ -130,6 +130,7 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
                                                 const float* __restrict__ eps_p, const float* __restrict__ eps_q,
                                                 const float* __restrict__ xi, const float* __restrict__ y_last,
                                                 SchedTables tb, float clip_val, uint64_t seed,
+                                                const float* __restrict__ lambda,   // per-env threshold rule, or null
                                                 float* __restrict__ x_out, int32_t* __restrict__ t_next,
                                                 int32_t* __restrict__ n_accept, int32_t* __restrict__ n_adv,
                                                 uint8_t* __restrict__ flags, float* __restrict__ logratio,
@@ -196,7 +197,8 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
     }
     const int t = row_t[rr];
     const double sa = tb.sqrt_abar[t], s1 = tb.sqrt_1m[t], c0 = tb.c0[t], sig = s * (double)tb.sigma[t];
-    const double lu = log((double)accept_uniform(seed, env, t));
+    // stochastic test: log U;  threshold rule p = min(1, alpha) >= lambda  <=>  log alpha >= log lambda (lambda <= 1)
+    const double lu = lambda ? log((double)lambda[b]) : log((double)accept_uniform(seed, env, t));
     double dd = 0.0, dx = 0.0;                      // sums of delta^2 and delta*xi, delta = x0_p - x0_q
 #pragma unroll
     for (int it = 0; it < MAXI; ++it) {
@@ -270,7 +272,7 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
             dd2 = group16_sum(dd2); dx2 = group16_sum(dx2);
             const double kap2 = CLIP ? c02 / sig2 : -(c02 * s12) / (sa2 * sig2);
             const double l2 = -0.5 * kap2 * kap2 * dd2 - kap2 * dx2;
-            const double lu2 = log((double)accept_uniform(seed, env, t2));
+            const double lu2 = lambda ? log((double)lambda[b]) : log((double)accept_uniform(seed, env, t2));
             if (gl == 0) {
               if (flags) flags[q2] = lu2 <= l2 ? 1 : 0;
               if (logratio) logratio[q2] = (float)l2;

@@ -687,10 +687,11 @@ int tsdp_verify(tsdp_ctx* c, int B, int R_cap, const int32_t* d_row_ptr, const i
   return TSDP_OK;
 }
 
-int tsdp_accept(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32_t* d_row_t, const int32_t* d_env_id,
-                const float* d_sigma_scale, const float* d_states, const float* d_eps_p, const float* d_eps_q,
-                const float* d_xi, const float* d_y_last, float* d_x_out, int32_t* d_t_next, int32_t* d_n_accept,
-                int32_t* d_n_adv, uint8_t* d_flags, float* d_logratio, float* d_logu, void* stream) {
+static int accept_impl(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32_t* d_row_t, const int32_t* d_env_id,
+                       const float* d_sigma_scale, const float* d_lambda, const float* d_states, const float* d_eps_p,
+                       const float* d_eps_q, const float* d_xi, const float* d_y_last, float* d_x_out, int32_t* d_t_next,
+                       int32_t* d_n_accept, int32_t* d_n_adv, uint8_t* d_flags, float* d_logratio, float* d_logu,
+                       void* stream) {
   int rc = check_ready(c, B, false);
   if (rc) return rc;
   if (B == 0) return TSDP_OK;
@@ -706,7 +707,7 @@ int tsdp_accept(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32_t* d_r
   const int maxi = (c->D / 4 + 15) / 16;            // float4 per lane and row, 1..8 (H*A <= 512 is checked at create)
 #define TSDP_ACCEPT(CL, MI)                                                                                     \
   hipLaunchKernelGGL((k_accept<CL, MI>), g, blk, 0, s, B, c->D, d_row_ptr, d_row_t, d_env_id, d_sigma_scale,   \
-                     d_states, d_eps_p, d_eps_q, d_xi, d_y_last, c->tb, cf.clip_val, cf.seed, d_x_out, d_t_next, \
+                     d_states, d_eps_p, d_eps_q, d_xi, d_y_last, c->tb, cf.clip_val, cf.seed, d_lambda, d_x_out, d_t_next, \
                      d_n_accept, d_n_adv, d_flags, d_logratio, d_logu)
 #define TSDP_ACCEPT_MI(MI) \
   case MI: if (cf.clip_x0) TSDP_ACCEPT(true, MI); else TSDP_ACCEPT(false, MI); break;
@@ -722,8 +723,27 @@ int tsdp_accept(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32_t* d_r
   return TSDP_OK;
 }
 
-int tsdp_round(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
-               const int32_t* d_env_id, int32_t* d_n_accept, int32_t* d_n_advanced, void* stream) {
+int tsdp_accept(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32_t* d_row_t, const int32_t* d_env_id,
+                const float* d_sigma_scale, const float* d_states, const float* d_eps_p, const float* d_eps_q,
+                const float* d_xi, const float* d_y_last, float* d_x_out, int32_t* d_t_next, int32_t* d_n_accept,
+                int32_t* d_n_adv, uint8_t* d_flags, float* d_logratio, float* d_logu, void* stream) {
+  return accept_impl(c, B, d_row_ptr, d_row_t, d_env_id, d_sigma_scale, nullptr, d_states, d_eps_p, d_eps_q, d_xi, d_y_last,
+                     d_x_out, d_t_next, d_n_accept, d_n_adv, d_flags, d_logratio, d_logu, stream);
+}
+
+int tsdp_accept_threshold(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32_t* d_row_t,
+                          const float* d_sigma_scale, const float* d_lambda, const float* d_states, const float* d_eps_p,
+                          const float* d_eps_q, const float* d_xi, const float* d_y_last, float* d_x_out,
+                          int32_t* d_t_next, int32_t* d_n_accept, int32_t* d_n_adv, uint8_t* d_flags, float* d_logratio,
+                          void* stream) {
+  if (c && B > 0 && !d_lambda) return fail(c, TSDP_E_INVAL, "d_lambda is null");
+  return accept_impl(c, B, d_row_ptr, d_row_t, nullptr, d_sigma_scale, d_lambda, d_states, d_eps_p, d_eps_q, d_xi, d_y_last,
+                     d_x_out, d_t_next, d_n_accept, d_n_adv, d_flags, d_logratio, nullptr, stream);
+}
+
+static int round_impl(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
+                      const int32_t* d_env_id, const float* d_lambda, int32_t* d_n_accept, int32_t* d_n_advanced,
+                      void* stream) {
   int rc = check_ready(c, B, true);
   if (rc) return rc;
   if (B == 0) return TSDP_OK;
@@ -736,9 +756,21 @@ int tsdp_round(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K,
   if ((rc = tsdp_verify(c, B, B * c->cfg.K_max, c->row_ptr, c->row_t, c->row_env, c->states, c->eps_q, stream)))
     return rc;
   // x and t are overwritten in place: the acceptance kernel reads only the round's own buffers
-  return tsdp_accept(c, B, c->row_ptr, c->row_t, d_env_id, d_sigma_scale, c->states, c->eps_p, c->eps_q, c->xi,
+  return accept_impl(c, B, c->row_ptr, c->row_t, d_env_id, d_sigma_scale, d_lambda, c->states, c->eps_p, c->eps_q, c->xi,
                      c->y_last, d_x, d_t, d_n_accept ? d_n_accept : c->n_acc, d_n_advanced ? d_n_advanced : c->n_adv,
                      nullptr, nullptr, nullptr, stream);
+}
+
+int tsdp_round(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
+               const int32_t* d_env_id, int32_t* d_n_accept, int32_t* d_n_advanced, void* stream) {
+  return round_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, nullptr, d_n_accept, d_n_advanced, stream);
+}
+
+int tsdp_round_threshold(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
+                         const int32_t* d_env_id, const float* d_lambda, int32_t* d_n_accept, int32_t* d_n_advanced,
+                         void* stream) {
+  if (c && B > 0 && !d_lambda) return fail(c, TSDP_E_INVAL, "d_lambda is null");
+  return round_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, d_lambda, d_n_accept, d_n_advanced, stream);
 }
 
 int tsdp_status(tsdp_ctx* c, void* stream, int32_t* h_status) {

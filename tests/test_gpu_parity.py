@@ -217,3 +217,36 @@ def test_error_paths_return_codes():
     assert e.value.code == -2                                          # B > B_max
     ctx.tsdp_round(x, i, i, f, None)
     ctx.close()
+
+
+def test_threshold_rule_matches_oracle():
+    # deterministic p >= lambda rule (Section 3.2) on identical tensors: flags exact outside the near-tie window
+    wl = ti.small_variant(ti.C2, B=10, base=ti.NetShape(2, 256, 4))
+    S = _setup(wl, 10, head_scale=0.5)
+    rng = np.random.default_rng(4)
+    t0 = rng.integers(0, 100, 10); K = rng.integers(1, 9, 10); s = rng.uniform(1, 1.5, 10); lam = rng.uniform(0.05, 1.0, 10)
+    lam[0] = 1.0
+    rows = _gpu_draft(S, t0, K, s, None)
+    S["ctx"].tsdp_verify(10, rows)
+    out = S["ctx"].tsdp_accept_threshold(10, to_dev(s.astype(np.float32)), to_dev(lam.astype(np.float32)), rows)
+    g = {k: v.cpu().numpy() for k, v in out.items()}
+    R = int(rows["row_ptr"].cpu().numpy()[-1])
+    ref = sr.accept(S["sched"], rows["row_ptr"].cpu().numpy(), rows["row_t"].cpu().numpy()[:R], s.astype(np.float32), None,
+                    S["seed"], rows["states"].cpu().numpy()[:R], rows["eps_p"].cpu().numpy()[:R],
+                    rows["eps_q"].cpu().numpy()[:R], rows["xi"].cpu().numpy()[:R], rows["y_last"].cpu().numpy(),
+                    lam=lam.astype(np.float32))
+    near = np.abs(ref["logu"] - ref["logratio"]) < 1e-6
+    assert not np.any((g["flags"][:R] != ref["flags"]) & ~near)
+    assert not near.any()
+    for k in ("n_accept", "n_adv", "t_next"):
+        np.testing.assert_array_equal(g[k], ref[k])
+    np.testing.assert_allclose(g["x_out"], ref["x_out"], rtol=1e-5, atol=1e-6)
+    assert 0 < g["flags"][:R].sum() < R
+    # the fused round with the same thresholds gives the same counters
+    import torch
+    x = to_dev(S["x"]); t = to_dev(t0.astype(np.int32)); na = torch.zeros(10, dtype=torch.int32, device="cuda"); nd = torch.zeros_like(na)
+    S["ctx"].tsdp_round_threshold(x, t, to_dev(K.astype(np.int32)), to_dev(s.astype(np.float32)), None,
+                                  to_dev(lam.astype(np.float32)), na, nd)
+    np.testing.assert_array_equal(na.cpu().numpy(), ref["n_accept"])
+    np.testing.assert_array_equal(t.cpu().numpy(), ref["t_next"])
+    S["ctx"].close()

@@ -94,3 +94,34 @@ def test_accept_or_reflect_output_follows_the_target_law():
     # the drafted samples themselves follow the draft law, not the target: the test can tell
     zp = (out[acc] - mu_q) / sig
     assert stats.kstest(zp @ e, "norm").pvalue < 1e-6
+
+
+def test_threshold_rule_is_deterministic_monotone_and_matches_its_definition():
+    # Section 3.2: accept iff p = min(1, exp(log alpha)) >= lambda.  Pins: no dependence on the seed, acceptance is
+    # non-increasing in lambda, lambda = 1 accepts exactly the rows with log alpha >= 0, a tiny lambda accepts all,
+    # and the committed prefix / reflected row follow the same scan as the stochastic rule.
+    from oracle.ddpm import Schedule
+    rng = np.random.default_rng(8)
+    sched = Schedule(100, 1)
+    B, K, D = 40, 6, 12
+    row_ptr = np.arange(B + 1) * K
+    t0 = rng.integers(K, 100, B)
+    row_t = (t0[:, None] - np.arange(K)[None]).ravel()
+    states = rng.standard_normal((B * K, D)); eps_p = 0.3 * rng.standard_normal((B * K, D))
+    eps_q = eps_p + 0.2 * rng.standard_normal((B * K, D)); xi = rng.standard_normal((B * K, D))
+    y_last = rng.standard_normal((B, D)); s = np.ones(B)
+    prev = None
+    for lam in (1e-12, 0.05, 0.3, 0.7, 1.0):
+        a = sr.accept(sched, row_ptr, row_t, s, None, 1, states, eps_p, eps_q, xi, y_last, lam=np.full(B, lam))
+        b = sr.accept(sched, row_ptr, row_t, s, None, 999, states, eps_p, eps_q, xi, y_last, lam=np.full(B, lam))
+        np.testing.assert_array_equal(a["flags"], b["flags"])                      # no random number is consumed
+        np.testing.assert_array_equal(a["flags"], (np.minimum(1, np.exp(a["logratio"])) >= lam).astype(np.uint8))
+        if prev is not None:
+            assert np.all(a["flags"] <= prev)                                       # monotone in lambda
+        prev = a["flags"]
+        for e in range(B):
+            f = a["flags"][e * K:(e + 1) * K]
+            assert a["n_accept"][e] == sr.first_rejection(f) - 1
+    assert sr.accept(sched, row_ptr, row_t, s, None, 1, states, eps_p, eps_q, xi, y_last, lam=1e-12)["flags"].all()
+    one = sr.accept(sched, row_ptr, row_t, s, None, 1, states, eps_p, eps_q, xi, y_last, lam=1.0)
+    np.testing.assert_array_equal(one["flags"], (one["logratio"] >= 0).astype(np.uint8))
