@@ -154,6 +154,7 @@ def main():
     ap.add_argument("--workload", default="C4", choices=list(ti.WORKLOADS))
     ap.add_argument("--point", default="calibrated", choices=["natural", "calibrated", "identical"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-chain", action="store_true", help="skip the whole-chain (action prediction) measurement")
     ap.add_argument("--no-accept-xl", action="store_true", help="skip the acceptance-kernel HBM stress shape")
     ap.add_argument("--cpu-envs", type=int, default=0, help="environments of the oracle sample (0 = by workload)")
     ap.add_argument("--calibrate", action="store_true", help="print acceptance vs head_scale and exit")
@@ -264,6 +265,23 @@ def main():
                      "kernel_ms_median": k_med, "kernel_ms_last_timed_step": last_verify_kernel_ms,
                      "algorithmic_flops_per_launch": flops},
     }
+    if not args.no_chain:
+        # whole action prediction: every environment from t = T-1 down to the clean action (tsdp_chain)
+        tT = torch.full((wl.B,), wl.T - 1, dtype=torch.int32, device=dev)
+        xc, tc = x0d.clone(), tT.clone()
+        ctx.tsdp_chain(xc, tc, Kd, sd, None, check_every=4, totals=False)          # warm-up
+        xc, tc = x0d.clone(), tT.clone()
+        torch.cuda.synchronize(); tic = time.perf_counter()
+        n_rounds, tot = ctx.tsdp_chain(xc, tc, Kd, sd, None, check_every=4)
+        torch.cuda.synchronize(); el = time.perf_counter() - tic
+        a, d, r = (float(tot[k].float().mean().item()) for k in ("accept", "drafts", "rounds"))
+        res["chain"] = {"denoising_steps": wl.T, "rounds_enqueued": n_rounds, "seconds": el,
+                        "action_predictions_per_s": wl.B / el, "denoising_steps_per_s": wl.B * wl.T / el,
+                        "latency_ms_per_action_prediction": 1e3 * el,
+                        "mean_rounds_per_env": r, "mean_drafts_per_env": d, "mean_accepted_drafts_per_env": a,
+                        "acceptance_of_all_drafts": a / max(d, 1e-9),
+                        # paper's convention: a drafter call costs (drafter blocks / base blocks) of a base call
+                        "nfe_fraction_of_plain_chain": (r + d * wl.draft.layers / wl.base.layers) / wl.T}
     if not args.no_accept_xl:
         res["accept_roofline"] = accept_xl(torch, Tsdp, dev)
     if not args.no_cpu:

@@ -133,6 +133,17 @@ int tsdp_round_threshold(tsdp_ctx* ctx, int B, float* d_x, int32_t* d_t, const i
                          const float* d_sigma_scale, const int32_t* d_env_id, const float* d_lambda,
                          int32_t* d_n_accept, int32_t* d_n_advanced, void* stream);
 
+/* Whole denoising chain: rounds repeat until every environment has finished (t = -1), as in the paper's inference
+ * loop ("this process repeats iteratively until the denoising is complete", Section 1; Sections 3.2).  Rounds are
+ * enqueued back to back; every `check_every` rounds the number of running environments is read back (this call
+ * synchronises the stream at those points) and the loop stops when it is zero or after `max_rounds`.  d_x and d_t
+ * are updated in place; d_lambda selects the threshold rule (NULL = the lossless stochastic test).  Optional
+ * per-environment totals over the chain (NULL to skip, zeroed by the call): accepted drafts, drafted transitions,
+ * rounds in which the environment ran.  *h_rounds receives the number of rounds enqueued. */
+int tsdp_chain(tsdp_ctx* ctx, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
+               const int32_t* d_env_id, const float* d_lambda, int max_rounds, int check_every,
+               int32_t* d_tot_accept, int32_t* d_tot_drafts, int32_t* d_tot_rounds, int32_t* h_rounds, void* stream);
+
 /* Synchronises `stream` and returns the device status word accumulated since the last call:
  * bit 0 = some K was outside 0..K_max (clamped), bit 1 = some t0 was >= T (treated as T-1). */
 int tsdp_status(tsdp_ctx* ctx, void* stream, int32_t* h_status);

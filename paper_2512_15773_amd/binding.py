@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtsdp.so")
 
 EXPORTS = ["tsdp_create", "tsdp_destroy", "tsdp_load_weights", "tsdp_set_cond", "tsdp_draft", "tsdp_verify",
-           "tsdp_accept", "tsdp_round", "tsdp_accept_threshold", "tsdp_round_threshold", "tsdp_status", "tsdp_kernel_timing", "tsdp_kernel_ms", "tsdp_path_name",
+           "tsdp_accept", "tsdp_round", "tsdp_accept_threshold", "tsdp_round_threshold", "tsdp_chain", "tsdp_status", "tsdp_kernel_timing", "tsdp_kernel_ms", "tsdp_path_name",
            "tsdp_last_error"]
 
 
@@ -49,6 +49,7 @@ def load_library():
     lib.tsdp_round.argtypes = [vp, i32] + [vp] * 7 + [vp]
     lib.tsdp_accept_threshold.argtypes = [vp, i32] + [vp] * 15 + [vp]
     lib.tsdp_round_threshold.argtypes = [vp, i32] + [vp] * 8 + [vp]
+    lib.tsdp_chain.argtypes = [vp, i32] + [vp] * 6 + [i32, i32] + [vp] * 3 + [C.POINTER(C.c_int32), vp]
     lib.tsdp_status.argtypes = [vp, vp, C.POINTER(C.c_int32)]
     lib.tsdp_kernel_timing.argtypes = [vp, i32]
     lib.tsdp_kernel_ms.argtypes = [vp, i32, C.POINTER(C.c_float)]
@@ -200,6 +201,20 @@ class Tsdp:
                                                 _ptr(K, torch.int32), _ptr(sigma_scale, torch.float32),
                                                 _ptr(env_id, torch.int32), _ptr(lam, torch.float32),
                                                 _ptr(n_accept, torch.int32), _ptr(n_advanced, torch.int32), _stream(stream)))
+
+    def tsdp_chain(self, x, t, K, sigma_scale, env_id, lam=None, max_rounds=1000, check_every=4, totals=True, stream=None):
+        """Runs rounds until every environment finishes; returns (rounds, totals dict or None)."""
+        B = x.shape[0]
+        tot = None
+        if totals:
+            tot = {k: torch.zeros(B, dtype=torch.int32, device=x.device) for k in ("accept", "drafts", "rounds")}
+        n = C.c_int32(0)
+        self._chk(self.lib.tsdp_chain(self.ctx, B, _ptr(x, torch.float32), _ptr(t, torch.int32), _ptr(K, torch.int32),
+                                      _ptr(sigma_scale, torch.float32), _ptr(env_id, torch.int32), _ptr(lam, torch.float32),
+                                      max_rounds, check_every, _ptr(tot["accept"]) if tot else None,
+                                      _ptr(tot["drafts"]) if tot else None, _ptr(tot["rounds"]) if tot else None,
+                                      C.byref(n), _stream(stream)))
+        return n.value, tot
 
     def tsdp_round(self, x, t, K, sigma_scale, env_id, n_accept=None, n_advanced=None, stream=None):
         self._chk(self.lib.tsdp_round(self.ctx, x.shape[0], _ptr(x, torch.float32), _ptr(t, torch.int32),

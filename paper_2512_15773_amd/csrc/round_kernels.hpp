@@ -319,4 +319,25 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
   }
 }
 
+// Chain bookkeeping after a round: per-environment totals and the number of environments still running.
+__global__ void k_chain_accum(int B, const int32_t* __restrict__ t, const int32_t* __restrict__ K_eff,
+                              const int32_t* __restrict__ n_acc, const int32_t* __restrict__ n_adv,
+                              const int32_t* __restrict__ row_ptr, int32_t* __restrict__ tot_accept,
+                              int32_t* __restrict__ tot_drafts, int32_t* __restrict__ tot_rounds, int32_t* __restrict__ live) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const bool ran = row_ptr[b + 1] > row_ptr[b];      // the environment had rows in this round
+  if (ran) {
+    if (tot_accept) tot_accept[b] += n_acc[b];
+    if (tot_drafts) tot_drafts[b] += K_eff[b];
+    if (tot_rounds) tot_rounds[b] += 1;
+  }
+  if (t[b] >= 0) atomicAdd(live, 1);
+}
+
+__global__ void k_fill_i32(int32_t* p, int n, int32_t v) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
 }  // namespace tsdp

@@ -61,6 +61,7 @@ struct tsdp_ctx {
   bool cond_set = false;
   int cond_B = 0;
   int32_t* status = nullptr;
+  int32_t* live = nullptr;      // environments still running (chain driver)
   int32_t* K_eff = nullptr;     // [B_max]
   // network workspace (lazy)
   bool ws_ready = false;
@@ -771,6 +772,44 @@ int tsdp_round_threshold(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int
                          void* stream) {
   if (c && B > 0 && !d_lambda) return fail(c, TSDP_E_INVAL, "d_lambda is null");
   return round_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, d_lambda, d_n_accept, d_n_advanced, stream);
+}
+
+int tsdp_chain(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
+               const int32_t* d_env_id, const float* d_lambda, int max_rounds, int check_every, int32_t* d_tot_accept,
+               int32_t* d_tot_drafts, int32_t* d_tot_rounds, int32_t* h_rounds, void* stream) {
+  int rc = check_ready(c, B, true);
+  if (rc) return rc;
+  if (h_rounds) *h_rounds = 0;
+  if (B == 0) return TSDP_OK;
+  if (!d_x || !d_t || !d_K || !d_sigma_scale) return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_chain");
+  if (max_rounds < 1 || check_every < 1) return fail(c, TSDP_E_INVAL, "max_rounds and check_every must be positive");
+  if ((rc = ensure_round_buffers(c))) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  if (!c->live) {
+    if ((rc = dev_alloc(c, &c->live, 1))) return rc;
+  }
+  const dim3 gb((B + 255) / 256), blk(256);
+  for (int32_t* p : {d_tot_accept, d_tot_drafts, d_tot_rounds})
+    if (p) hipLaunchKernelGGL(k_fill_i32, gb, blk, 0, s, p, B, 0);
+  int rounds = 0;
+  while (rounds < max_rounds) {
+    if ((rc = round_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, d_lambda, c->n_acc, c->n_adv, stream))) return rc;
+    ++rounds;
+    const bool check = rounds % check_every == 0 || rounds == max_rounds;
+    hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(1), 0, s, c->live, 1, 0);
+    hipLaunchKernelGGL(k_chain_accum, gb, blk, 0, s, B, (const int32_t*)d_t, (const int32_t*)c->K_eff,
+                       (const int32_t*)c->n_acc, (const int32_t*)c->n_adv, (const int32_t*)c->row_ptr, d_tot_accept,
+                       d_tot_drafts, d_tot_rounds, c->live);
+    if (check) {
+      int32_t live = 0;
+      HIPCHK(c, hipMemcpyAsync(&live, c->live, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+      HIPCHK(c, hipStreamSynchronize(s));
+      if (live == 0) break;
+    }
+  }
+  if (h_rounds) *h_rounds = rounds;
+  HIPCHK(c, hipGetLastError());
+  return TSDP_OK;
 }
 
 int tsdp_status(tsdp_ctx* c, void* stream, int32_t* h_status) {

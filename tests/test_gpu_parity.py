@@ -250,3 +250,45 @@ def test_threshold_rule_matches_oracle():
     np.testing.assert_array_equal(na.cpu().numpy(), ref["n_accept"])
     np.testing.assert_array_equal(t.cpu().numpy(), ref["t_next"])
     S["ctx"].close()
+
+
+def test_chain_runs_rounds_until_every_environment_finishes():
+    # fp32: the chain driver must equal the oracle's round applied repeatedly (same noise stream, same decisions)
+    wl = ti.small_variant(ti.C1, B=6)
+    S = _setup(wl, 6, head_scale=0.6)
+    t0 = np.array([9, 9, 6, 3, 0, -1]); K = np.array([4, 2, 4, 3, 4, 4]); s = np.array([1.0, 1.2, 1.0, 1.0, 1.0, 1.0])
+    x = to_dev(S["x"]); t = to_dev(t0.astype(np.int32))
+    rounds, tot = S["ctx"].tsdp_chain(x, t, to_dev(K.astype(np.int32)), to_dev(s.astype(np.float32)), None, check_every=1)
+    xr, tr = np.asarray(S["x"], float), t0.copy()
+    acc = np.zeros(6, int); drafts = np.zeros(6, int); nr = np.zeros(6, int); n = 0
+    while (tr >= 0).any():
+        r = sr.spec_round(S["base"], S["drafter"], S["sched"], xr, tr, K, s, None, S["seed"], S["cond"])
+        ran = tr >= 0
+        acc += r["n_accept"]; drafts += r["draft"]["K_eff"]; nr += ran
+        near = (np.abs(r["logu"] - r["logratio"]) < 1e-4) & (r["draft"]["row_t"] > 0)
+        assert not near.any()                                             # no near-tie on this seed: decisions are comparable
+        xr, tr = r["x_out"], r["t_next"]; n += 1
+    assert rounds == n
+    assert (t.cpu().numpy() == -1).all()
+    np.testing.assert_array_equal(tot["accept"].cpu().numpy(), acc)
+    np.testing.assert_array_equal(tot["drafts"].cpu().numpy(), drafts)
+    np.testing.assert_array_equal(tot["rounds"].cpu().numpy(), nr)
+    assert scaled_err(x.cpu().numpy(), xr) < 1e-4                         # fp32 rounding compounded over the chain
+    S["ctx"].close()
+
+
+def test_chain_bf16_invariants():
+    # every environment ends at t = -1 and the rounds it ran advance it by exactly t0 + 1 steps in total
+    wl = ti.small_variant(ti.C3, B=12)
+    S = _setup(wl, 12, head_scale=0.2, b_std=0.0)
+    t0 = np.array([99, 99, 80, 64, 50, 33, 17, 16, 15, 1, 0, -1]); K = np.full(12, 16); s = np.ones(12)
+    x = to_dev(S["x"]); t = to_dev(t0.astype(np.int32))
+    rounds, tot = S["ctx"].tsdp_chain(x, t, to_dev(K.astype(np.int32)), to_dev(s.astype(np.float32)), None, check_every=3)
+    assert (t.cpu().numpy() == -1).all() and np.isfinite(x.cpu().numpy()).all()
+    a, d, r = (tot[k].cpu().numpy() for k in ("accept", "drafts", "rounds"))
+    assert r[-1] == 0 and r[-2] == 1 and (r[:-1] >= 1).all() and rounds >= r.max()
+    assert (a <= d).all() and (a[:4] > 0).all()
+    # steps advanced = accepted drafts + one corrected / base step per round that did not accept everything;
+    # at least one step per round and never more than t0 + 1 in total
+    assert ((a + r >= t0 + 1) | (t0 < 0)).all()
+    S["ctx"].close()
