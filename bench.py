@@ -203,7 +203,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    fused = ctx.path_name(0).startswith("bf16-mfma")
+    fused = "mfma-fused" in ctx.path_name(0)
     if fused:
         ctx.tsdp_kernel_timing(True)                 # one event pair per stage and step, on the launch stream
     tic = time.perf_counter()
@@ -238,7 +238,7 @@ def main():
         kname = "k_fused_forward (verify forward, all layers in one launch)"
     else:
         k_ms, k_med, kd_ms, kname = t_verify[0], t_verify[1], None, "tsdp_verify (sequence of fp32 operator kernels)"
-    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS
+    peak = PEAK_BF16_TFLOPS if bf16 else PEAK_FP32_TFLOPS    # fp32 networks: fp32 MFMA / vector peak
     achieved = flops / (k_ms * 1e-3) / 1e12
     res = {
         "metric": "accepted denoising steps/s on 1 GPU", "value": adv * args.steps / wall,
@@ -259,7 +259,7 @@ def main():
                        "verify": {"mean": t_verify[0], "p50": t_verify[1], "p95": t_verify[2]},
                        "accept": {"mean": t_accept[0], "p50": t_accept[1], "p95": t_accept[2]},
                        "drafter_kernel": kd_ms},
-        "roofline": {"kernel": kname, "bound": "mfma" if bf16 else "alu", "achieved": achieved, "peak": peak,
+        "roofline": {"kernel": kname, "bound": "mfma" if (bf16 or fused) else "alu", "achieved": achieved, "peak": peak,
                      "unit": "TFLOP/s", "frac": achieved / peak,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name) if fused else None, "kernel_ms": k_ms,
                      "kernel_ms_median": k_med, "kernel_ms_last_timed_step": last_verify_kernel_ms,

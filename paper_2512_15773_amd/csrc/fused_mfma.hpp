@@ -26,12 +26,12 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 struct FusedLayer {            // device pointers of one layer
-  const bf16x8* qkv;           // [3D/16][D/32][64] fragments, rows grouped per head group as q|k|v per head
-  const bf16x8* o;             // [D/16][D/32][64]
-  const bf16x8* up;            // [M/16][D/32][64]
-  const bf16x8* dn;            // [D/16][M/32][64]
-  const bf16x8* cq;            // [D/16][D/32][64]   (cross-attention only)
-  const bf16x8* co;            // [D/16][D/32][64]
+  const void* qkv;           // [3D/16][D/32][64] fragments, rows grouped per head group as q|k|v per head
+  const void* o;             // [D/16][D/32][64]
+  const void* up;            // [M/16][D/32][64]
+  const void* dn;            // [D/16][M/32][64]
+  const void* cq;            // [D/16][D/32][64]   (cross-attention only)
+  const void* co;            // [D/16][D/32][64]
   const float* qkv_b;          // [3D] in the same row order as qkv
   const float* o_b; const float* up_b; const float* dn_b; const float* cq_b; const float* co_b;
 };
@@ -42,9 +42,9 @@ struct FusedNet {
   FusedLayer layer[FUSED_MAX_LAYERS];
   int L;
   const float* tok_w; const float* tok_b; const float* pos;   // fp32 [D,A], [D], [H,D]
-  const bf16x8* head;          // [1][D/32][64] fragments of head_w padded to 16 rows
+  const void* head;            // [1][D/32][64] fragments of head_w padded to 16 rows
   const float* head_b;         // [A]
-  const bf16x8* modw;          // [L*4D/16][D/32][64] FiLM projections of all layers (drafter kernel)
+  const void* modw;            // [L*4D/16][D/32][64] FiLM projections of all layers (drafter kernel)
   const float* modb;           // [L*4D]
   const float* temb;           // [T, D]
   const float* cemb;           // [B, D] conditioning embedding (vector conditioning) or null
@@ -81,6 +81,43 @@ __device__ __forceinline__ float gelu_fast(float x) {
   return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(w));
 }
 
+// Element-type traits of the fused kernels.  A "fragment" is what one lane holds of a 16-row operand for one
+// k-step: VW consecutive K entries (16 bytes), rows l%16, K offset (l/16)*VW.
+//   TBF16: bf16 operands, k-step 32, one mfma_f32_16x16x32_bf16 per fragment pair.
+//   TF32 : fp32 operands, k-step 16, four mfma_f32_16x16x4_f32 per fragment pair; MFMA j of the four contracts
+//          the K entries {4g + j : g = 0..3}, which is just a permutation of the k-step's 16 entries.
+struct TBF16 {
+  typedef __bf16 elem;
+  typedef bf16x8 frag;
+  typedef bf16x4 vec4;
+  static constexpr int VW = 8, KSTEP = 32, PAD = 8;
+  static __device__ __forceinline__ void mma(const frag& a, const frag& b, f32x4& c) {
+    c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+  }
+  // 16-deep contraction with 4 entries per lane (keys (l/16)*4..): the P.V product of attention
+  static __device__ __forceinline__ void mma16(const vec4& a, const vec4& b, f32x4& c) {
+    c = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, a), __builtin_bit_cast(s16x4, b), c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ vec4 cvt(f32x4 v) {
+    vec4 r;
+    r[0] = (__bf16)v[0]; r[1] = (__bf16)v[1]; r[2] = (__bf16)v[2]; r[3] = (__bf16)v[3];
+    return r;
+  }
+};
+
+struct TF32 {
+  typedef float elem;
+  typedef f32x4 frag;
+  typedef f32x4 vec4;
+  static constexpr int VW = 4, KSTEP = 16, PAD = 4;
+  static __device__ __forceinline__ void mma(const frag& a, const frag& b, f32x4& c) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) c = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j], b[j], c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ void mma16(const vec4& a, const vec4& b, f32x4& c) { mma(a, b, c); }
+  static __device__ __forceinline__ vec4 cvt(f32x4 v) { return v; }
+};
+
 __device__ __forceinline__ float silu_fast(float g) { return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)); }
 
 __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
@@ -113,33 +150,35 @@ __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
 // that about TSDP_INFLIGHT_CLK cycles of MFMA work separate a request from its use (one L2 round trip)
 // without flooding the small vector L1.  issue() requests k-step 0 only and may be called a whole phase
 // early (before an epilogue, a barrier or the attention of the previous phase); run() does the rest.
-template <int MB, int NB, int NKS, int BD = 2>
+template <class TT, int MB, int NB, int NKS, int BD = 2>
 struct FragGemm {
+  typedef typename TT::frag frag;
+  typedef typename TT::elem elem;
   static constexpr int STEP_CLK = MB * NB * 16;
   static constexpr int PFW = (TSDP_INFLIGHT_CLK + STEP_CLK - 1) / STEP_CLK;
   static constexpr int PF0 = PFW < 1 ? 1 : (PFW > TSDP_PFMAX ? TSDP_PFMAX : PFW);
   static constexpr int PF = PF0 > NKS ? NKS : PF0;
-  bf16x8 a[PF + 1][MB];
-  const bf16x8* wl;
+  frag a[PF + 1][MB];
+  const frag* wl;
   int kst;                     // elements between the fragment rows of consecutive mb (in k-steps)
 
   // fragment row of index mb is mf0 + mb*mfs
-  __device__ __forceinline__ void issue(const bf16x8* __restrict__ wp, int ks_total, int mf0, int ks0, int lane, int mfs = 1) {
-    wl = wp + ((size_t)mf0 * ks_total + ks0) * 64 + lane;
+  __device__ __forceinline__ void issue(const void* __restrict__ wp, int ks_total, int mf0, int ks0, int lane, int mfs = 1) {
+    wl = reinterpret_cast<const frag*>(wp) + ((size_t)mf0 * ks_total + ks0) * 64 + lane;
     kst = ks_total * mfs;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) a[0][mb] = wl[(size_t)mb * kst * 64];
   }
 
-  __device__ __forceinline__ void run(const __bf16* act, int stride, f32x4 (&acc)[MB][NB], int lane) {
-    const __bf16* al = act + (lane & 15) * stride + (lane >> 4) * 8;
-    bf16x8 b[BD][NB];
+  __device__ __forceinline__ void run(const elem* act, int stride, f32x4 (&acc)[MB][NB], int lane) {
+    const elem* al = act + (lane & 15) * stride + (lane >> 4) * TT::VW;
+    frag b[BD][NB];
 #pragma unroll
     for (int p = 1; p < PF; ++p)
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) a[p][mb] = wl[((size_t)mb * kst + p) * 64];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb) b[0][nb] = *reinterpret_cast<const bf16x8*>(al + nb * 16 * stride);
+    for (int nb = 0; nb < NB; ++nb) b[0][nb] = *reinterpret_cast<const frag*>(al + nb * 16 * stride);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int k = 0; k < NKS; ++k) {
@@ -151,7 +190,7 @@ struct FragGemm {
       if (BD == 2 && k + 1 < NKS) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
-          b[(k + 1) & 1][nb] = (TSDP_ABL & 2) ? b[0][nb] : *reinterpret_cast<const bf16x8*>(al + nb * 16 * stride + (k + 1) * 32);
+          b[(k + 1) & 1][nb] = (TSDP_ABL & 2) ? b[0][nb] : *reinterpret_cast<const frag*>(al + nb * 16 * stride + (k + 1) * TT::KSTEP);
       }
       __builtin_amdgcn_sched_barrier(0);
       if (!(TSDP_ABL & 4)) {
@@ -159,11 +198,11 @@ struct FragGemm {
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb)
-            acc[mb][nb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[k % (PF + 1)][mb], b[k % BD][nb], acc[mb][nb], 0, 0, 0);
+            TT::mma(a[k % (PF + 1)][mb], b[k % BD][nb], acc[mb][nb]);
       }
       if (BD == 1 && k + 1 < NKS) {
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) b[0][nb] = *reinterpret_cast<const bf16x8*>(al + nb * 16 * stride + (k + 1) * 32);
+        for (int nb = 0; nb < NB; ++nb) b[0][nb] = *reinterpret_cast<const frag*>(al + nb * 16 * stride + (k + 1) * TT::KSTEP);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -173,8 +212,10 @@ struct FragGemm {
 // D model width, NT tokens per workgroup, H tokens per row, HEADS attention heads, CM conditioning mode,
 // CH hidden-chunk width of the MLP, SX observation tokens (cross-attention), HP heads per attention phase,
 // NW wavefronts per workgroup; every wavefront owns D/NW residual features of every token of the tile.
-template <int D_, int NT_, int H_, int HEADS_, int CM_, int CH_, int SX_, int HP_, int NW_>
+template <class TT_, int D_, int NT_, int H_, int HEADS_, int CM_, int CH_, int SX_, int HP_, int NW_>
 struct FusedCfg {
+  typedef TT_ TT;
+  static constexpr int ES = sizeof(typename TT_::elem), KSTEP = TT_::KSTEP;
   static constexpr int D = D_, NT = NT_, H = H_, HEADS = HEADS_, CM = CM_, CH = CH_, SX = SX_, HP = HP_, NW = NW_;
   static constexpr int THREADS = NW * 64;
   static constexpr int DH = D / HEADS;
@@ -186,15 +227,15 @@ struct FusedCfg {
   static constexpr int RPT = NT / H;                    // rows per tile
   static constexpr int NKF = H / 16;                    // key / query fragments of self-attention
   static constexpr int SF = SX / 16;                    // key fragments of cross-attention
-  static constexpr int AS = D + 8;                      // LDS strides (bf16 elements), +8 against bank conflicts
-  static constexpr int QS = DH + 8;
+  static constexpr int AS = D + TT_::PAD;               // LDS strides (elements), +16 bytes against bank conflicts
+  static constexpr int QS = DH + TT_::PAD;
   static constexpr int VS = H + 4;
-  static constexpr int US = CH + 8;
-  static constexpr int ACT_B = NT * AS * 2;
-  static constexpr int Q_B = HP * NT * QS * 2;
-  static constexpr int VT_B = HP * RPT * DH * VS * 2;
+  static constexpr int US = CH + TT_::PAD;
+  static constexpr int ACT_B = NT * AS * ES;
+  static constexpr int Q_B = HP * NT * QS * ES;
+  static constexpr int VT_B = HP * RPT * DH * VS * ES;
   static constexpr int QKV_B = 2 * Q_B + VT_B;
-  static constexpr int U_B = NT * US * 2;
+  static constexpr int U_B = NT * US * ES;
   static constexpr int XT_B = NT * 64 * 4;              // fp32 latent staging of the verify kernel (A <= 64)
   // two hidden-chunk buffers (one barrier per chunk instead of two) when a single workgroup owns the CU's LDS
 #ifndef TSDP_UDB_OK
@@ -209,11 +250,11 @@ struct FusedCfg {
   static constexpr int SCR_B = SCR0_B > XT_B ? SCR0_B : XT_B;
   static constexpr int RED_B = 2 * NW * NT * 4;
   static constexpr int LDS_B = ACT_B + SCR_B + RED_B;   // body; the drafter kernel appends its own regions
-  static constexpr int WG_PER_CU = LDS_B <= 80 * 1024 && NW == 4 ? 2 : 1;
+  static constexpr int WG_PER_CU = LDS_B <= 80 * 1024 && NW <= 4 ? 2 : 1;
 #ifdef TSDP_FORCE_BD
   static constexpr int BD = TSDP_FORCE_BD;
 #else
-  static constexpr int WAVES_PER_SIMD = WG_PER_CU * NW / 4;
+  static constexpr int WAVES_PER_SIMD = (WG_PER_CU * NW + 3) / 4;
   static constexpr int BD = WAVES_PER_SIMD >= 2 ? 1 : 2; // LDS operand buffers: a second wave on the SIMD hides LDS latency
 #endif
 #ifdef TSDP_FORCE_XPF
@@ -221,10 +262,11 @@ struct FusedCfg {
 #else
   static constexpr bool XPF = WAVES_PER_SIMD == 1;      // request the first weight fragments of a phase one phase early
 #endif
-  static_assert(D % (16 * NW) == 0 && NT % 16 == 0 && H % 16 == 0 && NT % H == 0 && DH % 32 == 0, "shape");
+  static_assert(D % (16 * NW) == 0 && NT % 16 == 0 && H % 16 == 0 && NT % H == 0 && DH % KSTEP == 0, "shape");
+  static_assert(D % KSTEP == 0 && CH % KSTEP == 0, "shape");
   static_assert((HEADS % HP) == 0 && (HP * 3 * DH) % (16 * NW) == 0 && (HP * DH) % (16 * NW) == 0, "shape");
   static_assert(CH % (16 * NW) == 0 && (4 * D) % CH == 0, "shape");
-  static_assert(CM == 0 || (SX % 16 == 0 && SX >= 16), "observation tokens must be a multiple of 16");
+  static_assert(CM == 0 || (SX % 16 == 0 && SX >= 16 && ES == 2), "cross-attention: bf16 only, tokens a multiple of 16");
 };
 
 // One forward pass for the tile.  xt: LDS fp32 [NT][A] latent tokens (may alias the scratch region: it is
@@ -239,11 +281,16 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   constexpr int DH = C::DH, HP = C::HP, NB = C::NB, MBH = C::MBH, MBQ = C::MBQ, MBU = C::MBU, MBC = C::MBC,
                 RPT = C::RPT, NKF = C::NKF, AS = C::AS, QS = C::QS, VS = C::VS, US = C::US, SF = C::SF;
   constexpr int NG = HEADS / HP, NC = 4 * D / CH;
-  __bf16* act = reinterpret_cast<__bf16*>(lds);
-  __bf16* qbuf = reinterpret_cast<__bf16*>(lds + C::ACT_B);
-  __bf16* kbuf = qbuf + HP * NT * QS;
-  __bf16* vtb = kbuf + HP * NT * QS;
-  __bf16* ubuf = qbuf;
+  typedef typename C::TT TT;
+  typedef typename TT::elem elem;
+  typedef typename TT::frag frag;
+  typedef typename TT::vec4 vec4;
+  constexpr int KSTEP = TT::KSTEP, VW = TT::VW;
+  elem* act = reinterpret_cast<elem*>(lds);
+  elem* qbuf = reinterpret_cast<elem*>(lds + C::ACT_B);
+  elem* kbuf = qbuf + HP * NT * QS;
+  elem* vtb = kbuf + HP * NT * QS;
+  elem* ubuf = qbuf;
   float* red1 = reinterpret_cast<float*>(lds + C::ACT_B + C::SCR_B);
   float* red2 = red1 + NW * NT;
 
@@ -255,11 +302,12 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
 
   constexpr int BD = C::BD;
   constexpr bool XPF = C::XPF;
-  typedef FragGemm<MBQ, NB, D / 32, BD> GQ;             // q|k|v projection of one head group
-  typedef FragGemm<MBH, NB, DH / 32, BD> GO;            // output projection, one head's slice of K
-  typedef FragGemm<MBU, NB, D / 32, BD> GU;             // MLP up, one hidden chunk
-  typedef FragGemm<MBH, NB, CH / 32, BD> GD;            // MLP down, one hidden chunk of K
-  typedef FragGemm<MBC, NB, D / 32, BD> GC;             // cross-attention query projection
+  constexpr int KD = D / KSTEP, KH = DH / KSTEP, KC = CH / KSTEP, KM = 4 * D / KSTEP;   // k-steps of D, DH, CH, 4D
+  typedef FragGemm<TT, MBQ, NB, KD, BD> GQ;             // q|k|v projection of one head group
+  typedef FragGemm<TT, MBH, NB, KH, BD> GO;             // output projection, one head's slice of K
+  typedef FragGemm<TT, MBU, NB, KD, BD> GU;             // MLP up, one hidden chunk
+  typedef FragGemm<TT, MBH, NB, KC, BD> GD;             // MLP down, one hidden chunk of K
+  typedef FragGemm<TT, (MBC > 0 ? MBC : 1), NB, KD, BD> GC;   // cross-attention query projection
 
 #ifdef TSDP_TRACE
   long long tacc_[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -329,7 +377,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
           const f32x4 b = *reinterpret_cast<const f32x4*>(mp + D);
           v = v * (1.0f + g) + b;
         }
-        *reinterpret_cast<bf16x4*>(act + (nb * 16 + l16) * AS + f0) = to_bf16x4(v);
+        *reinterpret_cast<vec4*>(act + (nb * 16 + l16) * AS + f0) = TT::cvt(v);
       }
       __builtin_amdgcn_sched_barrier(0);                // keep the FiLM loads of one fragment row in flight, not all
     }
@@ -354,37 +402,37 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
     sum += __shfl_xor(sum, 16); sum += __shfl_xor(sum, 32);
     const float inv = 1.0f / sum;
 #pragma unroll
-    for (int kf = 0; kf < NK; ++kf) p[kf] = to_bf16x4(s[kf] * inv);
+    for (int kf = 0; kf < NK; ++kf) p[kf] = TT::cvt(s[kf] * inv);
   };
 
   // softmax(q k^T) v for query fragment qf of (row, head) held in LDS; the result overwrites those q rows
   auto self_attention = [&](int r, int hh, int qf) {
-    __bf16* qp = qbuf + (hh * NT + r * H + qf * 16) * QS;
-    const __bf16* kp = kbuf + (hh * NT + r * H) * QS;
+    elem* qp = qbuf + (hh * NT + r * H + qf * 16) * QS;
+    const elem* kp = kbuf + (hh * NT + r * H) * QS;
     f32x4 s[NKF];                                       // [key frag]; lane: query l16, keys lg*4..
 #pragma unroll
     for (int kf = 0; kf < NKF; ++kf) s[kf] = f32x4{0, 0, 0, 0};
 #pragma unroll
-    for (int ks = 0; ks < DH / 32; ++ks) {
-      const bf16x8 qb = *reinterpret_cast<const bf16x8*>(qp + l16 * QS + ks * 32 + lg * 8);
+    for (int ks = 0; ks < KH; ++ks) {
+      const frag qb = *reinterpret_cast<const frag*>(qp + l16 * QS + ks * KSTEP + lg * VW);
 #pragma unroll
       for (int kf = 0; kf < NKF; ++kf) {
-        const bf16x8 ka = *reinterpret_cast<const bf16x8*>(kp + (kf * 16 + l16) * QS + ks * 32 + lg * 8);
-        s[kf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka, qb, s[kf], 0, 0, 0);
+        const frag ka = *reinterpret_cast<const frag*>(kp + (kf * 16 + l16) * QS + ks * KSTEP + lg * VW);
+        TT::mma(ka, qb, s[kf]);
       }
     }
-    bf16x4 p[NKF];
+    vec4 p[NKF];
     softmax_col(s, p, std::integral_constant<int, NKF>{});
-    const __bf16* vp = vtb + (size_t)(hh * RPT + r) * DH * VS;
+    const elem* vp = vtb + (size_t)(hh * RPT + r) * DH * VS;
 #pragma unroll
     for (int cf = 0; cf < DH / 16; ++cf) {
       f32x4 o = f32x4{0, 0, 0, 0};
 #pragma unroll
       for (int kf = 0; kf < NKF; ++kf) {
-        const s16x4 va = *reinterpret_cast<const s16x4*>(vp + (cf * 16 + l16) * VS + kf * 16 + lg * 4);
-        o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(va, __builtin_bit_cast(s16x4, p[kf]), o, 0, 0, 0);
+        const vec4 va = *reinterpret_cast<const vec4*>(vp + (cf * 16 + l16) * VS + kf * 16 + lg * 4);
+        TT::mma16(va, p[kf], o);
       }
-      *reinterpret_cast<bf16x4*>(qp + l16 * QS + cf * 16 + lg * 4) = to_bf16x4(o);
+      *reinterpret_cast<vec4*>(qp + l16 * QS + cf * 16 + lg * 4) = TT::cvt(o);
     }
   };
 
@@ -392,35 +440,41 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   // Keys and transposed values come from global memory already in MFMA fragment order; cross_load requests them
   // (it needs nothing from this phase, so it runs before the query projection) and cross_attend consumes them.
   constexpr int SFc = SF > 0 ? SF : 1;
-  auto cross_load = [&](int r, int layer, int head, bf16x8 (&ka)[DH / 32][SFc], bf16x4 (&va)[DH / 16][SFc]) {
+  constexpr int KHc = KH > 0 ? KH : 1;
+  auto cross_load = [&](int r, int layer, int head, bf16x8 (&ka)[KHc][SFc], bf16x4 (&va)[DH / 16][SFc]) {
     if constexpr (CM == 1) {
       const size_t eh = ((size_t)env_of_row[r] * net.L + layer) * HEADS + head;
-      const bf16x8* kcp = net.kc + eh * (SF * (DH / 32)) * 64 + lane;
+      const bf16x8* kcp = net.kc + eh * (SF * (KH)) * 64 + lane;
       const bf16x4* vcp = net.vct + eh * ((DH / 16) * SF) * 64 + lane;
 #pragma unroll
-      for (int ks = 0; ks < DH / 32; ++ks)
+      for (int ks = 0; ks < KH; ++ks)
 #pragma unroll
-        for (int kf = 0; kf < SF; ++kf) ka[ks][kf] = kcp[(kf * (DH / 32) + ks) * 64];
+        for (int kf = 0; kf < SF; ++kf) ka[ks][kf] = kcp[(kf * (KH) + ks) * 64];
 #pragma unroll
       for (int cf = 0; cf < DH / 16; ++cf)
 #pragma unroll
         for (int kf = 0; kf < SF; ++kf) va[cf][kf] = vcp[(cf * SF + kf) * 64];
     }
   };
-  auto cross_attend = [&](int r, int hh, int qf, const bf16x8 (&ka)[DH / 32][SFc], const bf16x4 (&va)[DH / 16][SFc]) {
+  auto cross_attend = [&](int r, int hh, int qf, const bf16x8 (&ka)[KHc][SFc], const bf16x4 (&va)[DH / 16][SFc]) {
     if constexpr (CM == 1) {
-      __bf16* qp = qbuf + (hh * NT + r * H + qf * 16) * QS;
+      __bf16* qp = reinterpret_cast<__bf16*>(qbuf) + (hh * NT + r * H + qf * 16) * QS;
       f32x4 s[SF];
 #pragma unroll
       for (int kf = 0; kf < SF; ++kf) s[kf] = f32x4{0, 0, 0, 0};
 #pragma unroll
-      for (int ks = 0; ks < DH / 32; ++ks) {
+      for (int ks = 0; ks < KH; ++ks) {
         const bf16x8 qb = *reinterpret_cast<const bf16x8*>(qp + l16 * QS + ks * 32 + lg * 8);
 #pragma unroll
         for (int kf = 0; kf < SF; ++kf) s[kf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks][kf], qb, s[kf], 0, 0, 0);
       }
       bf16x4 p[SF];
-      softmax_col(s, p, std::integral_constant<int, SF>{});
+      {
+        vec4 pv[SF];
+        softmax_col(s, pv, std::integral_constant<int, SF>{});
+#pragma unroll
+        for (int kf = 0; kf < SF; ++kf) p[kf] = __builtin_bit_cast(bf16x4, pv[kf]);
+      }
 #pragma unroll
       for (int cf = 0; cf < DH / 16; ++cf) {
         f32x4 o = f32x4{0, 0, 0, 0};
@@ -443,7 +497,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   };
 
   GQ gq;
-  if (XPF) gq.issue(net.layer[0].qkv, D / 32, wave, 0, lane, NW);
+  if (XPF) gq.issue(net.layer[0].qkv, KD, wave, 0, lane, NW);
   for (int layer = 0; layer < net.L; ++layer) {
     const FusedLayer& W = net.layer[layer];
     // ================= self-attention block =================
@@ -462,10 +516,10 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
         }
-        if (!XPF) gq.issue(W.qkv, D / 32, g * (HP * 3 * DH / 16) + wave, 0, lane, NW);
+        if (!XPF) gq.issue(W.qkv, KD, g * (HP * 3 * DH / 16) + wave, 0, lane, NW);
         gq.run(act, AS, acc, lane);
         TSDP_TICK(1)
-        if (XPF) go.issue(W.o, D / 32, wave * MBH, g * HP * DH / 32, lane);      // needed only after the attention
+        if (XPF) go.issue(W.o, KD, wave * MBH, g * HP * KH, lane);      // needed only after the attention
         if (g > 0) __syncthreads();                     // previous group's O-projection has read qbuf
         TSDP_TICK(2)
 #pragma unroll
@@ -478,13 +532,13 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
             const f32x4 v = acc[mb][nb] + bias[mb];
             const int t = nb * 16 + l16;
             if (cls == 0) {
-              *reinterpret_cast<bf16x4*>(qbuf + (hh * NT + t) * QS + c0) = to_bf16x4(v);
+              *reinterpret_cast<vec4*>(qbuf + (hh * NT + t) * QS + c0) = TT::cvt(v);
             } else if (cls == 1) {
-              *reinterpret_cast<bf16x4*>(kbuf + (hh * NT + t) * QS + c0) = to_bf16x4(v);
+              *reinterpret_cast<vec4*>(kbuf + (hh * NT + t) * QS + c0) = TT::cvt(v);
             } else {
-              __bf16* vp = vtb + ((size_t)(hh * RPT + t / H) * DH + c0) * VS + (t % H);
+              elem* vp = vtb + ((size_t)(hh * RPT + t / H) * DH + c0) * VS + (t % H);
 #pragma unroll
-              for (int i = 0; i < 4; ++i) vp[i * VS] = (__bf16)v[i];
+              for (int i = 0; i < 4; ++i) vp[i * VS] = (elem)v[i];
             }
           }
         }
@@ -498,12 +552,12 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       TSDP_TICK(4)
       __syncthreads();
       TSDP_TICK(2)
-      if (XPF && g + 1 < NG) gq.issue(W.qkv, D / 32, (g + 1) * (HP * 3 * DH / 16) + wave, 0, lane, NW);
-      if (!XPF) go.issue(W.o, D / 32, wave * MBH, g * HP * DH / 32, lane);
+      if (XPF && g + 1 < NG) gq.issue(W.qkv, KD, (g + 1) * (HP * 3 * DH / 16) + wave, 0, lane, NW);
+      if (!XPF) go.issue(W.o, KD, wave * MBH, g * HP * KH, lane);
       go.run(qbuf, QS, h, lane);
 #pragma unroll
       for (int hh = 1; hh < HP; ++hh) {
-        go.issue(W.o, D / 32, wave * MBH, (g * HP + hh) * DH / 32, lane);
+        go.issue(W.o, KD, wave * MBH, (g * HP + hh) * KH, lane);
         go.run(qbuf + hh * NT * QS, QS, h, lane);
       }
       TSDP_TICK(5)
@@ -512,7 +566,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
     // ================= cross-attention block (observation tokens) =================
     if constexpr (CM == 1) {
       GC gc;
-      if (XPF) gc.issue(W.cq, D / 32, wave * MBC, 0, lane);
+      if (XPF) gc.issue(W.cq, KD, wave * MBC, 0, lane);
       TSDP_TICK(11)
       write_ln(layer, -1);                               // its barriers order the O-projection reads before qbuf writes
       TSDP_TICK(0)
@@ -520,7 +574,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         TSDP_FENCE_IDS();
         GO go;
         // operands of this wave's first attention task of the group: requested before the query projection
-        bf16x8 ka[DH / 32][SFc];
+        bf16x8 ka[KHc][SFc];
         bf16x4 va[DH / 16][SFc];
         constexpr int NTASK = RPT * HP * NKF;
         if (TSDP_XLOAD_EARLY && wave < NTASK) cross_load((wave / NKF) % RPT, layer, g * HP + wave / (NKF * RPT), ka, va);
@@ -533,10 +587,10 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
           }
-          if (!XPF) gc.issue(W.cq, D / 32, g * (HP * DH / 16) + wave * MBC, 0, lane);
+          if (!XPF) gc.issue(W.cq, KD, g * (HP * DH / 16) + wave * MBC, 0, lane);
           gc.run(act, AS, acc, lane);
           TSDP_TICK(1)
-          if (XPF) go.issue(W.co, D / 32, wave * MBH, g * HP * DH / 32, lane);
+          if (XPF) go.issue(W.co, KD, wave * MBH, g * HP * KH, lane);
           if (g > 0) __syncthreads();
           TSDP_TICK(2)
 #pragma unroll
@@ -544,7 +598,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
             const int lr = (wave * MBC + mb) * 16, hh = lr / DH, c0 = lr % DH + lg * 4;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
-              *reinterpret_cast<bf16x4*>(qbuf + (hh * NT + nb * 16 + l16) * QS + c0) = to_bf16x4(acc[mb][nb] + bias[mb]);
+              *reinterpret_cast<vec4*>(qbuf + (hh * NT + nb * 16 + l16) * QS + c0) = TT::cvt(acc[mb][nb] + bias[mb]);
           }
         }
         TSDP_TICK(3)
@@ -559,12 +613,12 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         TSDP_TICK(10)
         __syncthreads();
         TSDP_TICK(2)
-        if (XPF && g + 1 < NG) gc.issue(W.cq, D / 32, (g + 1) * (HP * DH / 16) + wave * MBC, 0, lane);
-        if (!XPF) go.issue(W.co, D / 32, wave * MBH, g * HP * DH / 32, lane);
+        if (XPF && g + 1 < NG) gc.issue(W.cq, KD, (g + 1) * (HP * DH / 16) + wave * MBC, 0, lane);
+        if (!XPF) go.issue(W.co, KD, wave * MBH, g * HP * KH, lane);
         go.run(qbuf, QS, h, lane);
 #pragma unroll
         for (int hh = 1; hh < HP; ++hh) {
-          go.issue(W.co, D / 32, wave * MBH, (g * HP + hh) * DH / 32, lane);
+          go.issue(W.co, KD, wave * MBH, (g * HP + hh) * KH, lane);
           go.run(qbuf + hh * NT * QS, QS, h, lane);
         }
         TSDP_TICK(5)
@@ -573,7 +627,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
     }
     // ================= MLP block =================
     GU gu;
-    if (XPF) gu.issue(W.up, D / 32, wave * MBU, 0, lane);
+    if (XPF) gu.issue(W.up, KD, wave * MBU, 0, lane);
     TSDP_TICK(11)
     write_ln(layer, 2);                                  // its barriers also order the projection reads before ubuf writes
     TSDP_TICK(0)
@@ -589,15 +643,15 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
         }
-        if (!XPF) gu.issue(W.up, D / 32, c * (CH / 16) + wave * MBU, 0, lane);
+        if (!XPF) gu.issue(W.up, KD, c * (CH / 16) + wave * MBU, 0, lane);
         gu.run(act, AS, acc, lane);
         TSDP_TICK(6)
-        if (XPF) gd.issue(W.dn, 4 * D / 32, wave * MBH, c * (CH / 32), lane);
+        if (XPF) gd.issue(W.dn, KM, wave * MBH, c * (KC), lane);
         // single buffer: the previous chunk's down-projection has read ubuf; double buffer: the buffer written
         // now was last read two chunks ago, and every wave has passed a barrier since
         if (c > 0 && !C::UDB) __syncthreads();
         TSDP_TICK(7)
-        __bf16* ub = ubuf + (C::UDB ? (c & 1) * NT * US : 0);
+        elem* ub = ubuf + (C::UDB ? (c & 1) * NT * US : 0);
 #pragma unroll
         for (int mb = 0; mb < MBU; ++mb) {
           const int f0 = (wave * MBU + mb) * 16 + lg * 4;
@@ -606,7 +660,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
             f32x4 v = acc[mb][nb] + bias[mb];
 #pragma unroll
             for (int i = 0; i < 4; ++i) v[i] = (TSDP_ABL & 16) ? v[i] : gelu_fast(v[i]);
-            *reinterpret_cast<bf16x4*>(ub + (nb * 16 + l16) * US + f0) = to_bf16x4(v);
+            *reinterpret_cast<vec4*>(ub + (nb * 16 + l16) * US + f0) = TT::cvt(v);
           }
         }
       }
@@ -614,10 +668,10 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       __syncthreads();
       TSDP_TICK(7)
       if (XPF) {
-        if (c + 1 < NC) gu.issue(W.up, D / 32, (c + 1) * (CH / 16) + wave * MBU, 0, lane);
-        else if (layer + 1 < net.L) gq.issue(net.layer[layer + 1].qkv, D / 32, wave, 0, lane, NW);
+        if (c + 1 < NC) gu.issue(W.up, KD, (c + 1) * (CH / 16) + wave * MBU, 0, lane);
+        else if (layer + 1 < net.L) gq.issue(net.layer[layer + 1].qkv, KD, wave, 0, lane, NW);
       } else {
-        gd.issue(W.dn, 4 * D / 32, wave * MBH, c * (CH / 32), lane);
+        gd.issue(W.dn, KM, wave * MBH, c * (KC), lane);
       }
       gd.run(ubuf + (C::UDB ? (c & 1) * NT * US : 0), US, h, lane);
       TSDP_TICK(9)
@@ -634,8 +688,8 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
     for (int j = 0; j < NBW; ++j) e[0][j] = f32x4{0, 0, 0, 0};
     const int nb0 = wave * NBW;
     if (nb0 < NB) {
-      FragGemm<1, NBW, D / 32> gh;
-      gh.issue(net.head, D / 32, 0, 0, lane);
+      FragGemm<TT, 1, NBW, KD> gh;
+      gh.issue(net.head, KD, 0, 0, lane);
       gh.run(act + nb0 * 16 * AS, AS, e, lane);
 #pragma unroll
       for (int j = 0; j < NBW; ++j) {
@@ -685,9 +739,10 @@ __global__ __launch_bounds__(C::THREADS, C::WG_PER_CU) void k_fused_forward(Fuse
 //   y <- mu_p(y, eps, t_k) + s sigma_{t_k} xi_{env,t_k},   t_k = t0 - k + 1,
 // and stores the input state, the drafter output and the noise of the transition in its ragged row.
 template <class C>
-__global__ __launch_bounds__(256) void k_fused_draft(FusedNet net, DraftIO io, int A) {
-  static_assert(C::NW == 4, "the drafter kernel runs four wavefronts");
-  constexpr int D = C::D, NT = C::NT, H = C::H;
+__global__ __launch_bounds__(C::THREADS) void k_fused_draft(FusedNet net, DraftIO io, int A) {
+  typedef typename C::TT TT;
+  typedef typename TT::elem elem;
+  constexpr int D = C::D, NT = C::NT, H = C::H, TH = C::THREADS, SGS = D + TT::PAD;
   constexpr int RPT = C::RPT;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   __shared__ int32_t envs[RPT], s_t0[RPT], s_keff[RPT], s_rowp[RPT], s_kmax;
@@ -696,7 +751,7 @@ __global__ __launch_bounds__(256) void k_fused_draft(FusedNet net, DraftIO io, i
   float* yt = reinterpret_cast<float*>(lds + C::LDS_B);              // [NT*A] latents
   float* et = yt + NT * A;                                           // [NT*A] drafter output
   float* modbuf = et + NT * A;                                       // [RPT][L*4D] FiLM vectors of this step
-  __bf16* sgbuf = reinterpret_cast<__bf16*>(modbuf + RPT * mod_stride);   // [16][D+8] SiLU(g), rows >= RPT zero
+  elem* sgbuf = reinterpret_cast<elem*>(modbuf + RPT * mod_stride);        // [16][D+pad] SiLU(g), rows >= RPT zero
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l16 = lane & 15, lg = lane >> 4;
   const int env0 = blockIdx.x * RPT;
   if (threadIdx.x == 0) s_kmax = 0;
@@ -713,8 +768,8 @@ __global__ __launch_bounds__(256) void k_fused_draft(FusedNet net, DraftIO io, i
     s_rowp[threadIdx.x] = live ? io.row_ptr[b] : 0;
     atomicMax(&s_kmax, ke);
   }
-  for (int i = threadIdx.x; i < 16 * (D + 8); i += 256) sgbuf[i] = (__bf16)0.0f;
-  for (int i = threadIdx.x; i < NT * A; i += 256) {
+  for (int i = threadIdx.x; i < 16 * SGS; i += TH) sgbuf[i] = (elem)0.0f;
+  for (int i = threadIdx.x; i < NT * A; i += TH) {
     const int b = env0 + i / DE;
     yt[i] = b < io.B ? io.y[(size_t)env0 * DE + i] : 0.0f;
   }
@@ -722,25 +777,25 @@ __global__ __launch_bounds__(256) void k_fused_draft(FusedNet net, DraftIO io, i
   const int kmax = s_kmax;
   for (int k = 1; k <= kmax; ++k) {
     // FiLM input of this step: SiLU(temb[t_k] + cemb[env]) as bf16 rows of the mod product's B operand
-    for (int i = threadIdx.x; i < RPT * D; i += 256) {
+    for (int i = threadIdx.x; i < RPT * D; i += TH) {
       const int r = i / D, c = i % D;
       int t = s_t0[r] - k + 1;
       t = t < 0 ? 0 : t;
       float g = net.temb[(size_t)t * D + c];
       if (net.cemb) g += net.cemb[(size_t)envs[r] * D + c];
-      sgbuf[r * (D + 8) + c] = (__bf16)silu_fast(g);
+      sgbuf[r * SGS + c] = (elem)silu_fast(g);
     }
     __syncthreads();
     {
-      constexpr int MBM = 4;
-      const int fpw = net.L * 4 * D / 64;               // mod fragments per wave
+      constexpr int MBM = 2;
+      const int fpw = net.L * 4 * D / (16 * C::NW);     // mod fragments per wave
       for (int f = 0; f < fpw; f += MBM) {
         f32x4 acc[MBM][1];
 #pragma unroll
         for (int mb = 0; mb < MBM; ++mb) acc[mb][0] = f32x4{0, 0, 0, 0};
-        FragGemm<MBM, 1, D / 32> gm;
-        gm.issue(net.modw, D / 32, wave * fpw + f, 0, lane);
-        gm.run(sgbuf, D + 8, acc, lane);
+        FragGemm<TT, MBM, 1, D / TT::KSTEP> gm;
+        gm.issue(net.modw, D / TT::KSTEP, wave * fpw + f, 0, lane);
+        gm.run(sgbuf, SGS, acc, lane);
         if (l16 < RPT) {
 #pragma unroll
           for (int mb = 0; mb < MBM; ++mb) {
@@ -756,7 +811,7 @@ __global__ __launch_bounds__(256) void k_fused_draft(FusedNet net, DraftIO io, i
     __syncthreads();
     // DDPM step of transition k for the environments that still draft
     const int nblk = DE >> 2;
-    for (int i = threadIdx.x; i < RPT * nblk; i += 256) {
+    for (int i = threadIdx.x; i < RPT * nblk; i += TH) {
       const int r = i / nblk, blk = i % nblk;
       if (k > s_keff[r]) continue;
       const int b = env0 + r;
@@ -784,7 +839,7 @@ __global__ __launch_bounds__(256) void k_fused_draft(FusedNet net, DraftIO io, i
     }
     __syncthreads();
   }
-  for (int i = threadIdx.x; i < NT * A; i += 256) {
+  for (int i = threadIdx.x; i < NT * A; i += TH) {
     const int b = env0 + i / DE;
     if (b < io.B) io.y[(size_t)env0 * DE + i] = yt[i];
   }
@@ -794,7 +849,7 @@ __global__ __launch_bounds__(256) void k_fused_draft(FusedNet net, DraftIO io, i
 // for all layers at once.  Tile: 128 rows x 256 outputs per workgroup; the SiLU input rows are built in LDS as
 // bf16 and the weights stream as fragments (FusedNet::modw).
 template <int D>
-__global__ __launch_bounds__(256) void k_mod_gemm(const bf16x8* __restrict__ modw, const float* __restrict__ modb,
+__global__ __launch_bounds__(256) void k_mod_gemm(const void* __restrict__ modw, const float* __restrict__ modb,
                                                   const float* __restrict__ temb, const float* __restrict__ cemb,
                                                   const int32_t* __restrict__ t_arr, int t_sub,
                                                   const int32_t* __restrict__ env_arr, int T, int Nm,
@@ -815,7 +870,7 @@ __global__ __launch_bounds__(256) void k_mod_gemm(const bf16x8* __restrict__ mod
     if (cemb) g += *reinterpret_cast<const f32x4*>(cemb + (size_t)(env_arr ? env_arr[row] : row) * D + c);
 #pragma unroll
     for (int j = 0; j < 4; ++j) g[j] = silu_fast(g[j]);
-    *reinterpret_cast<bf16x4*>(sg + r * AS + c) = to_bf16x4(g);
+    *reinterpret_cast<bf16x4*>(sg + r * AS + c) = TBF16::cvt(g);
   }
   __syncthreads();
   const int l16 = lane & 15, lg = lane >> 4;
@@ -827,7 +882,7 @@ __global__ __launch_bounds__(256) void k_mod_gemm(const bf16x8* __restrict__ mod
     for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
-    FragGemm<MB, NB, D / 32> gm;
+    FragGemm<TBF16, MB, NB, D / 32> gm;
     gm.issue(modw, D / 32, mf0, 0, lane);
     gm.run(sg, AS, acc, lane);
 #pragma unroll

@@ -127,22 +127,32 @@ uint16_t bf16_bits(float f) {
   return (uint16_t)b;
 }
 
-// Fragment order of a logical [rows, K] matrix for mfma 16x16x32 A operands: [rows/16][Kpad/32][64 lanes][8];
-// lane l of fragment (mf, ks) holds row mf*16 + l%16, columns ks*32 + (l/16)*8 .. +7.  src_row(lr) maps a
-// logical row to a row of W (or -1 for a zero row).
+// Fragment order of a logical [rows, K] matrix as MFMA A operands: [rows/16][Kpad/KSTEP][64 lanes][VW elements];
+// lane l of fragment (mf, ks) holds row mf*16 + l%16, columns ks*KSTEP + (l/16)*VW .. +VW-1, with VW = 8 bf16
+// (k-step 32) or VW = 4 fp32 (k-step 16).  src_row(lr) maps a logical row to a row of W (or -1 for a zero row).
+// Offsets returned by the callers are in bytes of `out`.
 template <typename RowMap>
-void pack_frags(std::vector<uint16_t>& out, const float* W, int K, int rows, RowMap src_row) {
-  const int mfs = (rows + 15) / 16, kss = (K + 31) / 32;
+void pack_frags(std::vector<uint8_t>& out, bool f32, const float* W, int K, int rows, RowMap src_row) {
+  const int VW = f32 ? 4 : 8, KSTEP = 4 * VW, ES = f32 ? 4 : 2;
+  const int mfs = (rows + 15) / 16, kss = (K + KSTEP - 1) / KSTEP;
   const size_t base = out.size();
-  out.resize(base + (size_t)mfs * kss * 64 * 8, 0);
+  out.resize(base + (size_t)mfs * kss * 64 * VW * ES, 0);
   for (int mf = 0; mf < mfs; ++mf)
     for (int ks = 0; ks < kss; ++ks)
       for (int l = 0; l < 64; ++l) {
         const int lr = mf * 16 + (l & 15);
         const int sr = lr < rows ? src_row(lr) : -1;
-        for (int i = 0; i < 8; ++i) {
-          const int col = ks * 32 + (l >> 4) * 8 + i;
-          if (sr >= 0 && col < K) out[base + (((size_t)mf * kss + ks) * 64 + l) * 8 + i] = bf16_bits(W[(size_t)sr * K + col]);
+        for (int i = 0; i < VW; ++i) {
+          const int col = ks * KSTEP + (l >> 4) * VW + i;
+          if (sr < 0 || col >= K) continue;
+          const float v = W[(size_t)sr * K + col];
+          uint8_t* dst = &out[base + ((((size_t)mf * kss + ks) * 64 + l) * VW + i) * ES];
+          if (f32) {
+            std::memcpy(dst, &v, 4);
+          } else {
+            const uint16_t b = bf16_bits(v);
+            std::memcpy(dst, &b, 2);
+          }
         }
       }
 }
@@ -162,14 +172,14 @@ void launch_verify(const FusedNet& n, const FusedIO& io, int A, int R_cap, hipSt
 template <class C>
 void launch_draft(const FusedNet& n, const DraftIO& io, int A, hipStream_t s) {
   auto kern = k_fused_draft<C>;
-  const int lds = C::LDS_B + 2 * C::NT * A * 4 + C::RPT * n.L * 4 * C::D * 4 + 16 * (C::D + 8) * 2;
+  const int lds = C::LDS_B + 2 * C::NT * A * 4 + C::RPT * n.L * 4 * C::D * 4 + 16 * (C::D + C::TT::PAD) * C::ES;
   static int attr_lds = 0;
   if (lds > attr_lds) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     attr_lds = lds;
   }
   const int tiles = (io.B + C::RPT - 1) / C::RPT;
-  hipLaunchKernelGGL(kern, dim3(tiles), dim3(256), lds, s, n, io, A);
+  hipLaunchKernelGGL(kern, dim3(tiles), dim3(C::THREADS), lds, s, n, io, A);
 }
 
 template <int D>
@@ -192,24 +202,28 @@ struct FusedKernels {
 };
 
 // shapes with compiled fused kernels
-bool find_fused(int D, int H, int heads, int cm, int S, int mlp_ratio, int L, FusedKernels& k) {
+bool find_fused(int dtype, int D, int H, int heads, int cm, int S, int mlp_ratio, int L, FusedKernels& k) {
   if (mlp_ratio != 4 || L > FUSED_MAX_LAYERS) return false;
-#define TSDP_SHAPE(D_, H_, HD_, CM_, SX_, NTV, CHV, HPV, NWV, NTS, NTB, CHD)                               \
-  if (D == D_ && H == H_ && heads == HD_ && cm == CM_ && (CM_ == 0 || S == SX_)) {                     \
-    constexpr int HPD = (D_ / HD_) >= 64 ? 1 : 64 / (D_ / HD_);                                        \
-    k.verify = launch_verify<FusedCfg<D_, NTV, H_, HD_, CM_, CHV, SX_, HPV, NWV>>;                     \
-    k.mod = launch_mod<D_>;                                                                            \
-    k.draft_small = launch_draft<FusedCfg<D_, NTS, H_, HD_, CM_, CHD, SX_, HPD, 4>>; k.rpt_small = NTS / H_; \
-    k.draft_big = launch_draft<FusedCfg<D_, NTB, H_, HD_, CM_, CHD, SX_, HPD, 4>>;   k.rpt_big = NTB / H_;   \
-    return true;                                                                                       \
+#define TSDP_SHAPE(TT_, DT_, D_, H_, HD_, CM_, SX_, NTV, CHV, HPV, NWV, NTS, NTB, CHD, HPD, NWD)                \
+  if (dtype == DT_ && D == D_ && H == H_ && heads == HD_ && cm == CM_ && (CM_ == 0 || S == SX_)) {             \
+    k.verify = launch_verify<FusedCfg<TT_, D_, NTV, H_, HD_, CM_, CHV, SX_, HPV, NWV>>;                        \
+    k.mod = DT_ == 1 ? launch_mod<D_> : nullptr;                                                               \
+    k.draft_small = launch_draft<FusedCfg<TT_, D_, NTS, H_, HD_, CM_, CHD, SX_, HPD, NWD>>; k.rpt_small = NTS / H_; \
+    k.draft_big = launch_draft<FusedCfg<TT_, D_, NTB, H_, HD_, CM_, CHD, SX_, HPD, NWD>>;   k.rpt_big = NTB / H_;   \
+    return true;                                                                                               \
   }
-  //          D   H  heads cm  S | verify: NT  CH  HP NW | draft: NT small, big, CH
-  TSDP_SHAPE(256, 16, 4, 0, 0, 64, 128, 1, 4, 16, 64, 128)
-  TSDP_SHAPE(384, 16, 6, 0, 0, 64, 192, 1, 4, 16, 64, 128)
-  TSDP_SHAPE(128, 16, 4, 0, 0, 128, 128, 2, 4, 16, 64, 128)
-  TSDP_SHAPE(192, 16, 6, 0, 0, 128, 128, 2, 4, 16, 64, 128)
-  TSDP_SHAPE(512, 32, 8, 1, 64, 64, 256, 2, 8, 32, 64, 128)
-  TSDP_SHAPE(256, 32, 8, 1, 64, 64, 256, 2, 4, 32, 64, 128)
+  //         type dtype  D   H heads cm  S | verify: NT  CH  HP NW | draft: NT small, big, CH, HP, NW
+  TSDP_SHAPE(TBF16, 1, 256, 16, 4, 0, 0, 64, 128, 1, 4, 16, 64, 128, 1, 4)
+  TSDP_SHAPE(TBF16, 1, 384, 16, 6, 0, 0, 64, 192, 1, 4, 16, 64, 128, 1, 4)
+  TSDP_SHAPE(TBF16, 1, 128, 16, 4, 0, 0, 128, 128, 2, 4, 16, 64, 128, 2, 4)
+  TSDP_SHAPE(TBF16, 1, 192, 16, 6, 0, 0, 128, 128, 2, 4, 16, 64, 128, 2, 4)
+  TSDP_SHAPE(TBF16, 1, 512, 32, 8, 1, 64, 64, 256, 2, 8, 32, 64, 128, 1, 4)
+  TSDP_SHAPE(TBF16, 1, 256, 32, 8, 1, 64, 64, 256, 2, 4, 32, 64, 128, 2, 4)
+  // fp32 networks on the fp32 matrix cores: one row (16 tokens) per workgroup, weights streamed per workgroup
+  TSDP_SHAPE(TF32, 0, 256, 16, 4, 0, 0, 16, 128, 1, 4, 16, 16, 128, 1, 4)
+  TSDP_SHAPE(TF32, 0, 128, 16, 4, 0, 0, 16, 128, 2, 4, 16, 16, 128, 2, 4)
+  TSDP_SHAPE(TF32, 0, 64, 16, 2, 0, 0, 16, 64, 2, 4, 16, 16, 64, 2, 4)
+  TSDP_SHAPE(TF32, 0, 32, 16, 2, 0, 0, 16, 32, 2, 2, 16, 16, 32, 2, 2)
 #undef TSDP_SHAPE
   return false;
 }
@@ -251,7 +265,8 @@ size_t layout_net(const tsdp_config& cf, int which, Net& n) {
 int build_fused(tsdp_ctx* c, Net& n, const std::vector<float>& w, const std::vector<float>& modw_cat, const FusedKernels& fk) {
   const tsdp_config& cf = c->cfg;
   const int d = n.d, m = n.m, L = n.L, DH = d / n.heads, HP = DH >= 64 ? 1 : 64 / DH;
-  std::vector<uint16_t> pk;
+  const bool f32 = cf.dtype == 0;
+  std::vector<uint8_t> pk;
   std::vector<float> qb((size_t)L * 3 * d);
   struct Off { size_t qkv, o, up, dn, cq, co; };
   std::vector<Off> off(L);
@@ -264,31 +279,31 @@ int build_fused(tsdp_ctx* c, Net& n, const std::vector<float>& w, const std::vec
       const int head = g * HP + r / (3 * DH), cls = (r / DH) % 3, cdim = r % DH;
       return cls * d + head * DH + cdim;
     };
-    off[l].qkv = pk.size(); pack_frags(pk, &w[o.qkv_w], d, 3 * d, qkv_row);
+    off[l].qkv = pk.size(); pack_frags(pk, f32, &w[o.qkv_w], d, 3 * d, qkv_row);
     for (int lr = 0; lr < 3 * d; ++lr) qb[(size_t)l * 3 * d + lr] = w[o.qkv_b + qkv_row(lr)];
-    off[l].o = pk.size(); pack_frags(pk, &w[o.o_w], d, d, ident);
-    off[l].up = pk.size(); pack_frags(pk, &w[o.up_w], d, m, ident);
-    off[l].dn = pk.size(); pack_frags(pk, &w[o.dn_w], m, d, ident);
+    off[l].o = pk.size(); pack_frags(pk, f32, &w[o.o_w], d, d, ident);
+    off[l].up = pk.size(); pack_frags(pk, f32, &w[o.up_w], d, m, ident);
+    off[l].dn = pk.size(); pack_frags(pk, f32, &w[o.dn_w], m, d, ident);
     if (cf.cond_mode == 1) {
-      off[l].cq = pk.size(); pack_frags(pk, &w[o.cq_w], d, d, ident);
-      off[l].co = pk.size(); pack_frags(pk, &w[o.co_w], d, d, ident);
+      off[l].cq = pk.size(); pack_frags(pk, f32, &w[o.cq_w], d, d, ident);
+      off[l].co = pk.size(); pack_frags(pk, f32, &w[o.co_w], d, d, ident);
     }
   }
   const size_t head_off = pk.size();
-  pack_frags(pk, &w[n.head_w], d, 16, [&](int r) { return r < cf.A ? r : -1; });
+  pack_frags(pk, f32, &w[n.head_w], d, 16, [&](int r) { return r < cf.A ? r : -1; });
   const size_t mod_off = pk.size();
-  pack_frags(pk, modw_cat.data(), d, L * 4 * d, ident);
-  uint16_t* dpk = nullptr;
+  pack_frags(pk, f32, modw_cat.data(), d, L * 4 * d, ident);
+  uint8_t* dpk = nullptr;
   float* dqb = nullptr;
   int rc;
   if ((rc = dev_alloc(c, &dpk, pk.size()))) return rc;
   if ((rc = dev_alloc(c, &dqb, qb.size()))) return rc;
-  HIPCHK(c, hipMemcpy(dpk, pk.data(), pk.size() * sizeof(uint16_t), hipMemcpyHostToDevice));
+  HIPCHK(c, hipMemcpy(dpk, pk.data(), pk.size(), hipMemcpyHostToDevice));
   HIPCHK(c, hipMemcpy(dqb, qb.data(), qb.size() * sizeof(float), hipMemcpyHostToDevice));
   FusedNet& f = n.fnet;
   std::memset(&f, 0, sizeof(f));
   f.L = L;
-  auto P = [&](size_t o) { return reinterpret_cast<const bf16x8*>(dpk + o); };
+  auto P = [&](size_t o) { return reinterpret_cast<const void*>(dpk + o); };
   for (int l = 0; l < L; ++l) {
     const LayerOff& o = n.lay[l];
     FusedLayer& fl = f.layer[l];
@@ -318,7 +333,7 @@ int build_fused(tsdp_ctx* c, Net& n, const std::vector<float>& w, const std::vec
   n.fused_mod = fk.mod;
   n.fused_draft_small = fk.draft_small; n.fused_draft_big = fk.draft_big;
   n.draft_rpt_small = fk.rpt_small; n.draft_rpt_big = fk.rpt_big;
-  n.path = "bf16-mfma-fused";
+  n.path = f32 ? "f32-mfma-fused" : "bf16-mfma-fused";
   return TSDP_OK;
 }
 
@@ -381,7 +396,13 @@ void forward(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t*
     return;
   }
   const tsdp_config& cf = c->cfg;
-  n.fused_mod(n.fnet, t_arr, t_sub, env_arr, cf.T, d_R, R_cap, c->mod, s);
+  if (n.fused_mod) {
+    n.fused_mod(n.fnet, t_arr, t_sub, env_arr, cf.T, d_R, R_cap, c->mod, s);
+  } else {                                            // fp32 networks: exact fp32 FiLM vectors from the operator kernels
+    hipLaunchKernelGGL(k_gvec, grid1((long long)R_cap * n.d, 256), dim3(256), 0, s, t_arr, t_sub, env_arr, n.temb,
+                       cf.cond_mode == 0 ? n.cemb : nullptr, c->sg, n.d, cf.T, d_R, R_cap);
+    linear<0>(s, c->sg, n.modw, n.modb, c->mod, R_cap, 1, n.L * 4 * n.d, n.d, d_R);
+  }
   FusedIO io;
   io.x_rows = x_rows; io.mod = c->mod; io.row_env = env_arr; io.d_R = d_R; io.R_cap = R_cap; io.eps_out = eps_out;
   const int stage = (&n == &c->net[0]) ? 1 : -1;          // only the base network's forward is the verify stage
@@ -392,10 +413,12 @@ void forward(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t*
 
 // dynamic LDS of the persistent drafter kernel for `rpt` environments per workgroup (mirrors launch_draft)
 size_t fused_draft_lds(const Net& n, const tsdp_config& cf, int rpt) {
-  const size_t D = n.d, NT = (size_t)rpt * cf.H, DH = D / n.heads, HP = DH >= 64 ? 1 : 64 / DH, CH = 128;
-  const size_t act = NT * (D + 8) * 2, q = HP * NT * (DH + 8) * 2, vt = HP * rpt * DH * (cf.H + 4) * 2;
-  const size_t scr = std::max(std::max(2 * q + vt, NT * (CH + 8) * 2), NT * 64 * 4);
-  return act + scr + 2 * 4 * NT * 4 + 2 * NT * cf.A * 4 + (size_t)rpt * n.L * 4 * D * 4 + 16 * (D + 8) * 2;
+  const size_t ES = cf.dtype == 0 ? 4 : 2, PAD = cf.dtype == 0 ? 4 : 8;
+  const size_t D = n.d, NT = (size_t)rpt * cf.H, DH = D / n.heads, HP = std::min<size_t>(n.heads, DH >= 64 ? 1 : 64 / DH);
+  const size_t CH = std::min<size_t>(128, D);
+  const size_t act = NT * (D + PAD) * ES, q = HP * NT * (DH + PAD) * ES, vt = HP * rpt * DH * (cf.H + 4) * ES;
+  const size_t scr = std::max(std::max(2 * q + vt, NT * (CH + PAD) * ES), NT * 64 * 4);
+  return act + scr + 2 * 4 * NT * 4 + 2 * NT * cf.A * 4 + (size_t)rpt * n.L * 4 * D * 4 + 16 * (D + PAD) * ES;  // upper bound
 }
 
 int ensure_workspace(tsdp_ctx* c) {
@@ -581,9 +604,9 @@ int tsdp_load_weights(tsdp_ctx* c, int which, const float* h_blob, size_t nbytes
   c->cond_set = false;
   n.fused = false;
   n.path = "f32-ops";
-  if (cf.dtype == 1 && !std::getenv("TSDP_DISABLE_FUSED")) {
+  if (!std::getenv("TSDP_DISABLE_FUSED")) {
     FusedKernels fk;
-    if (find_fused(n.d, cf.H, n.heads, cf.cond_mode, cf.cond_tokens, n.m / n.d, n.L, fk) &&
+    if (find_fused(cf.dtype, n.d, cf.H, n.heads, cf.cond_mode, cf.cond_tokens, n.m / n.d, n.L, fk) &&
         (rc = build_fused(c, n, w, modw, fk)))
       return rc;
   }

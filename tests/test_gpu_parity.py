@@ -101,7 +101,7 @@ def _stage_parity(wl, B, t0, K, s, env=None, clip=None, b_std=0.02, paths=None):
 
 def test_c1_stages():
     wl = ti.C1
-    g, ref = _stage_parity(wl, 1, np.array([9]), np.array([4]), np.array([1.0]))
+    g, ref = _stage_parity(wl, 1, np.array([9]), np.array([4]), np.array([1.0]), paths=("f32-mfma-fused", "f32-mfma-fused"))
     assert ref["n_adv"][0] >= 1
 
 
@@ -117,7 +117,7 @@ def test_c1_ragged_edges_with_clip():
 
 def test_c2_stages():
     wl = ti.C2
-    _stage_parity(wl, 1, np.array([99]), np.array([8]), np.array([1.0]))
+    _stage_parity(wl, 1, np.array([99]), np.array([8]), np.array([1.0]), paths=("f32-mfma-fused", "f32-mfma-fused"))
     _stage_parity(wl, 1, np.array([50]), np.array([8]), np.array([1.0]))
 
 
@@ -292,3 +292,11 @@ def test_chain_bf16_invariants():
     # at least one step per round and never more than t0 + 1 in total
     assert ((a + r >= t0 + 1) | (t0 < 0)).all()
     S["ctx"].close()
+
+
+def test_operator_kernel_path_for_shapes_without_a_fused_kernel():
+    # a width with no compiled fused kernel (d = 96) runs the general fp32 operator kernels, both conditioning modes
+    for cm, extra in ((0, {}), (1, dict(cond_dim=24, cond_tokens=5))):
+        wl = ti.small_variant(ti.C1, B=3, cond_mode=cm, base=ti.NetShape(2, 96, 3), draft=ti.NetShape(1, 48, 3), **extra)
+        t0 = np.array([9, 4, 0]); K = np.array([4, 3, 2]); s = np.array([1.0, 1.3, 1.0])
+        _stage_parity(wl, 3, t0, K, s, paths=("f32-ops", "f32-ops"))
