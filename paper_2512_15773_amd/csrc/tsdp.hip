@@ -41,6 +41,8 @@ struct Net {
   bool fused = false;
   FusedNet fnet;
   void (*fused_verify)(const FusedNet&, const FusedIO&, int A, int R_cap, hipStream_t) = nullptr;
+  void (*fused_verify_few)(const FusedNet&, const FusedIO&, int A, int R_cap, hipStream_t) = nullptr;
+  int verify_rpt = 1;
   void (*fused_mod)(const FusedNet&, const int32_t*, int, const int32_t*, int, const int32_t*, int, float*, hipStream_t) = nullptr;
   void (*fused_draft_small)(const FusedNet&, const DraftIO&, int A, hipStream_t) = nullptr;   // few environments per workgroup
   void (*fused_draft_big)(const FusedNet&, const DraftIO&, int A, hipStream_t) = nullptr;     // many environments per workgroup
@@ -194,6 +196,9 @@ void launch_mod(const FusedNet& n, const int32_t* t_arr, int t_sub, const int32_
 }
 
 struct FusedKernels {
+  // variant for batches of at most one tile per CU: one 8-wave workgroup per CU instead of two 4-wave ones
+  void (*verify_few)(const FusedNet&, const FusedIO&, int, int, hipStream_t) = nullptr;
+  int rpt_verify = 0;
   void (*mod)(const FusedNet&, const int32_t*, int, const int32_t*, int, const int32_t*, int, float*, hipStream_t) = nullptr;
   void (*verify)(const FusedNet&, const FusedIO&, int, int, hipStream_t) = nullptr;
   void (*draft_small)(const FusedNet&, const DraftIO&, int, hipStream_t) = nullptr;
@@ -207,12 +212,17 @@ bool find_fused(int dtype, int D, int H, int heads, int cm, int S, int mlp_ratio
 #define TSDP_SHAPE(TT_, DT_, D_, H_, HD_, CM_, SX_, NTV, CHV, HPV, NWV, NTS, NTB, CHD, HPD, NWD)                \
   if (dtype == DT_ && D == D_ && H == H_ && heads == HD_ && cm == CM_ && (CM_ == 0 || S == SX_)) {             \
     k.verify = launch_verify<FusedCfg<TT_, D_, NTV, H_, HD_, CM_, CHV, SX_, HPV, NWV>>;                        \
+    k.rpt_verify = NTV / H_;                                                                                   \
     k.mod = DT_ == 1 ? launch_mod<D_> : nullptr;                                                               \
     k.draft_small = launch_draft<FusedCfg<TT_, D_, NTS, H_, HD_, CM_, CHD, SX_, HPD, NWD>>; k.rpt_small = NTS / H_; \
     k.draft_big = launch_draft<FusedCfg<TT_, D_, NTB, H_, HD_, CM_, CHD, SX_, HPD, NWD>>;   k.rpt_big = NTB / H_;   \
     return true;                                                                                               \
   }
   //         type dtype  D   H heads cm  S | verify: NT  CH  HP NW | draft: NT small, big, CH, HP, NW
+  if (dtype == 1 && D == 256 && H == 16 && heads == 4 && cm == 0)
+    k.verify_few = launch_verify<FusedCfg<TBF16, 256, 64, 16, 4, 0, 256, 0, 2, 8>>;
+  if (dtype == 1 && D == 384 && H == 16 && heads == 6 && cm == 0)
+    k.verify_few = launch_verify<FusedCfg<TBF16, 384, 64, 16, 6, 0, 256, 0, 2, 8>>;
   TSDP_SHAPE(TBF16, 1, 256, 16, 4, 0, 0, 64, 128, 1, 4, 16, 64, 128, 1, 4)
   TSDP_SHAPE(TBF16, 1, 384, 16, 6, 0, 0, 64, 192, 1, 4, 16, 64, 128, 1, 4)
   TSDP_SHAPE(TBF16, 1, 128, 16, 4, 0, 0, 128, 128, 2, 4, 16, 64, 128, 2, 4)
@@ -330,6 +340,8 @@ int build_fused(tsdp_ctx* c, Net& n, const std::vector<float>& w, const std::vec
 #endif
   n.fused = true;
   n.fused_verify = fk.verify;
+  n.fused_verify_few = fk.verify_few;
+  n.verify_rpt = fk.rpt_verify;
   n.fused_mod = fk.mod;
   n.fused_draft_small = fk.draft_small; n.fused_draft_big = fk.draft_big;
   n.draft_rpt_small = fk.rpt_small; n.draft_rpt_big = fk.rpt_big;
@@ -407,7 +419,8 @@ void forward(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t*
   io.x_rows = x_rows; io.mod = c->mod; io.row_env = env_arr; io.d_R = d_R; io.R_cap = R_cap; io.eps_out = eps_out;
   const int stage = (&n == &c->net[0]) ? 1 : -1;          // only the base network's forward is the verify stage
   if (stage == 1) tick(c, 1, 0, s);
-  n.fused_verify(n.fnet, io, cf.A, R_cap, s);
+  const bool few = n.fused_verify_few && (R_cap + n.verify_rpt - 1) / n.verify_rpt <= 288;
+  (few ? n.fused_verify_few : n.fused_verify)(n.fnet, io, cf.A, R_cap, s);
   if (stage == 1) tick(c, 1, 1, s);
 }
 
