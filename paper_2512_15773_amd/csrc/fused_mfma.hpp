@@ -269,6 +269,17 @@ struct FusedCfg {
   static_assert(CM == 0 || (SX % 16 == 0 && SX >= 16 && ES == 2), "cross-attention: bf16 only, tokens a multiple of 16");
 };
 
+// Configuration of the persistent drafter: a rollout has few workgroups in flight (one per environment tile), so no
+// second wave hides latency; it therefore always prefetches across phases and double-buffers the LDS operands.
+template <class Base>
+struct DraftCfg : Base {
+#ifndef TSDP_DRAFT_XPF
+#define TSDP_DRAFT_XPF 1
+#endif
+  static constexpr bool XPF = TSDP_DRAFT_XPF;
+  static constexpr int BD = TSDP_DRAFT_XPF ? 2 : Base::BD;
+};
+
 // One forward pass for the tile.  xt: LDS fp32 [NT][A] latent tokens (may alias the scratch region: it is
 // consumed before the first barrier-protected write).  modp: FiLM vectors of local row r at
 // modp + min(r, mod_rows-1)*mod_stride (global or LDS).  env_of_row: environment of local row r (cross-attention).
@@ -807,7 +818,7 @@ __global__ __launch_bounds__(C::THREADS) void k_fused_draft(FusedNet net, DraftI
       }
     }
     __syncthreads();
-    fused_body<C>(net, lds, yt, A, modbuf, mod_stride, RPT, envs, et, NT);
+    fused_body<DraftCfg<C>>(net, lds, yt, A, modbuf, mod_stride, RPT, envs, et, NT);
     __syncthreads();
     // DDPM step of transition k for the environments that still draft
     const int nblk = DE >> 2;
