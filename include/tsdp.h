@@ -144,6 +144,13 @@ int tsdp_chain(tsdp_ctx* ctx, int B, float* d_x, int32_t* d_t, const int32_t* d_
                const int32_t* d_env_id, const float* d_lambda, int max_rounds, int check_every,
                int32_t* d_tot_accept, int32_t* d_tot_drafts, int32_t* d_tot_rounds, int32_t* h_rounds, void* stream);
 
+/* Forward value of the drafter's distillation objective (Section 3.2, Draft Model Training) over R rows:
+ * L_pred = mean_r |eps_p[r] - eps_q[r]|^2, L_norm = mean over rows with t > 0 of |(mu_p - mu_q)/sigma_t|^2 (DDPM
+ * means from the same state, unscaled sigma_t), L = lambda1 L_pred + lambda2 L_norm.  fp64 reduction in a fixed
+ * order (deterministic).  d_states is read only when x0 clipping is on.  out: d_loss[3] = {L_pred, L_norm, L}. */
+int tsdp_distill_loss(tsdp_ctx* ctx, int R, const int32_t* d_row_t, const float* d_states, const float* d_eps_p,
+                      const float* d_eps_q, float lambda1, float lambda2, double* d_loss, void* stream);
+
 /* Synchronises `stream` and returns the device status word accumulated since the last call:
  * bit 0 = some K was outside 0..K_max (clamped), bit 1 = some t0 was >= T (treated as T-1). */
 int tsdp_status(tsdp_ctx* ctx, void* stream, int32_t* h_status);

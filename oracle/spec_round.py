@@ -212,3 +212,26 @@ def base_chain_step(base, sched, x, t, sigma_scale, env_id, seed, cond, clip=Non
     z = philox.normal(seed, env_id, t, int(np.prod(x.shape[1:]))).reshape(x.shape)
     sig = (np.asarray(sigma_scale, dtype=np.float64) * sched.sigma[t]).reshape((-1,) + (1,) * (x.ndim - 1))
     return mu + sig * z
+
+
+def distill_loss(sched, row_t, states, eps_p, eps_q, lam1, lam2, clip=None):
+    """Forward value of the drafter's distillation objective (Section 3.2, Draft Model Training):
+    L_pred = E ||m_hat - m||^2 on the network outputs, L_norm = E ||(mu_hat - mu)/sigma_t||^2 on the DDPM means,
+    L = lam1 L_pred + lam2 L_norm, the expectations taken as means over the given rows.  Rows at t = 0 have
+    sigma_0 = 0 and are left out of L_norm (reading: the normalised term is defined for noisy steps only)."""
+    row_t = np.asarray(row_t, dtype=np.int64)
+    eps_p = np.asarray(eps_p, dtype=np.float64); eps_q = np.asarray(eps_q, dtype=np.float64)
+    R = len(row_t)
+    if R == 0:
+        return 0.0, 0.0, 0.0
+    diff = (eps_p - eps_q).reshape(R, -1)
+    l_pred = float(np.mean(np.sum(diff * diff, axis=1)))
+    mu_p = sched.posterior_mean(states, eps_p, row_t, clip).reshape(R, -1)
+    mu_q = sched.posterior_mean(states, eps_q, row_t, clip).reshape(R, -1)
+    noisy = row_t > 0
+    if noisy.any():
+        d = (mu_p[noisy] - mu_q[noisy]) / sched.sigma[row_t[noisy]][:, None]
+        l_norm = float(np.mean(np.sum(d * d, axis=1)))
+    else:
+        l_norm = 0.0
+    return l_pred, l_norm, lam1 * l_pred + lam2 * l_norm

@@ -340,4 +340,78 @@ __global__ void k_fill_i32(int32_t* p, int n, int32_t v) {
   if (i < n) p[i] = v;
 }
 
+// Distillation-loss forward: per row the squared distance of the two noise predictions and of the two posterior
+// means in units of sigma_t, reduced in fp64.  One row per group of 16 lanes; every workgroup writes one partial
+// pair, a second single-workgroup kernel adds the partials in a fixed order (deterministic result).
+template <bool CLIP>
+__global__ __launch_bounds__(256) void k_distill_partial(int R, int D, const int32_t* __restrict__ row_t,
+                                                         const float* __restrict__ states, const float* __restrict__ eps_p,
+                                                         const float* __restrict__ eps_q, SchedTables tb, float clip_val,
+                                                         double* __restrict__ partial) {
+  __shared__ double sp[16], sn[16];
+  const int lane = threadIdx.x & 63, grp = threadIdx.x >> 4, gl = threadIdx.x & 15;
+  const int r = blockIdx.x * 16 + grp;
+  const int nb = D >> 2;
+  double pred = 0.0, nrm = 0.0;
+  if (r < R) {
+    const int t = row_t[r];
+    const double sa = tb.sqrt_abar[t], s1 = tb.sqrt_1m[t], c0 = tb.c0[t], sig = tb.sigma[t], cv = clip_val;
+    const float4* ep = reinterpret_cast<const float4*>(eps_p + (long long)r * D);
+    const float4* eq = reinterpret_cast<const float4*>(eps_q + (long long)r * D);
+    const float4* st = reinterpret_cast<const float4*>(states + (long long)r * D);
+    double dd = 0.0, dm = 0.0;
+    for (int i = gl; i < nb; i += 16) {
+      const float4 p = ep[i], q = eq[i];
+      const float pp[4] = {p.x, p.y, p.z, p.w}, qq[4] = {q.x, q.y, q.z, q.w};
+      float yy[4] = {0, 0, 0, 0};
+      if (CLIP) { const float4 y = st[i]; yy[0] = y.x; yy[1] = y.y; yy[2] = y.z; yy[3] = y.w; }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const double de = (double)pp[j] - (double)qq[j];
+        dd = fma(de, de, dd);
+        if (CLIP) {
+          const double xp = fmin(fmax(((double)yy[j] - s1 * (double)pp[j]) / sa, -cv), cv);
+          const double xq = fmin(fmax(((double)yy[j] - s1 * (double)qq[j]) / sa, -cv), cv);
+          dm = fma(xp - xq, xp - xq, dm);
+        }
+      }
+    }
+    dd = group16_sum(dd); dm = group16_sum(dm);
+    pred = dd;
+    if (t > 0) {
+      const double kap = CLIP ? c0 / sig : (c0 * s1) / (sa * sig);
+      nrm = kap * kap * (CLIP ? dm : dd);
+    }
+  }
+  (void)lane;
+  if (gl == 0) { sp[grp] = pred; sn[grp] = nrm; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double a = 0.0, b = 0.0;
+    for (int i = 0; i < 16; ++i) { a += sp[i]; b += sn[i]; }
+    partial[2 * blockIdx.x] = a; partial[2 * blockIdx.x + 1] = b;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_distill_final(int nparts, int R, const int32_t* __restrict__ row_t,
+                                                       const double* __restrict__ partial, float lam1, float lam2,
+                                                       double* __restrict__ loss) {
+  __shared__ double sa[256], sb[256];
+  __shared__ int sc[256];
+  double a = 0.0, b = 0.0;
+  int noisy = 0;
+  for (int i = threadIdx.x; i < nparts; i += 256) { a += partial[2 * i]; b += partial[2 * i + 1]; }
+  for (int i = threadIdx.x; i < R; i += 256) noisy += row_t[i] > 0;
+  sa[threadIdx.x] = a; sb[threadIdx.x] = b; sc[threadIdx.x] = noisy;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if ((int)threadIdx.x < o) { sa[threadIdx.x] += sa[threadIdx.x + o]; sb[threadIdx.x] += sb[threadIdx.x + o]; sc[threadIdx.x] += sc[threadIdx.x + o]; }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double lp = R > 0 ? sa[0] / R : 0.0, ln = sc[0] > 0 ? sb[0] / sc[0] : 0.0;
+    loss[0] = lp; loss[1] = ln; loss[2] = (double)lam1 * lp + (double)lam2 * ln;
+  }
+}
+
 }  // namespace tsdp

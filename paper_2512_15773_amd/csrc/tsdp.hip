@@ -64,6 +64,7 @@ struct tsdp_ctx {
   int cond_B = 0;
   int32_t* status = nullptr;
   int32_t* live = nullptr;      // environments still running (chain driver)
+  double* loss_partial = nullptr;   // per-workgroup partial sums of the distillation loss
   int32_t* K_eff = nullptr;     // [B_max]
   // network workspace (lazy)
   bool ws_ready = false;
@@ -846,6 +847,32 @@ int tsdp_chain(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K,
     }
   }
   if (h_rounds) *h_rounds = rounds;
+  HIPCHK(c, hipGetLastError());
+  return TSDP_OK;
+}
+
+int tsdp_distill_loss(tsdp_ctx* c, int R, const int32_t* d_row_t, const float* d_states, const float* d_eps_p,
+                      const float* d_eps_q, float lambda1, float lambda2, double* d_loss, void* stream) {
+  if (!c) return TSDP_E_INVAL;
+  if (R < 0 || (long long)R > (long long)c->cfg.B_max * c->cfg.K_max) return fail(c, TSDP_E_SHAPE, "R outside 0..B_max*K_max");
+  if (!d_loss || (R > 0 && (!d_row_t || !d_states || !d_eps_p || !d_eps_q)))
+    return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_distill_loss");
+  hipStream_t s = (hipStream_t)stream;
+  const int parts = (R + 15) / 16;
+  if (!c->loss_partial) {
+    int rc = dev_alloc(c, &c->loss_partial, 2 * (((size_t)c->cfg.B_max * c->cfg.K_max + 15) / 16) + 2);
+    if (rc) return rc;
+  }
+  if (parts > 0) {
+    if (c->cfg.clip_x0)
+      hipLaunchKernelGGL(k_distill_partial<true>, dim3(parts), dim3(256), 0, s, R, c->D, d_row_t, d_states, d_eps_p, d_eps_q,
+                         c->tb, c->cfg.clip_val, c->loss_partial);
+    else
+      hipLaunchKernelGGL(k_distill_partial<false>, dim3(parts), dim3(256), 0, s, R, c->D, d_row_t, d_states, d_eps_p, d_eps_q,
+                         c->tb, c->cfg.clip_val, c->loss_partial);
+  }
+  hipLaunchKernelGGL(k_distill_final, dim3(1), dim3(256), 0, s, parts, R, d_row_t, (const double*)c->loss_partial, lambda1,
+                     lambda2, d_loss);
   HIPCHK(c, hipGetLastError());
   return TSDP_OK;
 }

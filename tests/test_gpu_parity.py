@@ -300,3 +300,22 @@ def test_operator_kernel_path_for_shapes_without_a_fused_kernel():
         wl = ti.small_variant(ti.C1, B=3, cond_mode=cm, base=ti.NetShape(2, 96, 3), draft=ti.NetShape(1, 48, 3), **extra)
         t0 = np.array([9, 4, 0]); K = np.array([4, 3, 2]); s = np.array([1.0, 1.3, 1.0])
         _stage_parity(wl, 3, t0, K, s, paths=("f32-ops", "f32-ops"))
+
+
+def test_distillation_loss_matches_oracle():
+    wl = ti.small_variant(ti.C2, B=9, base=ti.NetShape(2, 256, 4))
+    for clip in (None, 1.5):
+        S = _setup(wl, 9, clip=clip)
+        t0 = np.array([99, 70, 40, 20, 9, 3, 1, 0, -1]); K = np.full(9, 8); s = np.ones(9)
+        rows = _gpu_draft(S, t0, K, s, None)
+        S["ctx"].tsdp_verify(9, rows)
+        R = int(rows["row_ptr"].cpu().numpy()[-1])
+        got = S["ctx"].tsdp_distill_loss(R, rows, 0.7, 0.3).cpu().numpy()
+        ref = sr.distill_loss(S["sched"], rows["row_t"].cpu().numpy()[:R], rows["states"].cpu().numpy()[:R],
+                              rows["eps_p"].cpu().numpy()[:R], rows["eps_q"].cpu().numpy()[:R],
+                              float(np.float32(0.7)), float(np.float32(0.3)), clip)   # the ABI takes the weights as fp32
+        np.testing.assert_allclose(got, ref, rtol=1e-10)
+        again = S["ctx"].tsdp_distill_loss(R, rows, 0.7, 0.3).cpu().numpy()
+        assert got.tobytes() == again.tobytes()                            # fixed reduction order
+        assert got[0] > 0 and got[1] > 0
+        S["ctx"].close()

@@ -125,3 +125,30 @@ def test_threshold_rule_is_deterministic_monotone_and_matches_its_definition():
     assert sr.accept(sched, row_ptr, row_t, s, None, 1, states, eps_p, eps_q, xi, y_last, lam=1e-12)["flags"].all()
     one = sr.accept(sched, row_ptr, row_t, s, None, 1, states, eps_p, eps_q, xi, y_last, lam=1.0)
     np.testing.assert_array_equal(one["flags"], (one["logratio"] >= 0).astype(np.uint8))
+
+
+def test_distillation_loss_closed_forms():
+    # eps_hat = eps + c  =>  L_pred = D c^2 and, without clipping, mu_hat - mu = -(beta_t/(sqrt(alpha_t) sqrt(1-abar_t))) c
+    # (textbook eps-form of the posterior mean), so L_norm = D c^2 mean_t (beta_t/(sqrt(alpha_t) sqrt(1-abar_t) sigma_t))^2.
+    from oracle.ddpm import Schedule
+    T, R, D, c = 100, 64, 12, 0.3
+    sched = Schedule(T, 1, round_fp32=False)
+    rng = np.random.default_rng(9)
+    row_t = rng.integers(1, T, R)
+    states = rng.standard_normal((R, D)); eps_q = rng.standard_normal((R, D)); eps_p = eps_q + c
+    lp, ln, l = sr.distill_loss(sched, row_t, states, eps_p, eps_q, 0.7, 0.2)
+    beta, abar = sched.beta, sched.abar
+    abar_prev = np.concatenate([[1.0], abar[:-1]])
+    with np.errstate(divide="ignore"):                                 # entry t = 0 (sigma_0 = 0) is never indexed
+        kap = beta / (np.sqrt(1 - beta) * np.sqrt(1 - abar)) / np.sqrt(beta * (1 - abar_prev) / (1 - abar))
+    assert abs(lp - D * c * c) < 1e-12
+    assert abs(ln - D * c * c * np.mean(kap[row_t] ** 2)) < 1e-9 * ln
+    assert abs(l - (0.7 * lp + 0.2 * ln)) < 1e-12
+    # identical networks give zero; t = 0 rows contribute to L_pred only
+    assert sr.distill_loss(sched, row_t, states, eps_q, eps_q, 1, 1) == (0.0, 0.0, 0.0)
+    lp0, ln0, _ = sr.distill_loss(sched, np.zeros(R, int), states, eps_p, eps_q, 1, 1)
+    assert abs(lp0 - D * c * c) < 1e-12 and ln0 == 0.0
+    # the normalised term is the mean |d|^2 of the acceptance ratio at sigma scale 1
+    mu_p = sched.posterior_mean(states, eps_p, row_t); mu_q = sched.posterior_mean(states, eps_q, row_t)
+    _, dd, _ = sr.log_ratio(mu_p, mu_q, sched.sigma[row_t], np.zeros((R, D)))
+    assert abs(ln - dd.mean()) < 1e-9 * ln
