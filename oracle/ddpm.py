@@ -17,7 +17,11 @@ class Schedule:
     implementation) and then used in fp64 arithmetic.
     """
 
-    def __init__(self, T, schedule, beta0=1e-4, beta1=0.02, round_fp32=True):
+    def __init__(self, T, schedule, beta0=1e-4, beta1=0.02, round_fp32=True, sampler=0, eta=1.0):
+        """sampler 0: DDPM posterior (above).  sampler 1: DDIM(eta), eta in (0, 1] (the paper names "DDPM or DDIM
+        scheduler" without formulas; textbook DDIM): sigma_t = eta sqrt((1-abar_{t-1})/(1-abar_t)) sqrt(1-abar_t/abar_{t-1}),
+        mean = sqrt(abar_{t-1}) x0_hat + sqrt(1-abar_{t-1}-sigma_t^2) eps.  Both are written as
+        mu = c0 x0_hat + cx x + ce eps  (DDPM: ce = 0; DDIM: cx = 0)."""
         i = np.arange(T, dtype=np.float64)
         if schedule == 0:                       # linear
             beta = np.linspace(beta0, beta1, T, dtype=np.float64)
@@ -32,20 +36,34 @@ class Schedule:
         self.T = T
         self.beta = beta
         self.abar = abar
-        tables = dict(
-            sqrt_abar=np.sqrt(abar),                                   # x_t = sqrt_abar x0 + sqrt_1m eps
-            sqrt_1m=np.sqrt(1.0 - abar),
-            c0=np.sqrt(abar_prev) * beta / (1.0 - abar),               # posterior mean coefficient of x0_hat
-            cx=np.sqrt(alpha) * (1.0 - abar_prev) / (1.0 - abar),      # posterior mean coefficient of x_t
-            sigma=np.sqrt(beta * (1.0 - abar_prev) / (1.0 - abar)),    # posterior std, 0 at t = 0
-        )
+        if sampler == 0:
+            tables = dict(
+                sqrt_abar=np.sqrt(abar),                                   # x_t = sqrt_abar x0 + sqrt_1m eps
+                sqrt_1m=np.sqrt(1.0 - abar),
+                c0=np.sqrt(abar_prev) * beta / (1.0 - abar),               # posterior mean coefficient of x0_hat
+                cx=np.sqrt(alpha) * (1.0 - abar_prev) / (1.0 - abar),      # posterior mean coefficient of x_t
+                ce=np.zeros(T),                                            # coefficient of the predicted noise
+                sigma=np.sqrt(beta * (1.0 - abar_prev) / (1.0 - abar)),    # posterior std, 0 at t = 0
+            )
+        elif sampler == 1:
+            if not (0.0 < eta <= 1.0):
+                raise ValueError("DDIM eta must be in (0, 1]: eta = 0 has no Gaussian transition to test against")
+            sig = eta * np.sqrt((1.0 - abar_prev) / (1.0 - abar)) * np.sqrt(1.0 - abar / abar_prev)
+            tables = dict(
+                sqrt_abar=np.sqrt(abar), sqrt_1m=np.sqrt(1.0 - abar),
+                c0=np.sqrt(abar_prev), cx=np.zeros(T),
+                ce=np.sqrt(np.maximum(1.0 - abar_prev - sig ** 2, 0.0)),
+                sigma=sig,
+            )
+        else:
+            raise ValueError("unknown sampler")
         for k, v in tables.items():
             if round_fp32:
                 v = v.astype(np.float32).astype(np.float64)
             setattr(self, k, v)
 
     def posterior_mean(self, x, eps, t, clip=None):
-        """mu_t(x, eps): x0_hat = (x - sqrt(1-abar) eps)/sqrt(abar) [clamped], mu = c0 x0_hat + cx x.
+        """mu_t(x, eps): x0_hat = (x - sqrt(1-abar) eps)/sqrt(abar) [clamped], mu = c0 x0_hat + cx x + ce eps.
 
         x, eps: [R, ...]; t: [R] int.  Returns fp64.
         """
@@ -56,4 +74,4 @@ class Schedule:
         x0 = (x - self.sqrt_1m[t].reshape(sh) * eps) / self.sqrt_abar[t].reshape(sh)
         if clip is not None:
             x0 = np.clip(x0, -clip, clip)
-        return self.c0[t].reshape(sh) * x0 + self.cx[t].reshape(sh) * x
+        return self.c0[t].reshape(sh) * x0 + self.cx[t].reshape(sh) * x + self.ce[t].reshape(sh) * eps

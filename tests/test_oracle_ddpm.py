@@ -53,3 +53,29 @@ def test_fp32_rounding_is_small_and_clip_only_touches_x0():
     x0 = x / b.sqrt_abar[50]
     np.testing.assert_allclose(b.posterior_mean(x, e, t, clip=1.0), b.c0[50] * 1.0 + b.cx[50] * x)
     assert np.all(x0 > 1.0)
+
+
+def test_ddim_tables():
+    T = 100
+    for kind in (0, 1):
+        d = Schedule(T, kind, 1e-4, 0.02, round_fp32=False)
+        i = Schedule(T, kind, 1e-4, 0.02, round_fp32=False, sampler=1, eta=1.0)
+        # eta = 1: the DDIM transition is the DDPM posterior (same variance, same mean when x0 is not clamped)
+        np.testing.assert_allclose(i.sigma, d.sigma, rtol=1e-12, atol=1e-15)
+        rng = np.random.default_rng(1)
+        x = rng.standard_normal((T, 4)); e = rng.standard_normal((T, 4)); t = np.arange(T)
+        np.testing.assert_allclose(i.posterior_mean(x, e, t), d.posterior_mean(x, e, t), rtol=1e-9, atol=1e-12)
+        # any eta: marginal consistency  abar_{t-1} = c0^2 abar-free form:  c0 = sqrt(abar_{t-1}),  ce^2 + sigma^2 = 1 - abar_{t-1}
+        h = Schedule(T, kind, 1e-4, 0.02, round_fp32=False, sampler=1, eta=0.4)
+        abar_prev = np.concatenate([[1.0], h.abar[:-1]])
+        np.testing.assert_allclose(h.c0, np.sqrt(abar_prev), rtol=1e-12)
+        np.testing.assert_allclose(h.ce ** 2 + h.sigma ** 2, 1 - abar_prev, rtol=1e-9, atol=1e-15)
+        np.testing.assert_allclose(h.sigma, 0.4 * d.sigma, rtol=1e-12, atol=1e-15)
+        assert h.sigma[0] == 0 and np.all(h.cx == 0) and h.ce[0] == 0       # last step returns x0_hat
+        # a state built from (x0, eps) maps to sqrt(abar_{t-1}) x0 + ce eps: the noise direction is kept
+        x0 = rng.standard_normal((T, 4)); eps = rng.standard_normal((T, 4))
+        xt = h.sqrt_abar[:, None] * x0 + h.sqrt_1m[:, None] * eps
+        np.testing.assert_allclose(h.posterior_mean(xt, eps, t), np.sqrt(abar_prev)[:, None] * x0 + h.ce[:, None] * eps,
+                                   rtol=1e-9, atol=1e-12)
+    with pytest.raises(ValueError):
+        Schedule(T, 0, sampler=1, eta=0.0)

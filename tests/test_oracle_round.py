@@ -19,6 +19,24 @@ class LinearEps:
         return self.a[t].reshape(sh) * x + self.b[t].reshape(sh)
 
 
+def _closed_form_chain_ddim(T, kind, a, b, s, eta, beta0=1e-4, beta1=0.02):
+    """Final mean / variance of the base DDIM(eta) chain for eps(x,t) = a_t x + b_t, from the textbook update
+    x' = sqrt(abar') (x - sqrt(1-abar) eps)/sqrt(abar) + sqrt(1-abar'-sig^2) eps + s sig z."""
+    if kind == 0:
+        beta = np.linspace(beta0, beta1, T)
+    else:
+        f = lambda i: np.cos(((i / T) + 0.008) / 1.008 * np.pi / 2) ** 2
+        beta = np.minimum(1 - f(np.arange(1, T + 1)) / f(np.arange(T)), 0.999)
+    abar = np.cumprod(1 - beta); abar_prev = np.concatenate([[1.0], abar[:-1]])
+    m, v = 0.0, 1.0
+    for t in range(T - 1, -1, -1):
+        sig = eta * np.sqrt((1 - abar_prev[t]) / (1 - abar[t])) * np.sqrt(1 - abar[t] / abar_prev[t])
+        r = np.sqrt(abar_prev[t] / abar[t]); ce = np.sqrt(max(1 - abar_prev[t] - sig ** 2, 0.0))
+        A = r + (ce - r * np.sqrt(1 - abar[t])) * a[t]; Bc = (ce - r * np.sqrt(1 - abar[t])) * b[t]
+        m, v = A * m + Bc, A * A * v + (s * sig) ** 2
+    return m, v
+
+
 def _closed_form_chain(T, kind, a, b, s, beta0=1e-4, beta1=0.02):
     """Mean and variance of x_{-1} for x_{T-1} ~ N(0,1) under the base chain, from the textbook
     posterior written in its eps-form: x' = (x - beta/sqrt(1-abar) eps)/sqrt(alpha) + s sigma z."""
@@ -158,3 +176,16 @@ def test_round_is_independent_of_batch_composition_and_row_table_is_consistent()
             np.testing.assert_allclose(d["states"][r0 + 1], mu + s[b] * sched.sigma[t] * d["xi"][r0], rtol=1e-12)
     # with random independent nets some draft is rejected somewhere and the reflected output differs from y
     assert (full["n_accept"] < d["K_eff"]).any()
+
+
+def test_ddim_chain_with_imperfect_drafter_keeps_the_base_law():
+    T, n = 10, 60_000
+    rng = np.random.default_rng(12)
+    a = rng.uniform(0.2, 0.8, T); b = rng.uniform(-0.5, 0.5, T)
+    base = LinearEps(a, b)
+    drafter = LinearEps(a + rng.uniform(-0.1, 0.1, T), b + rng.uniform(-0.2, 0.2, T))
+    sched = Schedule(T, 0, 1e-4, 0.02, round_fp32=False, sampler=1, eta=0.7)
+    x, rate, rounds = _run_chains(base, drafter, sched, n, K=4, s=1.0, seed=91)
+    assert 0.2 < rate < 0.98
+    m, v = _closed_form_chain_ddim(T, 0, a, b, 1.0, 0.7)
+    _check_law(x, m, v)
