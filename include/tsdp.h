@@ -60,6 +60,9 @@ typedef struct {
   float   clip_val;
   int32_t B_max, K_max;   /* largest batch and largest per-environment draft count */
   uint64_t seed;          /* Philox4x32-10 key */
+  int32_t sampler;        /* 0 = DDPM posterior step, 1 = DDIM(eta) step (the paper names "DDPM or DDIM scheduler") */
+  float   eta;            /* DDIM only, in (0,1]: sigma_t = eta sqrt((1-abar_{t-1})/(1-abar_t)) sqrt(1-abar_t/abar_{t-1});
+                             eta = 0 has no Gaussian transition to test against and is rejected */
 } tsdp_config;
 
 /* Builds the DDPM tables (fp64 on the host, stored fp32) and an empty context.  Synchronous. */

@@ -24,7 +24,7 @@ class TsdpConfig(C.Structure):
                 ("draft_layers", C.c_int32), ("draft_d", C.c_int32), ("draft_heads", C.c_int32), ("draft_mlp_ratio", C.c_int32),
                 ("T", C.c_int32), ("schedule", C.c_int32), ("beta0", C.c_float), ("beta1", C.c_float),
                 ("clip_x0", C.c_int32), ("clip_val", C.c_float), ("B_max", C.c_int32), ("K_max", C.c_int32),
-                ("seed", C.c_uint64)]
+                ("seed", C.c_uint64), ("sampler", C.c_int32), ("eta", C.c_float)]
 
 
 _lib = None
@@ -87,14 +87,15 @@ class Tsdp:
     """One library context.  Methods carry the names of the C entry points."""
 
     def __init__(self, *, dtype, H, A, cond_mode, cond_dim, cond_tokens, base, draft, T, schedule,
-                 beta0=1e-4, beta1=0.02, clip=None, B_max, K_max, seed):
+                 beta0=1e-4, beta1=0.02, clip=None, B_max, K_max, seed, sampler=0, eta=1.0):
         """base / draft: (layers, d, heads, mlp_ratio)."""
         self.lib = load_library()
         self.cfg = TsdpConfig(dtype=dtype, H=H, A=A, cond_mode=cond_mode, cond_dim=cond_dim, cond_tokens=cond_tokens,
                               base_layers=base[0], base_d=base[1], base_heads=base[2], base_mlp_ratio=base[3],
                               draft_layers=draft[0], draft_d=draft[1], draft_heads=draft[2], draft_mlp_ratio=draft[3],
                               T=T, schedule=schedule, beta0=beta0, beta1=beta1, clip_x0=0 if clip is None else 1,
-                              clip_val=0.0 if clip is None else float(clip), B_max=B_max, K_max=K_max, seed=seed)
+                              clip_val=0.0 if clip is None else float(clip), B_max=B_max, K_max=K_max, seed=seed,
+                              sampler=sampler, eta=eta)
         self.ctx = C.c_void_p()
         rc = self.lib.tsdp_create(C.byref(self.cfg), C.byref(self.ctx))
         if rc != 0:
@@ -103,13 +104,13 @@ class Tsdp:
         self.H, self.A, self.D, self.K_max, self.B_max = H, A, H * A, K_max, B_max
 
     @classmethod
-    def from_workload(cls, wl, *, B_max=None, K_max=None, clip=None, seed=None):
+    def from_workload(cls, wl, *, B_max=None, K_max=None, clip=None, seed=None, sampler=0, eta=1.0):
         return cls(dtype=0 if wl.dtype == "fp32" else 1, H=wl.H, A=wl.A, cond_mode=wl.cond_mode, cond_dim=wl.cond_dim,
                    cond_tokens=wl.cond_tokens, base=(wl.base.layers, wl.base.d, wl.base.heads, wl.base.mlp_ratio),
                    draft=(wl.draft.layers, wl.draft.d, wl.draft.heads, wl.draft.mlp_ratio), T=wl.T,
                    schedule=wl.schedule, beta0=wl.beta0 or 1e-4, beta1=wl.beta1 or 0.02, clip=clip,
                    B_max=wl.B if B_max is None else B_max, K_max=wl.K_max if K_max is None else K_max,
-                   seed=wl.philox_seed if seed is None else seed)
+                   seed=wl.philox_seed if seed is None else seed, sampler=sampler, eta=eta)
 
     def close(self):
         if self.ctx:

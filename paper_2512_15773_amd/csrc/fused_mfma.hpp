@@ -63,7 +63,7 @@ struct FusedIO {               // batched verification
   float* eps_out;              // [R,H,A]
 };
 
-struct SchedDev { const float* sqrt_abar; const float* sqrt_1m; const float* c0; const float* cx; const float* sigma; int T; };
+struct SchedDev { const float* sqrt_abar; const float* sqrt_1m; const float* c0; const float* cx; const float* sigma; const float* ce; int T; };
 
 struct DraftIO {               // drafter rollout
   int B;
@@ -834,14 +834,14 @@ __global__ __launch_bounds__(C::THREADS) void k_fused_draft(FusedNet net, DraftI
       const f32x4 ev = *reinterpret_cast<const f32x4*>(ep);
       const float4 z4 = xi_block(io.seed, io.env_id ? io.env_id[b] : b, t, blk);
       const f32x4 z = {z4.x, z4.y, z4.z, z4.w};
-      const float sa = io.tb.sqrt_abar[t], s1 = io.tb.sqrt_1m[t], c0 = io.tb.c0[t], cx = io.tb.cx[t];
+      const float sa = io.tb.sqrt_abar[t], s1 = io.tb.sqrt_1m[t], c0 = io.tb.c0[t], cx = io.tb.cx[t], ce = io.tb.ce[t];
       const float sig = io.sigma_scale[b] * io.tb.sigma[t];
       f32x4 o;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         float x0 = (yv[j] - s1 * ev[j]) / sa;
         if (io.clip) x0 = fminf(fmaxf(x0, -io.clip_val), io.clip_val);
-        o[j] = c0 * x0 + cx * yv[j] + sig * z[j];
+        o[j] = c0 * x0 + cx * yv[j] + ce * ev[j] + sig * z[j];
       }
       *reinterpret_cast<f32x4*>(io.states + row * DE + 4 * blk) = yv;
       *reinterpret_cast<f32x4*>(io.eps_p + row * DE + 4 * blk) = ev;

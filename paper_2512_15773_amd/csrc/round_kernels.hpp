@@ -6,8 +6,8 @@
 
 namespace tsdp {
 
-struct SchedTables {          // device pointers, fp32[T] each
-  const float* sqrt_abar; const float* sqrt_1m; const float* c0; const float* cx; const float* sigma;
+struct SchedTables {          // device pointers, fp32[T] each; posterior mean = c0 x0_hat + cx x + ce eps
+  const float* sqrt_abar; const float* sqrt_1m; const float* c0; const float* cx; const float* sigma; const float* ce;
   int T;
 };
 
@@ -90,7 +90,7 @@ __global__ void k_draft_step(int k, const float* __restrict__ eps, const int32_t
   const float4 yv = *reinterpret_cast<const float4*>(y + (long long)b * D + 4 * blk);
   const float4 ev = *reinterpret_cast<const float4*>(eps + (long long)b * D + 4 * blk);
   const float4 z = xi_block(seed, env_id ? env_id[b] : b, t, blk);
-  const float sa = tb.sqrt_abar[t], s1 = tb.sqrt_1m[t], c0 = tb.c0[t], cx = tb.cx[t];
+  const float sa = tb.sqrt_abar[t], s1 = tb.sqrt_1m[t], c0 = tb.c0[t], cx = tb.cx[t], ce = tb.ce[t];
   const float sig = sigma_scale[b] * tb.sigma[t];
   const float yy[4] = {yv.x, yv.y, yv.z, yv.w}, ee[4] = {ev.x, ev.y, ev.z, ev.w}, zz[4] = {z.x, z.y, z.z, z.w};
   float o[4];
@@ -98,7 +98,7 @@ __global__ void k_draft_step(int k, const float* __restrict__ eps, const int32_t
   for (int j = 0; j < 4; ++j) {
     float x0 = (yy[j] - s1 * ee[j]) / sa;
     if (clip) x0 = fminf(fmaxf(x0, -clip_val), clip_val);
-    o[j] = c0 * x0 + cx * yy[j] + sig * zz[j];
+    o[j] = c0 * x0 + cx * yy[j] + ce * ee[j] + sig * zz[j];
   }
   *reinterpret_cast<float4*>(states + row * D + 4 * blk) = yv;
   *reinterpret_cast<float4*>(eps_p + row * D + 4 * blk) = ev;
@@ -151,7 +151,7 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
   const int t0 = row_t[r0];
   const double cv = (double)clip_val;
   if (t0 == 0) {                                    // deterministic last step of the base model
-    const double sa = tb.sqrt_abar[0], s1 = tb.sqrt_1m[0], c0 = tb.c0[0], cx = tb.cx[0];
+    const double sa = tb.sqrt_abar[0], s1 = tb.sqrt_1m[0], c0 = tb.c0[0], cx = tb.cx[0], ce = tb.ce[0];
     const float4* st = reinterpret_cast<const float4*>(states + (long long)r0 * D);
     const float4* eq = reinterpret_cast<const float4*>(eps_q + (long long)r0 * D);
     for (int i = lane; i < nb; i += 64) {
@@ -162,7 +162,7 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
       for (int j = 0; j < 4; ++j) {
         double x0 = ((double)yy[j] - s1 * (double)ee[j]) / sa;
         if (CLIP) x0 = fmin(fmax(x0, -cv), cv);
-        o[j] = (float)(c0 * x0 + cx * (double)yy[j]);
+        o[j] = (float)(c0 * x0 + cx * (double)yy[j] + ce * (double)ee[j]);
       }
       xo[i] = make_float4(o[0], o[1], o[2], o[3]);
     }
@@ -196,10 +196,12 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
       }
     }
     const int t = row_t[rr];
-    const double sa = tb.sqrt_abar[t], s1 = tb.sqrt_1m[t], c0 = tb.c0[t], sig = s * (double)tb.sigma[t];
+    const double sa = tb.sqrt_abar[t], s1 = tb.sqrt_1m[t], c0 = tb.c0[t], ce = tb.ce[t], sig = s * (double)tb.sigma[t];
     // stochastic test: log U;  threshold rule p = min(1, alpha) >= lambda  <=>  log alpha >= log lambda (lambda <= 1)
     const double lu = lambda ? log((double)lambda[b]) : log((double)accept_uniform(seed, env, t));
-    double dd = 0.0, dx = 0.0;                      // sums of delta^2 and delta*xi, delta = x0_p - x0_q
+    // sums of delta^2 and delta*xi; clamped x0: delta = mu_p - mu_q, else delta = eps_p - eps_q (mu_p - mu_q is a
+    // multiple of it)
+    double dd = 0.0, dx = 0.0;
 #pragma unroll
     for (int it = 0; it < MAXI; ++it) {
       if (gl + 16 * it < nb) {
@@ -211,7 +213,7 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
           for (int j = 0; j < 4; ++j) {
             const double xp = fmin(fmax(((double)yy[j] - s1 * (double)pp[j]) / sa, -cv), cv);
             const double xq = fmin(fmax(((double)yy[j] - s1 * (double)qq[j]) / sa, -cv), cv);
-            const double de = xp - xq;
+            const double de = c0 * (xp - xq) + ce * ((double)pp[j] - (double)qq[j]);
             dd = fma(de, de, dd); dx = fma(de, (double)zv[j], dx);
           }
         } else {
@@ -224,7 +226,7 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
       }
     }
     dd = group16_sum(dd); dx = group16_sum(dx);
-    const double kap = CLIP ? c0 / sig : -(c0 * s1) / (sa * sig);   // d = kap * delta
+    const double kap = CLIP ? 1.0 / sig : (ce - (c0 * s1) / sa) / sig;   // d = kap * delta
     const double n2 = kap * kap * dd, ip = kap * dx;                // |d|^2, <d,xi>
     const double l = -0.5 * n2 - ip;
     const bool acc = lu <= l;
@@ -244,7 +246,8 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
           const int q2 = r2 + grp;
           if (q2 < r1) {
             const int t2 = row_t[q2];
-            const double sa2 = tb.sqrt_abar[t2], s12 = tb.sqrt_1m[t2], c02 = tb.c0[t2], sig2 = s * (double)tb.sigma[t2];
+            const double sa2 = tb.sqrt_abar[t2], s12 = tb.sqrt_1m[t2], c02 = tb.c0[t2], ce2 = tb.ce[t2],
+                         sig2 = s * (double)tb.sigma[t2];
             const float4* ep2 = reinterpret_cast<const float4*>(eps_p + (long long)q2 * D);
             const float4* eq2 = reinterpret_cast<const float4*>(eps_q + (long long)q2 * D);
             const float4* zz2 = reinterpret_cast<const float4*>(xi + (long long)q2 * D);
@@ -261,7 +264,7 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
                 if (CLIP) {
                   const double xp = fmin(fmax(((double)yy[j] - s12 * (double)pp[j]) / sa2, -cv), cv);
                   const double xq = fmin(fmax(((double)yy[j] - s12 * (double)qq[j]) / sa2, -cv), cv);
-                  de = xp - xq;
+                  de = c02 * (xp - xq) + ce2 * ((double)pp[j] - (double)qq[j]);
                 } else {
                   de = (double)pp[j] - (double)qq[j];
                 }
@@ -270,7 +273,7 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
             }
             // 16-lane reductions below are executed by whole groups only (q2 depends on grp, not on gl)
             dd2 = group16_sum(dd2); dx2 = group16_sum(dx2);
-            const double kap2 = CLIP ? c02 / sig2 : -(c02 * s12) / (sa2 * sig2);
+            const double kap2 = CLIP ? 1.0 / sig2 : (ce2 - (c02 * s12) / sa2) / sig2;
             const double l2 = -0.5 * kap2 * kap2 * dd2 - kap2 * dx2;
             const double lu2 = lambda ? log((double)lambda[b]) : log((double)accept_uniform(seed, env, t2));
             if (gl == 0) {
@@ -293,7 +296,8 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
   {                                                 // reflect the first rejected draft about the target mean
     const int r = r0 + jstar - 1;
     const int t = row_t[r];
-    const double sa = tb.sqrt_abar[t], s1 = tb.sqrt_1m[t], c0 = tb.c0[t], cx = tb.cx[t], sig = s * (double)tb.sigma[t];
+    const double sa = tb.sqrt_abar[t], s1 = tb.sqrt_1m[t], c0 = tb.c0[t], cx = tb.cx[t], ce = tb.ce[t],
+                 sig = s * (double)tb.sigma[t];
     const double coef = rej_dd > 0.0 ? 2.0 * rej_dx / rej_dd : 0.0;   // 2 <d,xi>/|d|^2
     const float4* ep = reinterpret_cast<const float4*>(eps_p + (long long)r * D);
     const float4* eq = reinterpret_cast<const float4*>(eps_q + (long long)r * D);
@@ -309,8 +313,8 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
         double xp = ((double)yy[j] - s1 * (double)pp[j]) / sa;
         double xq = ((double)yy[j] - s1 * (double)qq[j]) / sa;
         if (CLIP) { xp = fmin(fmax(xp, -cv), cv); xq = fmin(fmax(xq, -cv), cv); }
-        const double muq = c0 * xq + cx * (double)yy[j];
-        const double dmu = c0 * (xp - xq);                          // mu_p - mu_q
+        const double muq = c0 * xq + cx * (double)yy[j] + ce * (double)qq[j];
+        const double dmu = c0 * (xp - xq) + ce * ((double)pp[j] - (double)qq[j]);   // mu_p - mu_q
         o[j] = (float)(muq + sig * (double)zv[j] - coef * dmu);
       }
       xo[i] = make_float4(o[0], o[1], o[2], o[3]);
@@ -355,7 +359,7 @@ __global__ __launch_bounds__(256) void k_distill_partial(int R, int D, const int
   double pred = 0.0, nrm = 0.0;
   if (r < R) {
     const int t = row_t[r];
-    const double sa = tb.sqrt_abar[t], s1 = tb.sqrt_1m[t], c0 = tb.c0[t], sig = tb.sigma[t], cv = clip_val;
+    const double sa = tb.sqrt_abar[t], s1 = tb.sqrt_1m[t], c0 = tb.c0[t], ce = tb.ce[t], sig = tb.sigma[t], cv = clip_val;
     const float4* ep = reinterpret_cast<const float4*>(eps_p + (long long)r * D);
     const float4* eq = reinterpret_cast<const float4*>(eps_q + (long long)r * D);
     const float4* st = reinterpret_cast<const float4*>(states + (long long)r * D);
@@ -372,14 +376,15 @@ __global__ __launch_bounds__(256) void k_distill_partial(int R, int D, const int
         if (CLIP) {
           const double xp = fmin(fmax(((double)yy[j] - s1 * (double)pp[j]) / sa, -cv), cv);
           const double xq = fmin(fmax(((double)yy[j] - s1 * (double)qq[j]) / sa, -cv), cv);
-          dm = fma(xp - xq, xp - xq, dm);
+          const double dmu = c0 * (xp - xq) + ce * de;
+          dm = fma(dmu, dmu, dm);
         }
       }
     }
     dd = group16_sum(dd); dm = group16_sum(dm);
     pred = dd;
     if (t > 0) {
-      const double kap = CLIP ? c0 / sig : (c0 * s1) / (sa * sig);
+      const double kap = CLIP ? 1.0 / sig : (ce - (c0 * s1) / sa) / sig;
       nrm = kap * kap * (CLIP ? dm : dd);
     }
   }

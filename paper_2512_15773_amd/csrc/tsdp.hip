@@ -57,7 +57,7 @@ struct tsdp_ctx {
   tsdp_config cfg;
   int D = 0;
   std::string err;
-  float* tables = nullptr;      // 5 x T fp32: sqrt_abar, sqrt_1m, c0, cx, sigma
+  float* tables = nullptr;      // 6 x T fp32: sqrt_abar, sqrt_1m, c0, cx, sigma, ce
   SchedTables tb;
   Net net[2];
   bool cond_set = false;
@@ -505,6 +505,7 @@ int tsdp_create(const tsdp_config* cfg, tsdp_ctx** out) {
       bad(f.draft_d, f.draft_heads, f.draft_layers, f.draft_mlp_ratio) || f.T < 1 || f.T > 4096 || f.schedule < 0 ||
       f.schedule > 1 || f.B_max < 1 || f.K_max < 1 || f.K_max > 64 || (f.clip_x0 && !(f.clip_val > 0.0f)))
     return TSDP_E_INVAL;
+  if (f.sampler < 0 || f.sampler > 1 || (f.sampler == 1 && !(f.eta > 0.0f && f.eta <= 1.0f))) return TSDP_E_INVAL;
   if (f.schedule == 0 && !(f.beta0 > 0.0f && f.beta1 >= f.beta0 && f.beta1 < 1.0f)) return TSDP_E_INVAL;
   if ((long long)f.B_max * f.K_max > (1ll << 24)) return TSDP_E_SHAPE;
   tsdp_ctx* c = new (std::nothrow) tsdp_ctx();
@@ -526,20 +527,29 @@ int tsdp_create(const tsdp_config* cfg, tsdp_ctx** out) {
     }
     abar[i] = (i ? abar[i - 1] : 1.0) * (1.0 - beta[i]);
   }
-  std::vector<float> tab(5 * (size_t)T);
+  std::vector<float> tab(6 * (size_t)T);
   for (int t = 0; t < T; ++t) {
     const double ap = t ? abar[t - 1] : 1.0;
     tab[0 * T + t] = (float)std::sqrt(abar[t]);
     tab[1 * T + t] = (float)std::sqrt(1.0 - abar[t]);
-    tab[2 * T + t] = (float)(std::sqrt(ap) * beta[t] / (1.0 - abar[t]));
-    tab[3 * T + t] = (float)(std::sqrt(1.0 - beta[t]) * (1.0 - ap) / (1.0 - abar[t]));
-    tab[4 * T + t] = (float)std::sqrt(beta[t] * (1.0 - ap) / (1.0 - abar[t]));
+    if (f.sampler == 0) {                             // DDPM posterior: mu = c0 x0_hat + cx x
+      tab[2 * T + t] = (float)(std::sqrt(ap) * beta[t] / (1.0 - abar[t]));
+      tab[3 * T + t] = (float)(std::sqrt(1.0 - beta[t]) * (1.0 - ap) / (1.0 - abar[t]));
+      tab[4 * T + t] = (float)std::sqrt(beta[t] * (1.0 - ap) / (1.0 - abar[t]));
+      tab[5 * T + t] = 0.0f;
+    } else {                                          // DDIM(eta): mu = sqrt(abar') x0_hat + sqrt(1 - abar' - sigma^2) eps
+      const double sig = (double)f.eta * std::sqrt((1.0 - ap) / (1.0 - abar[t])) * std::sqrt(1.0 - abar[t] / ap);
+      tab[2 * T + t] = (float)std::sqrt(ap);
+      tab[3 * T + t] = 0.0f;
+      tab[4 * T + t] = (float)sig;
+      tab[5 * T + t] = (float)std::sqrt(std::max(1.0 - ap - sig * sig, 0.0));
+    }
   }
   auto cleanup = [&](int code) { tsdp_destroy(c); return code; };
   if (dev_alloc(c, &c->tables, tab.size())) return cleanup(TSDP_E_NOMEM);
   if (hipMemcpy(c->tables, tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess)
     return cleanup(TSDP_E_HIP);
-  c->tb = {c->tables, c->tables + T, c->tables + 2 * T, c->tables + 3 * T, c->tables + 4 * T, T};
+  c->tb = {c->tables, c->tables + T, c->tables + 2 * T, c->tables + 3 * T, c->tables + 4 * T, c->tables + 5 * T, T};
   if (dev_alloc(c, &c->status, 1) || dev_alloc(c, &c->K_eff, (size_t)f.B_max)) return cleanup(TSDP_E_NOMEM);
   if (hipMemset(c->status, 0, sizeof(int32_t)) != hipSuccess) return cleanup(TSDP_E_HIP);
   *out = c;
@@ -690,7 +700,7 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
       DraftIO io;
       io.B = B; io.t0 = d_t0; io.K_eff = c->K_eff; io.row_ptr = d_row_ptr; io.sigma_scale = d_sigma_scale;
       io.env_id = d_env_id;
-      io.tb = {c->tb.sqrt_abar, c->tb.sqrt_1m, c->tb.c0, c->tb.cx, c->tb.sigma, c->tb.T};
+      io.tb = {c->tb.sqrt_abar, c->tb.sqrt_1m, c->tb.c0, c->tb.cx, c->tb.sigma, c->tb.ce, c->tb.T};
       io.clip = cf.clip_x0; io.clip_val = cf.clip_val; io.seed = cf.seed;
       io.y = d_y_last; io.states = d_states; io.eps_p = d_eps_p; io.xi = d_xi;
       tick(c, 0, 0, s);

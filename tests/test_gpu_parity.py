@@ -15,13 +15,13 @@ TOL = {"fp32": 1e-5, "bf16": 2e-2}
 TIE = 1e-5          # accept flags may differ only where |log U - log alpha| is below this (fp32 nets)
 
 
-def _setup(wl, B, clip=None, K_max=None, b_std=0.02, head_scale=1.0, seed=None):
+def _setup(wl, B, clip=None, K_max=None, b_std=0.02, head_scale=1.0, seed=None, sampler=0, eta=1.0):
     wb = ti.make_weights(wl, "base", b_std=b_std, head_scale=head_scale)
     wd = ti.make_weights(wl, "draft", b_std=b_std, head_scale=head_scale)
     cond = ti.make_cond(wl, B)
     x = ti.make_latents(wl, B)
-    base, drafter, sched = oracle_side(wl, wb, wd)
-    ctx = gpu_side(wl, wb, wd, cond, clip=clip, B_max=B, K_max=K_max, seed=seed)
+    base, drafter, sched = oracle_side(wl, wb, wd, sampler=sampler, eta=eta)
+    ctx = gpu_side(wl, wb, wd, cond, clip=clip, B_max=B, K_max=K_max, seed=seed, sampler=sampler, eta=eta)
     return dict(wl=wl, B=B, cond=cond, x=x, base=base, drafter=drafter, sched=sched, ctx=ctx, clip=clip,
                 seed=wl.philox_seed if seed is None else seed)
 
@@ -86,8 +86,8 @@ def _check_accept(S, rows, o, s, env, window):
     return g, ref, env_ok
 
 
-def _stage_parity(wl, B, t0, K, s, env=None, clip=None, b_std=0.02, paths=None):
-    S = _setup(wl, B, clip=clip, b_std=b_std)
+def _stage_parity(wl, B, t0, K, s, env=None, clip=None, b_std=0.02, paths=None, sampler=0, eta=1.0):
+    S = _setup(wl, B, clip=clip, b_std=b_std, sampler=sampler, eta=eta)
     if paths is not None:
         assert (S["ctx"].path_name(0), S["ctx"].path_name(1)) == paths
     tol = TOL[wl.dtype]
@@ -319,3 +319,23 @@ def test_distillation_loss_matches_oracle():
         assert got.tobytes() == again.tobytes()                            # fixed reduction order
         assert got[0] > 0 and got[1] > 0
         S["ctx"].close()
+
+
+def test_ddim_sampler_stages_and_loss():
+    # DDIM(eta) transitions in the draft step, the acceptance ratio, the reflection, the last step and the loss
+    wl = ti.small_variant(ti.C1, B=7)
+    t0 = np.array([9, 6, 3, 1, 0, -1, 9]); K = np.array([4, 4, 4, 2, 4, 4, 1]); s = np.array([1.0, 1.3, 1.0, 1.0, 1.0, 1.0, 1.1])
+    for clip in (None, 1.0):
+        _stage_parity(wl, 7, t0, K, s, clip=clip, sampler=1, eta=0.6)
+    wl = ti.small_variant(ti.C3, B=4)
+    t0, K, s = ti.make_schedule_inputs(wl, 4, t0=45)
+    _stage_parity(wl, 4, t0, K, s, sampler=1, eta=1.0, paths=("bf16-mfma-fused", "bf16-mfma-fused"))
+    S = _setup(ti.small_variant(ti.C2, B=3, base=ti.NetShape(2, 256, 4)), 3, clip=2.0, sampler=1, eta=0.5)
+    rows = _gpu_draft(S, np.array([60, 9, 0]), np.full(3, 8), np.ones(3), None)
+    S["ctx"].tsdp_verify(3, rows)
+    R = int(rows["row_ptr"].cpu().numpy()[-1])
+    got = S["ctx"].tsdp_distill_loss(R, rows, 1.0, 1.0).cpu().numpy()
+    ref = sr.distill_loss(S["sched"], rows["row_t"].cpu().numpy()[:R], rows["states"].cpu().numpy()[:R],
+                          rows["eps_p"].cpu().numpy()[:R], rows["eps_q"].cpu().numpy()[:R], 1.0, 1.0, 2.0)
+    np.testing.assert_allclose(got, ref, rtol=1e-10)
+    S["ctx"].close()
