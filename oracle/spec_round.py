@@ -17,6 +17,14 @@ commit) of the paper.  Readings taken where the text is silent or garbled:
 * Acceptance is the stochastic test U <= min(1, q/p), taken as
   log U <= log alpha with equality accepting.
 * Environments with t0 < 0 are finished: no rows, latent unchanged.
+* Bonus-row variant (the paper's candidate set has K+1 members): the state y_{K_eff} reached by the
+  last draft is verified too, at its own timestep t0 - K_eff >= 0; when every draft is accepted the
+  base model's prediction there gives one more, exact base step, so the round advances K_eff + 1
+  steps.  The lone row of a t0 = 0 environment is the K_eff = 0 case of the same rule.  With the
+  bonus row K = 0 is allowed (a plain base step); without it K >= 1.
+* Stage tables (the scheduler's action holds one draft count / sigma scale / threshold for each of
+  three denoising stages, whose boundaries the paper does not give): stage 0 while t >= t_hi, stage 1
+  while t_lo <= t < t_hi, stage 2 below t_lo; the stage is taken at the start of a round.
 
 Rows are stored environment-major, k ascending: row_ptr[b] + (k - 1).
 """
@@ -25,13 +33,15 @@ import numpy as np
 from . import philox
 
 
-def plan_rows(t0, K):
+def plan_rows(t0, K, bonus=False):
     """K_eff and the ragged row table (row_ptr [B+1], row_env [R], row_t [R])."""
     t0 = np.asarray(t0, dtype=np.int64)
     K = np.asarray(K, dtype=np.int64)
+    if (K < (0 if bonus else 1)).any():
+        raise ValueError("K must be >= 1 (>= 0 with the bonus row)")
     live = t0 >= 0
     K_eff = np.where(live, np.minimum(K, t0), 0)
-    nrows = np.where(live, np.maximum(K_eff, 1), 0)
+    nrows = np.where(live, K_eff + 1 if bonus else np.maximum(K_eff, 1), 0)
     row_ptr = np.concatenate([[0], np.cumsum(nrows)]).astype(np.int64)
     R = int(row_ptr[-1])
     row_env = np.zeros(R, dtype=np.int64)
@@ -43,7 +53,7 @@ def plan_rows(t0, K):
     return K_eff, row_ptr, row_env, row_t
 
 
-def draft(drafter, sched, x, t0, K, sigma_scale, env_id, seed, cond, clip=None):
+def draft(drafter, sched, x, t0, K, sigma_scale, env_id, seed, cond, clip=None, bonus=False):
     """Drafter rollout (Section 3.2, Draft Generation Procedure).
 
     For k = 1..K_eff:  eps_p = Mhat(y_{k-1}; t_k),  mu_p = posterior mean,
@@ -56,7 +66,7 @@ def draft(drafter, sched, x, t0, K, sigma_scale, env_id, seed, cond, clip=None):
     s = np.asarray(sigma_scale, dtype=np.float64)
     t0 = np.asarray(t0, dtype=np.int64)
     env_id = np.arange(B) if env_id is None else np.asarray(env_id, dtype=np.int64)
-    K_eff, row_ptr, row_env, row_t = plan_rows(t0, K)
+    K_eff, row_ptr, row_env, row_t = plan_rows(t0, K, bonus)
     R = int(row_ptr[-1])
     states = np.zeros((R,) + x.shape[1:])
     eps_p = np.zeros_like(states)
@@ -76,6 +86,12 @@ def draft(drafter, sched, x, t0, K, sigma_scale, env_id, seed, cond, clip=None):
         y[act] = mu + sig * z
         eps_p[rows] = e
         xi[rows] = z
+    if bonus:                                        # the state after the last draft and the noise of a base step from it
+        for b in np.nonzero(t0 >= 0)[0]:
+            r, tb = row_ptr[b] + K_eff[b], int(t0[b] - K_eff[b])
+            states[r] = y[b]
+            if tb > 0:
+                xi[r] = philox.normal(seed, env_id[b:b + 1], np.array([tb]), D).reshape(x.shape[1:])
     return dict(K_eff=K_eff, row_ptr=row_ptr, row_env=row_env, row_t=row_t,
                 states=states, eps_p=eps_p, xi=xi, y_last=y)
 
@@ -120,7 +136,8 @@ def reflect(mu_p, mu_q, sig, xi):
     return (mu_q.ravel() + v - 2.0 * e * float(e @ v)).reshape(mu_q.shape)
 
 
-def accept(sched, row_ptr, row_t, sigma_scale, env_id, seed, states, eps_p, eps_q, xi, y_last, clip=None, lam=None):
+def accept(sched, row_ptr, row_t, sigma_scale, env_id, seed, states, eps_p, eps_q, xi, y_last, clip=None, lam=None,
+           bonus=False):
     """Acceptance test, first-rejection scan and commit / reflection for every environment.
 
     lam = None: the lossless stochastic test U <= min(1, alpha) (Section 3.1).  lam = per-environment
@@ -149,7 +166,10 @@ def accept(sched, row_ptr, row_t, sigma_scale, env_id, seed, states, eps_p, eps_
     mu_q = sched.posterior_mean(states, eps_q, row_t, clip) if R else states
     mu_p = sched.posterior_mean(states, eps_p, row_t, clip) if R else states
     sig = s[row_env] * sched.sigma[row_t] if R else np.zeros(0)
-    dr = np.nonzero(row_t > 0)[0]                    # drafted rows (t = 0 rows are lone base steps)
+    drafted = row_t > 0                              # t = 0 rows are base steps ...
+    if bonus and R:
+        drafted[row_ptr[1:][np.diff(row_ptr) > 0] - 1] = False      # ... and so is the last row of every environment
+    dr = np.nonzero(drafted)[0]
     if len(dr):
         l, _, _ = log_ratio(mu_p[dr], mu_q[dr], sig[dr], xi[dr])
         logratio[dr] = l
@@ -172,33 +192,71 @@ def accept(sched, row_ptr, row_t, sigma_scale, env_id, seed, states, eps_p, eps_
         if r1 == r0:                                 # finished environment: untouched
             continue
         t0 = int(row_t[r0])
-        if t0 == 0:                                  # deterministic last step by the base model
-            x_out[b] = mu_q[r0]
-            n_adv[b] = 1
+        base_row = bonus or t0 == 0                  # the last row is a step of the base model itself
+        K_eff = r1 - r0 - 1 if base_row else r1 - r0
+        j = first_rejection(flags[r0:r0 + K_eff])
+        n_accept[b] = j - 1
+        if j <= K_eff:
+            r = r0 + j - 1
+            x_out[b] = reflect(mu_p[r], mu_q[r], sig[r], xi[r])
+            n_adv[b] = j
+        elif base_row:                               # exact base transition from y_{K_eff} (no noise at t = 0)
+            r = r1 - 1
+            x_out[b] = mu_q[r] + sig[r] * xi[r]
+            n_adv[b] = K_eff + 1
         else:
-            K_eff = r1 - r0
-            j = first_rejection(flags[r0:r1])
-            n_accept[b] = j - 1
-            if j <= K_eff:
-                r = r0 + j - 1
-                x_out[b] = reflect(mu_p[r], mu_q[r], sig[r], xi[r])
-                n_adv[b] = j
-            else:
-                n_adv[b] = K_eff                     # x_out = y_{K_eff}
+            n_adv[b] = K_eff                         # x_out = y_{K_eff}
         t_next[b] = t0 - n_adv[b]
     return dict(x_out=x_out, t_next=t_next, n_accept=n_accept, n_adv=n_adv,
                 flags=flags, logratio=logratio, logu=logu)
 
 
-def spec_round(base, drafter, sched, x, t0, K, sigma_scale, env_id, seed, cond, clip=None, lam=None):
+def spec_round(base, drafter, sched, x, t0, K, sigma_scale, env_id, seed, cond, clip=None, lam=None, bonus=False):
     """draft -> verify -> accept for a batch of environments; returns the accept dict plus the draft dict."""
-    dr = draft(drafter, sched, x, t0, K, sigma_scale, env_id, seed, cond, clip)
+    dr = draft(drafter, sched, x, t0, K, sigma_scale, env_id, seed, cond, clip, bonus)
     eps_q = verify(base, dr["row_env"], dr["row_t"], dr["states"], cond)
     ac = accept(sched, dr["row_ptr"], dr["row_t"], sigma_scale, env_id, seed,
-                dr["states"], dr["eps_p"], eps_q, dr["xi"], dr["y_last"], clip, lam)
+                dr["states"], dr["eps_p"], eps_q, dr["xi"], dr["y_last"], clip, lam, bonus)
     ac["draft"] = dr
     ac["eps_q"] = eps_q
     return ac
+
+
+def stage_select(t, t_hi, t_lo, table):
+    """Per-environment entry of a [B, 3] stage table: column 0 while t >= t_hi, 1 while t_lo <= t < t_hi, else 2."""
+    t = np.asarray(t, dtype=np.int64)
+    table = np.asarray(table)
+    stage = np.where(t >= t_hi, 0, np.where(t >= t_lo, 1, 2))
+    return table[np.arange(len(t)), stage]
+
+
+def chain(base, drafter, sched, x, t0, K, sigma_scale, env_id, seed, cond, clip=None, lam=None, bonus=False,
+          stages=None, max_rounds=10 ** 6):
+    """Rounds repeated until every environment has finished (the paper's inference loop).
+
+    stages = (t_hi, t_lo) makes K, sigma_scale (and lam, if given) [B, 3] stage tables read at the
+    start of every round.  Returns the final latents and timesteps, per-environment totals (accepted
+    drafts, drafted transitions, rounds run), the number of rounds and every round's result.
+    """
+    x = np.asarray(x, dtype=np.float64).copy()
+    t = np.asarray(t0, dtype=np.int64).copy()
+    B = len(t)
+    tot = {k: np.zeros(B, dtype=np.int64) for k in ("accept", "drafts", "rounds")}
+    history = []
+    while (t >= 0).any() and len(history) < max_rounds:
+        if stages is None:
+            K_r, s_r, lam_r = K, sigma_scale, lam
+        else:
+            K_r = stage_select(t, stages[0], stages[1], K)
+            s_r = stage_select(t, stages[0], stages[1], sigma_scale)
+            lam_r = None if lam is None else stage_select(t, stages[0], stages[1], lam)
+        r = spec_round(base, drafter, sched, x, t, K_r, s_r, env_id, seed, cond, clip, lam_r, bonus)
+        tot["accept"] += r["n_accept"]
+        tot["drafts"] += r["draft"]["K_eff"]
+        tot["rounds"] += t >= 0
+        x, t = r["x_out"], r["t_next"]
+        history.append(r)
+    return dict(x=x, t=t, totals=tot, rounds=len(history), history=history)
 
 
 def base_chain_step(base, sched, x, t, sigma_scale, env_id, seed, cond, clip=None):

@@ -189,3 +189,93 @@ def test_ddim_chain_with_imperfect_drafter_keeps_the_base_law():
     assert 0.2 < rate < 0.98
     m, v = _closed_form_chain_ddim(T, 0, a, b, 1.0, 0.7)
     _check_law(x, m, v)
+
+
+def test_bonus_row_identity_drafter_advances_one_extra_exact_base_step():
+    # K+1 candidate set: with drafter == base every draft passes and the round must equal K_eff + 1 plain base steps
+    wl, base = _tiny_nets()
+    sched = Schedule(wl.T, wl.schedule, wl.beta0, wl.beta1)
+    B = 6
+    x = ti.make_latents(wl, B); cond = ti.make_cond(wl, B)
+    t0 = np.array([9, 4, 2, 0, -1, 6]); K = np.array([4, 4, 4, 4, 4, 0]); s = np.array([1.0, 1.2, 1.0, 1.0, 1.0, 1.1])
+    env = np.arange(B) + 20
+    r = sr.spec_round(base, base, sched, x, t0, K, s, env, 0, cond, bonus=True)
+    d = r["draft"]
+    np.testing.assert_array_equal(d["K_eff"], [4, 4, 2, 0, 0, 0])
+    np.testing.assert_array_equal(np.diff(d["row_ptr"]), [5, 5, 3, 1, 0, 1])
+    np.testing.assert_array_equal(r["n_accept"], [4, 4, 2, 0, 0, 0])
+    np.testing.assert_array_equal(r["n_adv"], [5, 5, 3, 1, 0, 1])
+    np.testing.assert_array_equal(r["t_next"], [4, -1, -1, -1, -1, 5])
+    for b in range(B):                                                     # row timesteps run down to t0 - K_eff
+        rows = slice(d["row_ptr"][b], d["row_ptr"][b + 1])
+        np.testing.assert_array_equal(d["row_t"][rows], t0[b] - np.arange(rows.stop - rows.start))
+    ref = np.asarray(x, float).copy()
+    for b in range(B):
+        xb, tb = ref[b:b + 1], t0[b]
+        for _ in range(r["n_adv"][b]):
+            xb = sr.base_chain_step(base, sched, xb, np.array([tb]), s[b:b + 1], env[b:b + 1], 0, cond[b:b + 1])
+            tb -= 1
+        ref[b] = xb[0]
+    np.testing.assert_allclose(r["x_out"], ref, rtol=1e-10, atol=1e-12)
+    # without the bonus row K = 0 is refused
+    try:
+        sr.plan_rows(np.array([5]), np.array([0]))
+        raise AssertionError("K = 0 accepted without the bonus row")
+    except ValueError:
+        pass
+
+
+def test_bonus_row_chain_keeps_the_base_law_and_needs_fewer_rounds():
+    T, n = 10, 100_000
+    rng = np.random.default_rng(15)
+    a = rng.uniform(0.2, 0.8, T); b = rng.uniform(-0.5, 0.5, T)
+    base = LinearEps(a, b)
+    drafter = LinearEps(a + rng.uniform(-0.25, 0.25, T), b + rng.uniform(-0.6, 0.6, T))
+    sched = Schedule(T, 0, 1e-4, 0.02, round_fp32=False)
+    x0 = np.random.default_rng(79).standard_normal((n, 1, 2))
+    cond = np.zeros((n, 1))
+    t0 = np.full(n, T - 1)
+    plain = sr.chain(base, drafter, sched, x0, t0, np.full(n, 3), np.ones(n), None, 79, cond)
+    bonus = sr.chain(base, drafter, sched, x0, t0, np.full(n, 3), np.ones(n), None, 79, cond, bonus=True)
+    m, v = _closed_form_chain(T, 0, a, b, 1.0)
+    _check_law(bonus["x"].reshape(n, 2), m, v)
+    _check_law(plain["x"].reshape(n, 2), m, v)
+    assert (bonus["t"] == -1).all() and (plain["t"] == -1).all()
+    assert bonus["totals"]["rounds"].mean() < plain["totals"]["rounds"].mean()
+    # steps advanced add up to the chain length: accepted + one corrected or base step per round ran, at most
+    assert ((bonus["totals"]["accept"] + bonus["totals"]["rounds"]) >= T).all()
+
+
+def test_stage_tables_select_by_timestep_and_reduce_to_the_plain_chain():
+    # selection: brute force over every timestep
+    tab = np.array([[1, 5, 2], [3, 4, 6]])
+    for t in range(-1, 12):
+        got = sr.stage_select(np.array([t, t]), 8, 3, tab)
+        want = tab[:, 0] if t >= 8 else (tab[:, 1] if t >= 3 else tab[:, 2])
+        np.testing.assert_array_equal(got, want)
+    wl, base = _tiny_nets()
+    sched = Schedule(wl.T, wl.schedule, wl.beta0, wl.beta1)
+    B = 4
+    x = ti.make_latents(wl, B); cond = ti.make_cond(wl, B)
+    t0 = np.array([9, 9, 5, 2])
+    # constant tables == the plain chain
+    K = np.array([3, 2, 4, 1]); s = np.array([1.0, 1.1, 1.0, 1.2])
+    wd = ti.make_weights(wl, "draft", b_std=0.02)
+    drafter = Denoiser(wd, wl.draft.layers, wl.draft.heads, wl.cond_mode)
+    a = sr.chain(base, drafter, sched, x, t0, K, s, None, 4, cond)
+    b = sr.chain(base, drafter, sched, x, t0, np.repeat(K[:, None], 3, 1), np.repeat(s[:, None], 3, 1), None, 4, cond,
+                 stages=(7, 3))
+    np.testing.assert_array_equal(a["x"], b["x"])
+    assert a["rounds"] == b["rounds"]
+    # identity drafter: every draft passes, so the round count follows from the K table alone
+    Kt = np.array([[1, 4, 2]] * B); st = np.ones((B, 3))
+    c = sr.chain(base, base, sched, x, t0, Kt, st, None, 4, cond, stages=(7, 3))
+    want = []
+    for t in t0:
+        n = 0
+        while t >= 0:
+            k = 1 if t >= 7 else (4 if t >= 3 else 2)
+            t -= max(min(k, t), 1); n += 1
+        want.append(n)
+    np.testing.assert_array_equal(c["totals"]["rounds"], want)
+    np.testing.assert_array_equal(c["totals"]["accept"], c["totals"]["drafts"])
