@@ -63,6 +63,10 @@ typedef struct {
   int32_t sampler;        /* 0 = DDPM posterior step, 1 = DDIM(eta) step (the paper names "DDPM or DDIM scheduler") */
   float   eta;            /* DDIM only, in (0,1]: sigma_t = eta sqrt((1-abar_{t-1})/(1-abar_t)) sqrt(1-abar_t/abar_{t-1});
                              eta = 0 has no Gaussian transition to test against and is rejected */
+  int32_t bonus_row;      /* 1 = every running environment gets one more verify row, the state reached by its last
+                             draft (the K+1-member candidate set of Section 3.1): if all drafts pass, the base model's
+                             prediction there gives an exact extra base step, so a round advances up to K_eff + 1 steps.
+                             Row buffers then hold B*(K_max+1) rows and K = 0 (a plain base step) is allowed */
 } tsdp_config;
 
 /* Builds the DDPM tables (fp64 on the host, stored fp32) and an empty context.  Synchronous. */
@@ -86,18 +90,23 @@ int tsdp_load_weights(tsdp_ctx* ctx, int which, const float* h_blob, size_t nbyt
 int tsdp_set_cond(tsdp_ctx* ctx, const float* d_cond, int B, void* stream);
 
 /* Drafter rollout (Section 3.2, Draft Generation Procedure).
- * in : d_x[B,H,A], d_t0[B], d_K[B] (clamped to 0..K_max), d_sigma_scale[B],
+ * in : d_x[B,H,A], d_t0[B], d_K[B] (clamped to 1..K_max, to 0..K_max with bonus_row; status bit 0 reports it),
+ *      d_sigma_scale[B],
  *      d_env_id[B] global environment index used as Philox counter word (NULL = 0..B-1)
  * out: d_row_ptr[B+1], d_row_t[R_cap], d_row_env[R_cap], d_states[R_cap,H,A], d_eps_p[R_cap,H,A],
  *      d_xi[R_cap,H,A], d_y_last[B,H,A] (the latent after the last drafted step; x itself if no step
- *      was drafted).  R_cap = B*K_max rows must be allocated; rows beyond row_ptr[B] are not written. */
+ *      was drafted).  R_cap = B*(K_max + bonus_row) rows must be allocated; rows beyond row_ptr[B] are not
+ *      written.  Rows of environment b: K_eff = min(K, t0) drafted rows at timesteps t0, t0-1, ...; an environment
+ *      at t0 = 0 has the lone row (x, t = 0) of its deterministic base step; with bonus_row every running
+ *      environment ends with the row (y_{K_eff}, t0 - K_eff), whose d_xi is the noise of a base step from it
+ *      (zero at timestep 0) and whose d_eps_p is zero. */
 int tsdp_draft(tsdp_ctx* ctx, int B, const float* d_x, const int32_t* d_t0, const int32_t* d_K,
                const float* d_sigma_scale, const int32_t* d_env_id,
                int32_t* d_row_ptr, int32_t* d_row_t, int32_t* d_row_env,
                float* d_states, float* d_eps_p, float* d_xi, float* d_y_last, void* stream);
 
 /* Batched verification (Section 3.2, Verification of Speculative Drafts): base-network noise
- * prediction for every row of a ragged batch.  R_cap bounds the launch (<= B_max*K_max); the live row
+ * prediction for every row of a ragged batch.  R_cap bounds the launch (<= B_max*(K_max + bonus_row)); the live row
  * count is read on the device from d_row_ptr[B].  Row r uses timestep d_row_t[r] and the conditioning
  * of environment d_row_env[r] (index into the batch given to tsdp_set_cond).
  * out: d_eps_q[R_cap,H,A]. */
@@ -108,8 +117,10 @@ int tsdp_verify(tsdp_ctx* ctx, int B, int R_cap, const int32_t* d_row_ptr, const
  * per row d = (mu_p - mu_q)/(s sigma_t), log alpha = -|d|^2/2 - <d,xi>; accepted iff
  * log U_{env,t} <= log alpha; first rejection j*; the output latent is y_{K_eff} if all drafts pass,
  * else the reflection of draft j*; t_next = t0 - (steps advanced).  Arithmetic is fp64 on fp32 data.
+ * A base row (the lone row at t0 = 0; the last row of every environment with bonus_row) is not tested: when no
+ * draft before it was rejected the output is mu_q(state, eps_q) + s sigma_t xi of that row, one more step.
  * out: d_x_out[B,H,A], d_t_next[B], d_n_accept[B]; optional (NULL to skip): d_n_adv[B],
- *      d_flags[R] (1 = accepted draft), d_logratio[R], d_logu[R] (0 on the lone row of a t0 = 0 env). */
+ *      d_flags[R] (1 = accepted draft), d_logratio[R], d_logu[R] (all 0 on base rows). */
 int tsdp_accept(tsdp_ctx* ctx, int B, const int32_t* d_row_ptr, const int32_t* d_row_t,
                 const int32_t* d_env_id, const float* d_sigma_scale, const float* d_states,
                 const float* d_eps_p, const float* d_eps_q, const float* d_xi, const float* d_y_last,
@@ -146,6 +157,15 @@ int tsdp_round_threshold(tsdp_ctx* ctx, int B, float* d_x, int32_t* d_t, const i
 int tsdp_chain(tsdp_ctx* ctx, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
                const int32_t* d_env_id, const float* d_lambda, int max_rounds, int check_every,
                int32_t* d_tot_accept, int32_t* d_tot_drafts, int32_t* d_tot_rounds, int32_t* h_rounds, void* stream);
+
+/* The same loop with the scheduler's three-stage action (Section 3.3: sigma scale, acceptance threshold and draft
+ * count "for the three distinct denoising stages"): d_K3, d_sigma_scale3 and d_lambda3 (NULL = stochastic test) are
+ * [B,3] tables; before every round each environment takes column 0 while t >= t_hi, column 1 while t_lo <= t < t_hi,
+ * column 2 below t_lo (the paper does not give the stage boundaries: they are arguments, t_hi >= t_lo >= 0). */
+int tsdp_chain_staged(tsdp_ctx* ctx, int B, float* d_x, int32_t* d_t, const int32_t* d_K3, const float* d_sigma_scale3,
+                      const float* d_lambda3, int t_hi, int t_lo, const int32_t* d_env_id, int max_rounds,
+                      int check_every, int32_t* d_tot_accept, int32_t* d_tot_drafts, int32_t* d_tot_rounds,
+                      int32_t* h_rounds, void* stream);
 
 /* Forward value of the drafter's distillation objective (Section 3.2, Draft Model Training) over R rows:
  * L_pred = mean_r |eps_p[r] - eps_q[r]|^2, L_norm = mean over rows with t > 0 of |(mu_p - mu_q)/sigma_t|^2 (DDPM

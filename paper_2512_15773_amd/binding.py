@@ -13,7 +13,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtsdp.so")
 
 EXPORTS = ["tsdp_create", "tsdp_destroy", "tsdp_load_weights", "tsdp_set_cond", "tsdp_draft", "tsdp_verify",
-           "tsdp_accept", "tsdp_round", "tsdp_accept_threshold", "tsdp_round_threshold", "tsdp_chain", "tsdp_distill_loss", "tsdp_status", "tsdp_kernel_timing", "tsdp_kernel_ms", "tsdp_path_name",
+           "tsdp_accept", "tsdp_round", "tsdp_accept_threshold", "tsdp_round_threshold", "tsdp_chain", "tsdp_chain_staged",
+           "tsdp_distill_loss", "tsdp_status", "tsdp_kernel_timing", "tsdp_kernel_ms", "tsdp_path_name",
            "tsdp_last_error"]
 
 
@@ -24,7 +25,8 @@ class TsdpConfig(C.Structure):
                 ("draft_layers", C.c_int32), ("draft_d", C.c_int32), ("draft_heads", C.c_int32), ("draft_mlp_ratio", C.c_int32),
                 ("T", C.c_int32), ("schedule", C.c_int32), ("beta0", C.c_float), ("beta1", C.c_float),
                 ("clip_x0", C.c_int32), ("clip_val", C.c_float), ("B_max", C.c_int32), ("K_max", C.c_int32),
-                ("seed", C.c_uint64), ("sampler", C.c_int32), ("eta", C.c_float)]
+                ("seed", C.c_uint64), ("sampler", C.c_int32), ("eta", C.c_float),
+                ("bonus_row", C.c_int32)]
 
 
 _lib = None
@@ -50,6 +52,7 @@ def load_library():
     lib.tsdp_accept_threshold.argtypes = [vp, i32] + [vp] * 15 + [vp]
     lib.tsdp_round_threshold.argtypes = [vp, i32] + [vp] * 8 + [vp]
     lib.tsdp_chain.argtypes = [vp, i32] + [vp] * 6 + [i32, i32] + [vp] * 3 + [C.POINTER(C.c_int32), vp]
+    lib.tsdp_chain_staged.argtypes = [vp, i32] + [vp] * 5 + [i32, i32, vp, i32, i32] + [vp] * 3 + [C.POINTER(C.c_int32), vp]
     lib.tsdp_distill_loss.argtypes = [vp, i32, vp, vp, vp, vp, C.c_float, C.c_float, vp, vp]
     lib.tsdp_status.argtypes = [vp, vp, C.POINTER(C.c_int32)]
     lib.tsdp_kernel_timing.argtypes = [vp, i32]
@@ -87,7 +90,7 @@ class Tsdp:
     """One library context.  Methods carry the names of the C entry points."""
 
     def __init__(self, *, dtype, H, A, cond_mode, cond_dim, cond_tokens, base, draft, T, schedule,
-                 beta0=1e-4, beta1=0.02, clip=None, B_max, K_max, seed, sampler=0, eta=1.0):
+                 beta0=1e-4, beta1=0.02, clip=None, B_max, K_max, seed, sampler=0, eta=1.0, bonus_row=False):
         """base / draft: (layers, d, heads, mlp_ratio)."""
         self.lib = load_library()
         self.cfg = TsdpConfig(dtype=dtype, H=H, A=A, cond_mode=cond_mode, cond_dim=cond_dim, cond_tokens=cond_tokens,
@@ -95,22 +98,24 @@ class Tsdp:
                               draft_layers=draft[0], draft_d=draft[1], draft_heads=draft[2], draft_mlp_ratio=draft[3],
                               T=T, schedule=schedule, beta0=beta0, beta1=beta1, clip_x0=0 if clip is None else 1,
                               clip_val=0.0 if clip is None else float(clip), B_max=B_max, K_max=K_max, seed=seed,
-                              sampler=sampler, eta=eta)
+                              sampler=sampler, eta=eta, bonus_row=1 if bonus_row else 0)
         self.ctx = C.c_void_p()
         rc = self.lib.tsdp_create(C.byref(self.cfg), C.byref(self.ctx))
         if rc != 0:
             self.ctx = C.c_void_p()
             raise TsdpError(rc, "tsdp_create rejected the configuration")
         self.H, self.A, self.D, self.K_max, self.B_max = H, A, H * A, K_max, B_max
+        self.rows_per_env = K_max + (1 if bonus_row else 0)
 
     @classmethod
-    def from_workload(cls, wl, *, B_max=None, K_max=None, clip=None, seed=None, sampler=0, eta=1.0):
+    def from_workload(cls, wl, *, B_max=None, K_max=None, clip=None, seed=None, sampler=0, eta=1.0, bonus_row=False):
         return cls(dtype=0 if wl.dtype == "fp32" else 1, H=wl.H, A=wl.A, cond_mode=wl.cond_mode, cond_dim=wl.cond_dim,
                    cond_tokens=wl.cond_tokens, base=(wl.base.layers, wl.base.d, wl.base.heads, wl.base.mlp_ratio),
                    draft=(wl.draft.layers, wl.draft.d, wl.draft.heads, wl.draft.mlp_ratio), T=wl.T,
                    schedule=wl.schedule, beta0=wl.beta0 or 1e-4, beta1=wl.beta1 or 0.02, clip=clip,
                    B_max=wl.B if B_max is None else B_max, K_max=wl.K_max if K_max is None else K_max,
-                   seed=wl.philox_seed if seed is None else seed, sampler=sampler, eta=eta)
+                   seed=wl.philox_seed if seed is None else seed, sampler=sampler, eta=eta,
+                   bonus_row=bonus_row)
 
     def close(self):
         if self.ctx:
@@ -138,8 +143,8 @@ class Tsdp:
         self._chk(self.lib.tsdp_set_cond(self.ctx, _ptr(cond, torch.float32), cond.shape[0], _stream(stream)))
 
     def alloc_rows(self, B, device="cuda"):
-        """Caller-side ragged buffers for tsdp_draft / tsdp_verify / tsdp_accept (R_cap = B*K_max rows)."""
-        R, D = B * self.K_max, self.D
+        """Caller-side ragged buffers for tsdp_draft / tsdp_verify / tsdp_accept (R_cap = B*(K_max + bonus_row) rows)."""
+        R, D = B * self.rows_per_env, self.D
         f = lambda *s: torch.zeros(*s, dtype=torch.float32, device=device)
         i = lambda *s: torch.zeros(*s, dtype=torch.int32, device=device)
         return dict(row_ptr=i(B + 1), row_t=i(R), row_env=i(R), states=f(R, self.H, self.A), eps_p=f(R, self.H, self.A),
@@ -216,6 +221,22 @@ class Tsdp:
                                       max_rounds, check_every, _ptr(tot["accept"]) if tot else None,
                                       _ptr(tot["drafts"]) if tot else None, _ptr(tot["rounds"]) if tot else None,
                                       C.byref(n), _stream(stream)))
+        return n.value, tot
+
+    def tsdp_chain_staged(self, x, t, K3, sigma_scale3, lam3, t_hi, t_lo, env_id, max_rounds=1000, check_every=4,
+                          totals=True, stream=None):
+        """tsdp_chain with [B,3] stage tables; returns (rounds, totals dict or None)."""
+        B = x.shape[0]
+        tot = None
+        if totals:
+            tot = {k: torch.zeros(B, dtype=torch.int32, device=x.device) for k in ("accept", "drafts", "rounds")}
+        n = C.c_int32(0)
+        self._chk(self.lib.tsdp_chain_staged(self.ctx, B, _ptr(x, torch.float32), _ptr(t, torch.int32),
+                                             _ptr(K3, torch.int32), _ptr(sigma_scale3, torch.float32),
+                                             _ptr(lam3, torch.float32), t_hi, t_lo, _ptr(env_id, torch.int32),
+                                             max_rounds, check_every, _ptr(tot["accept"]) if tot else None,
+                                             _ptr(tot["drafts"]) if tot else None, _ptr(tot["rounds"]) if tot else None,
+                                             C.byref(n), _stream(stream)))
         return n.value, tot
 
     def tsdp_distill_loss(self, R, rows, lambda1, lambda2, stream=None):

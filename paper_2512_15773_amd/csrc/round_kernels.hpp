@@ -11,10 +11,11 @@ struct SchedTables {          // device pointers, fp32[T] each; posterior mean =
   int T;
 };
 
-// K_eff = min(clamp(K), t0), rows per env = live ? max(K_eff,1) : 0, exclusive scan into row_ptr[B+1].
+// K_eff = min(clamp(K), t0), rows per env = live ? (bonus ? K_eff + 1 : max(K_eff,1)) : 0, exclusive scan into
+// row_ptr[B+1].  K is clamped to 1..K_max (0..K_max with the bonus row, where K = 0 is a plain base step).
 // Single workgroup of 1024 threads, chunks of 1024 environments.
 __global__ __launch_bounds__(1024) void k_plan(const int32_t* __restrict__ t0, const int32_t* __restrict__ K,
-                                               int B, int K_max, int T, int32_t* __restrict__ K_eff,
+                                               int B, int K_max, int T, int bonus, int32_t* __restrict__ K_eff,
                                                int32_t* __restrict__ row_ptr, int32_t* __restrict__ status) {
   __shared__ int32_t part[1024];
   __shared__ int32_t carry;
@@ -25,11 +26,12 @@ __global__ __launch_bounds__(1024) void k_plan(const int32_t* __restrict__ t0, c
     int n = 0;
     if (b < B) {
       int k = K[b], t = t0[b];
-      if (k < 0 || k > K_max) { atomicOr(status, 1); k = k < 0 ? 0 : K_max; }
+      const int k_min = bonus ? 0 : 1;
+      if (k < k_min || k > K_max) { atomicOr(status, 1); k = k < k_min ? k_min : K_max; }
       if (t >= T) { atomicOr(status, 2); t = T - 1; }
       const int ke = t < 0 ? 0 : (k < t ? k : t);
       K_eff[b] = ke;
-      n = t < 0 ? 0 : (ke > 1 ? ke : 1);
+      n = t < 0 ? 0 : (bonus ? ke + 1 : (ke > 1 ? ke : 1));
     }
     part[threadIdx.x] = n;
     __syncthreads();
@@ -106,6 +108,42 @@ __global__ void k_draft_step(int k, const float* __restrict__ eps, const int32_t
   *reinterpret_cast<float4*>(y + (long long)b * D + 4 * blk) = make_float4(o[0], o[1], o[2], o[3]);
 }
 
+// Bonus row of every running environment: the state reached by the last draft, at timestep t0 - K_eff, with the
+// noise a base step from it would use (none at timestep 0); there is no drafter prediction for it.
+__global__ void k_bonus_rows(const int32_t* __restrict__ t0, const int32_t* __restrict__ K_eff,
+                             const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ env_id, int T, int D,
+                             uint64_t seed, const float* __restrict__ y, float* __restrict__ states,
+                             float* __restrict__ eps_p, float* __restrict__ xi) {
+  const int b = blockIdx.x;
+  const int r0 = row_ptr[b];
+  if (row_ptr[b + 1] == r0) return;
+  int t = t0[b];
+  if (t >= T) t = T - 1;
+  const int ke = K_eff[b];
+  t -= ke;
+  const long long row = r0 + ke;
+  const int env = env_id ? env_id[b] : b;
+  for (int blk = threadIdx.x; blk < (D >> 2); blk += blockDim.x) {
+    const float4 z = t > 0 ? xi_block(seed, env, t, blk) : make_float4(0.f, 0.f, 0.f, 0.f);
+    *reinterpret_cast<float4*>(states + row * D + 4 * blk) = *reinterpret_cast<const float4*>(y + (long long)b * D + 4 * blk);
+    *reinterpret_cast<float4*>(eps_p + row * D + 4 * blk) = make_float4(0.f, 0.f, 0.f, 0.f);
+    *reinterpret_cast<float4*>(xi + row * D + 4 * blk) = z;
+  }
+}
+
+// Stage tables of the chain driver: column 0 while t >= t_hi, 1 while t_lo <= t < t_hi, else 2.
+__global__ void k_stage_select(int B, const int32_t* __restrict__ t, int t_hi, int t_lo, const int32_t* __restrict__ K3,
+                               const float* __restrict__ s3, const float* __restrict__ l3, int32_t* __restrict__ K,
+                               float* __restrict__ s, float* __restrict__ l) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const int tt = t[b];
+  const int st = tt >= t_hi ? 0 : (tt >= t_lo ? 1 : 2);
+  K[b] = K3[3 * b + st];
+  s[b] = s3[3 * b + st];
+  if (l3) l[b] = l3[3 * b + st];
+}
+
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
@@ -131,6 +169,7 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
                                                 const float* __restrict__ xi, const float* __restrict__ y_last,
                                                 SchedTables tb, float clip_val, uint64_t seed,
                                                 const float* __restrict__ lambda,   // per-env threshold rule, or null
+                                                int bonus,                          // last row of an env is a base step
                                                 float* __restrict__ x_out, int32_t* __restrict__ t_next,
                                                 int32_t* __restrict__ n_accept, int32_t* __restrict__ n_adv,
                                                 uint8_t* __restrict__ flags, float* __restrict__ logratio,
@@ -150,38 +189,22 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
   }
   const int t0 = row_t[r0];
   const double cv = (double)clip_val;
-  if (t0 == 0) {                                    // deterministic last step of the base model
-    const double sa = tb.sqrt_abar[0], s1 = tb.sqrt_1m[0], c0 = tb.c0[0], cx = tb.cx[0], ce = tb.ce[0];
-    const float4* st = reinterpret_cast<const float4*>(states + (long long)r0 * D);
-    const float4* eq = reinterpret_cast<const float4*>(eps_q + (long long)r0 * D);
-    for (int i = lane; i < nb; i += 64) {
-      const float4 y = st[i], e = eq[i];
-      const float yy[4] = {y.x, y.y, y.z, y.w}, ee[4] = {e.x, e.y, e.z, e.w};
-      float o[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        double x0 = ((double)yy[j] - s1 * (double)ee[j]) / sa;
-        if (CLIP) x0 = fmin(fmax(x0, -cv), cv);
-        o[j] = (float)(c0 * x0 + cx * (double)yy[j] + ce * (double)ee[j]);
-      }
-      xo[i] = make_float4(o[0], o[1], o[2], o[3]);
-    }
-    if (lane == 0) {
-      t_next[b] = -1; n_accept[b] = 0; if (n_adv) n_adv[b] = 1;
-      if (flags) flags[r0] = 0;
-      if (logratio) logratio[r0] = 0.0f;
-      if (logu_out) logu_out[r0] = 0.0f;
-    }
-    return;
+  // the last row is a step of the base model itself: always with the bonus row, else only at t0 = 0
+  const bool base_row = bonus || t0 == 0;
+  const int rd = base_row ? r1 - 1 : r1;            // drafted rows are r0 .. rd-1
+  if (base_row && lane == 0) {
+    if (flags) flags[rd] = 0;
+    if (logratio) logratio[rd] = 0.0f;
+    if (logu_out) logu_out[rd] = 0.0f;
   }
   const double s = (double)sigma_scale[b];
   const int env = env_id ? env_id[b] : b;
   int jstar = 0;                                    // 0 = no rejection yet; else 1-based row index
   double rej_dd = 0.0, rej_dx = 0.0;
-  for (int rb = r0; rb < r1 && jstar == 0; rb += 4) {
+  for (int rb = r0; rb < rd && jstar == 0; rb += 4) {
     const int r = rb + grp;
-    const bool live = r < r1;
-    const int rr = live ? r : r1 - 1;               // idle groups re-read the last row (in bounds), result unused
+    const bool live = r < rd;
+    const int rr = live ? r : rd - 1;               // idle groups re-read the last row (in bounds), result unused
     const float4* ep = reinterpret_cast<const float4*>(eps_p + (long long)rr * D);
     const float4* eq = reinterpret_cast<const float4*>(eps_q + (long long)rr * D);
     const float4* zz = reinterpret_cast<const float4*>(xi + (long long)rr * D);
@@ -242,9 +265,9 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
       jstar = rb + g - r0 + 1;
       rej_dd = __shfl(n2, g * 16); rej_dx = __shfl(ip, g * 16);
       if (flags || logratio || logu_out) {          // diagnostics cover every row: finish the remaining passes
-        for (int r2 = rb + 4; r2 < r1; r2 += 4) {
+        for (int r2 = rb + 4; r2 < rd; r2 += 4) {
           const int q2 = r2 + grp;
-          if (q2 < r1) {
+          if (q2 < rd) {
             const int t2 = row_t[q2];
             const double sa2 = tb.sqrt_abar[t2], s12 = tb.sqrt_1m[t2], c02 = tb.c0[t2], ce2 = tb.ce[t2],
                          sig2 = s * (double)tb.sigma[t2];
@@ -286,7 +309,30 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
       }
     }
   }
-  const int K_eff = r1 - r0;
+  const int K_eff = rd - r0;
+  if (jstar == 0 && base_row) {                     // exact base transition from y_{K_eff} (no noise at timestep 0)
+    const int t = t0 - K_eff;
+    const double sa = tb.sqrt_abar[t], s1 = tb.sqrt_1m[t], c0 = tb.c0[t], cx = tb.cx[t], ce = tb.ce[t],
+                 sig = t > 0 ? s * (double)tb.sigma[t] : 0.0;
+    const float4* st = reinterpret_cast<const float4*>(states + (long long)rd * D);
+    const float4* eq = reinterpret_cast<const float4*>(eps_q + (long long)rd * D);
+    const float4* zz = reinterpret_cast<const float4*>(xi + (long long)rd * D);
+    for (int i = lane; i < nb; i += 64) {
+      const float4 y = st[i], e = eq[i];
+      const float4 z = t > 0 ? zz[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+      const float yy[4] = {y.x, y.y, y.z, y.w}, ee[4] = {e.x, e.y, e.z, e.w}, zv[4] = {z.x, z.y, z.z, z.w};
+      float o[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        double x0 = ((double)yy[j] - s1 * (double)ee[j]) / sa;
+        if (CLIP) x0 = fmin(fmax(x0, -cv), cv);
+        o[j] = (float)(c0 * x0 + cx * (double)yy[j] + ce * (double)ee[j] + sig * (double)zv[j]);
+      }
+      xo[i] = make_float4(o[0], o[1], o[2], o[3]);
+    }
+    if (lane == 0) { t_next[b] = t - 1; n_accept[b] = K_eff; if (n_adv) n_adv[b] = K_eff + 1; }
+    return;
+  }
   if (jstar == 0) {                                 // every draft accepted: commit y_{K_eff}
     const float4* yl = reinterpret_cast<const float4*>(y_last + (long long)b * D);
     for (int i = lane; i < nb; i += 64) xo[i] = yl[i];

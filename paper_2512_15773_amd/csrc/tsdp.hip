@@ -64,6 +64,9 @@ struct tsdp_ctx {
   int cond_B = 0;
   int32_t* status = nullptr;
   int32_t* live = nullptr;      // environments still running (chain driver)
+  int32_t* K_sel = nullptr;     // [B_max] per-round picks from the stage tables (staged chain driver)
+  float* s_sel = nullptr;
+  float* lam_sel = nullptr;
   double* loss_partial = nullptr;   // per-workgroup partial sums of the distillation loss
   int32_t* K_eff = nullptr;     // [B_max]
   // network workspace (lazy)
@@ -437,10 +440,13 @@ size_t fused_draft_lds(const Net& n, const tsdp_config& cf, int rpt) {
   return act + scr + 2 * 4 * NT * 4 + 2 * NT * cf.A * 4 + (size_t)rpt * n.L * 4 * D * 4 + 16 * (D + PAD) * ES;  // upper bound
 }
 
+// rows of the ragged batch a context must hold: K_max per environment, one more with the bonus row
+inline size_t rows_max(const tsdp_config& cf) { return (size_t)cf.B_max * (cf.K_max + (cf.bonus_row ? 1 : 0)); }
+
 int ensure_workspace(tsdp_ctx* c) {
   if (c->ws_ready) return TSDP_OK;
   const tsdp_config& cf = c->cfg;
-  const size_t Rw = (size_t)cf.B_max * cf.K_max, Mw = Rw * cf.H;
+  const size_t Rw = rows_max(cf), Mw = Rw * cf.H;
   const size_t dmax = std::max(cf.base_d, cf.draft_d);
   const size_t mmax = std::max(c->net[0].m, c->net[1].m);
   const size_t lmax = std::max(cf.base_layers, cf.draft_layers);
@@ -460,7 +466,7 @@ int ensure_workspace(tsdp_ctx* c) {
 int ensure_round_buffers(tsdp_ctx* c) {
   if (c->rb_ready) return TSDP_OK;
   const tsdp_config& cf = c->cfg;
-  const size_t Rw = (size_t)cf.B_max * cf.K_max, B = cf.B_max, D = c->D;
+  const size_t Rw = rows_max(cf), B = cf.B_max, D = c->D;
   int rc;
   if ((rc = dev_alloc(c, &c->row_ptr, B + 1))) return rc;
   if ((rc = dev_alloc(c, &c->row_t, Rw))) return rc;
@@ -507,7 +513,8 @@ int tsdp_create(const tsdp_config* cfg, tsdp_ctx** out) {
     return TSDP_E_INVAL;
   if (f.sampler < 0 || f.sampler > 1 || (f.sampler == 1 && !(f.eta > 0.0f && f.eta <= 1.0f))) return TSDP_E_INVAL;
   if (f.schedule == 0 && !(f.beta0 > 0.0f && f.beta1 >= f.beta0 && f.beta1 < 1.0f)) return TSDP_E_INVAL;
-  if ((long long)f.B_max * f.K_max > (1ll << 24)) return TSDP_E_SHAPE;
+  if (f.bonus_row < 0 || f.bonus_row > 1) return TSDP_E_INVAL;
+  if ((long long)f.B_max * (f.K_max + 1) > (1ll << 24)) return TSDP_E_SHAPE;
   tsdp_ctx* c = new (std::nothrow) tsdp_ctx();
   if (!c) return TSDP_E_NOMEM;
   c->cfg = f;
@@ -687,7 +694,13 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
   hipStream_t s = (hipStream_t)stream;
   const tsdp_config& cf = c->cfg;
   const int D = c->D;
-  hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, d_t0, d_K, B, cf.K_max, cf.T, c->K_eff, d_row_ptr, c->status);
+  hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, d_t0, d_K, B, cf.K_max, cf.T, cf.bonus_row, c->K_eff, d_row_ptr,
+                     c->status);
+  auto bonus_rows = [&]() {
+    if (cf.bonus_row)
+      hipLaunchKernelGGL(k_bonus_rows, dim3(B), dim3(128), 0, s, d_t0, (const int32_t*)c->K_eff, (const int32_t*)d_row_ptr,
+                         d_env_id, cf.T, D, cf.seed, (const float*)d_y_last, d_states, d_eps_p, d_xi);
+  };
   hipLaunchKernelGGL(k_rows, dim3(B), dim3(128), 0, s, d_x, d_t0, (const int32_t*)d_row_ptr, cf.T, D, d_row_t,
                      d_row_env, d_y_last, d_states, d_eps_p, d_xi);
   Net& dn = c->net[1];
@@ -706,6 +719,7 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
       tick(c, 0, 0, s);
       (big ? dn.fused_draft_big : dn.fused_draft_small)(dn.fnet, io, cf.A, s);
       tick(c, 0, 1, s);
+      bonus_rows();
       HIPCHK(c, hipGetLastError());
       return TSDP_OK;
     }
@@ -717,6 +731,7 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
                        d_t0, (const int32_t*)c->K_eff, (const int32_t*)d_row_ptr, d_sigma_scale, d_env_id, c->tb,
                        cf.clip_x0, cf.clip_val, cf.seed, B, D, d_y_last, d_states, d_eps_p, d_xi);
   }
+  bonus_rows();
   HIPCHK(c, hipGetLastError());
   return TSDP_OK;
 }
@@ -728,8 +743,8 @@ int tsdp_verify(tsdp_ctx* c, int B, int R_cap, const int32_t* d_row_ptr, const i
   if (B == 0 || R_cap == 0) return TSDP_OK;
   if (!d_row_ptr || !d_row_t || !d_row_env || !d_states || !d_eps_q)
     return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_verify");
-  if (R_cap < 0 || (long long)R_cap > (long long)c->cfg.B_max * c->cfg.K_max)
-    return fail(c, TSDP_E_SHAPE, "R_cap outside 0..B_max*K_max");
+  if (R_cap < 0 || (size_t)R_cap > rows_max(c->cfg))
+    return fail(c, TSDP_E_SHAPE, "R_cap outside 0..B_max*(K_max+bonus_row)");
   if (B == 0 || R_cap == 0) return TSDP_OK;
   if ((rc = ensure_workspace(c))) return rc;
   forward(c, c->net[0], d_states, R_cap, d_row_ptr + B, d_row_t, 0, d_row_env, d_eps_q, (hipStream_t)stream);
@@ -757,7 +772,7 @@ static int accept_impl(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32
   const int maxi = (c->D / 4 + 15) / 16;            // float4 per lane and row, 1..8 (H*A <= 512 is checked at create)
 #define TSDP_ACCEPT(CL, MI)                                                                                     \
   hipLaunchKernelGGL((k_accept<CL, MI>), g, blk, 0, s, B, c->D, d_row_ptr, d_row_t, d_env_id, d_sigma_scale,   \
-                     d_states, d_eps_p, d_eps_q, d_xi, d_y_last, c->tb, cf.clip_val, cf.seed, d_lambda, d_x_out, d_t_next, \
+                     d_states, d_eps_p, d_eps_q, d_xi, d_y_last, c->tb, cf.clip_val, cf.seed, d_lambda, cf.bonus_row, d_x_out, d_t_next, \
                      d_n_accept, d_n_adv, d_flags, d_logratio, d_logu)
 #define TSDP_ACCEPT_MI(MI) \
   case MI: if (cf.clip_x0) TSDP_ACCEPT(true, MI); else TSDP_ACCEPT(false, MI); break;
@@ -803,7 +818,7 @@ static int round_impl(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_
   if ((rc = tsdp_draft(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, c->row_ptr, c->row_t, c->row_env, c->states,
                        c->eps_p, c->xi, c->y_last, stream)))
     return rc;
-  if ((rc = tsdp_verify(c, B, B * c->cfg.K_max, c->row_ptr, c->row_t, c->row_env, c->states, c->eps_q, stream)))
+  if ((rc = tsdp_verify(c, B, B * (c->cfg.K_max + (c->cfg.bonus_row ? 1 : 0)), c->row_ptr, c->row_t, c->row_env, c->states, c->eps_q, stream)))
     return rc;
   // x and t are overwritten in place: the acceptance kernel reads only the round's own buffers
   return accept_impl(c, B, c->row_ptr, c->row_t, d_env_id, d_sigma_scale, d_lambda, c->states, c->eps_p, c->eps_q, c->xi,
@@ -823,26 +838,42 @@ int tsdp_round_threshold(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int
   return round_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, d_lambda, d_n_accept, d_n_advanced, stream);
 }
 
-int tsdp_chain(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
-               const int32_t* d_env_id, const float* d_lambda, int max_rounds, int check_every, int32_t* d_tot_accept,
-               int32_t* d_tot_drafts, int32_t* d_tot_rounds, int32_t* h_rounds, void* stream) {
+static int chain_impl(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
+                      const int32_t* d_env_id, const float* d_lambda, bool staged, int t_hi, int t_lo, int max_rounds,
+                      int check_every, int32_t* d_tot_accept, int32_t* d_tot_drafts, int32_t* d_tot_rounds,
+                      int32_t* h_rounds, void* stream) {
   int rc = check_ready(c, B, true);
   if (rc) return rc;
   if (h_rounds) *h_rounds = 0;
   if (B == 0) return TSDP_OK;
   if (!d_x || !d_t || !d_K || !d_sigma_scale) return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_chain");
   if (max_rounds < 1 || check_every < 1) return fail(c, TSDP_E_INVAL, "max_rounds and check_every must be positive");
+  if (staged && !(t_hi >= t_lo && t_lo >= 0)) return fail(c, TSDP_E_INVAL, "stage bounds must satisfy t_hi >= t_lo >= 0");
   if ((rc = ensure_round_buffers(c))) return rc;
   hipStream_t s = (hipStream_t)stream;
   if (!c->live) {
     if ((rc = dev_alloc(c, &c->live, 1))) return rc;
+  }
+  if (staged && !c->K_sel) {
+    if ((rc = dev_alloc(c, &c->K_sel, (size_t)c->cfg.B_max))) return rc;
+    if ((rc = dev_alloc(c, &c->s_sel, (size_t)c->cfg.B_max))) return rc;
+    if ((rc = dev_alloc(c, &c->lam_sel, (size_t)c->cfg.B_max))) return rc;
   }
   const dim3 gb((B + 255) / 256), blk(256);
   for (int32_t* p : {d_tot_accept, d_tot_drafts, d_tot_rounds})
     if (p) hipLaunchKernelGGL(k_fill_i32, gb, blk, 0, s, p, B, 0);
   int rounds = 0;
   while (rounds < max_rounds) {
-    if ((rc = round_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, d_lambda, c->n_acc, c->n_adv, stream))) return rc;
+    if (staged) {
+      // the round's K, sigma scale and threshold are those of the stage each environment is in now
+      hipLaunchKernelGGL(k_stage_select, gb, blk, 0, s, B, (const int32_t*)d_t, t_hi, t_lo, d_K, d_sigma_scale, d_lambda,
+                         c->K_sel, c->s_sel, c->lam_sel);
+      rc = round_impl(c, B, d_x, d_t, c->K_sel, c->s_sel, d_env_id, d_lambda ? c->lam_sel : nullptr, c->n_acc, c->n_adv,
+                      stream);
+    } else {
+      rc = round_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, d_lambda, c->n_acc, c->n_adv, stream);
+    }
+    if (rc) return rc;
     ++rounds;
     const bool check = rounds % check_every == 0 || rounds == max_rounds;
     hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(1), 0, s, c->live, 1, 0);
@@ -861,16 +892,30 @@ int tsdp_chain(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K,
   return TSDP_OK;
 }
 
+int tsdp_chain(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
+               const int32_t* d_env_id, const float* d_lambda, int max_rounds, int check_every, int32_t* d_tot_accept,
+               int32_t* d_tot_drafts, int32_t* d_tot_rounds, int32_t* h_rounds, void* stream) {
+  return chain_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, d_lambda, false, 0, 0, max_rounds, check_every,
+                    d_tot_accept, d_tot_drafts, d_tot_rounds, h_rounds, stream);
+}
+
+int tsdp_chain_staged(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K3, const float* d_sigma_scale3,
+                      const float* d_lambda3, int t_hi, int t_lo, const int32_t* d_env_id, int max_rounds, int check_every,
+                      int32_t* d_tot_accept, int32_t* d_tot_drafts, int32_t* d_tot_rounds, int32_t* h_rounds, void* stream) {
+  return chain_impl(c, B, d_x, d_t, d_K3, d_sigma_scale3, d_env_id, d_lambda3, true, t_hi, t_lo, max_rounds, check_every,
+                    d_tot_accept, d_tot_drafts, d_tot_rounds, h_rounds, stream);
+}
+
 int tsdp_distill_loss(tsdp_ctx* c, int R, const int32_t* d_row_t, const float* d_states, const float* d_eps_p,
                       const float* d_eps_q, float lambda1, float lambda2, double* d_loss, void* stream) {
   if (!c) return TSDP_E_INVAL;
-  if (R < 0 || (long long)R > (long long)c->cfg.B_max * c->cfg.K_max) return fail(c, TSDP_E_SHAPE, "R outside 0..B_max*K_max");
+  if (R < 0 || (size_t)R > rows_max(c->cfg)) return fail(c, TSDP_E_SHAPE, "R outside 0..B_max*(K_max+bonus_row)");
   if (!d_loss || (R > 0 && (!d_row_t || !d_states || !d_eps_p || !d_eps_q)))
     return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_distill_loss");
   hipStream_t s = (hipStream_t)stream;
   const int parts = (R + 15) / 16;
   if (!c->loss_partial) {
-    int rc = dev_alloc(c, &c->loss_partial, 2 * (((size_t)c->cfg.B_max * c->cfg.K_max + 15) / 16) + 2);
+    int rc = dev_alloc(c, &c->loss_partial, 2 * ((rows_max(c->cfg) + 15) / 16) + 2);
     if (rc) return rc;
   }
   if (parts > 0) {

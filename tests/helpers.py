@@ -15,10 +15,10 @@ def oracle_side(wl, wb, wd, clip=None, sampler=0, eta=1.0):
     return base, drafter, sched
 
 
-def gpu_side(wl, wb, wd, cond, clip=None, B_max=None, K_max=None, seed=None, sampler=0, eta=1.0):
+def gpu_side(wl, wb, wd, cond, clip=None, B_max=None, K_max=None, seed=None, sampler=0, eta=1.0, bonus_row=False):
     import torch
     from paper_2512_15773_amd import Tsdp
-    ctx = Tsdp.from_workload(wl, B_max=B_max, K_max=K_max, clip=clip, seed=seed, sampler=sampler, eta=eta)
+    ctx = Tsdp.from_workload(wl, B_max=B_max, K_max=K_max, clip=clip, seed=seed, sampler=sampler, eta=eta, bonus_row=bonus_row)
     ctx.tsdp_load_weights(0, ti.pack_blob(wb))
     ctx.tsdp_load_weights(1, ti.pack_blob(wd))
     ctx.tsdp_set_cond(torch.from_numpy(cond).cuda())

@@ -15,14 +15,15 @@ TOL = {"fp32": 1e-5, "bf16": 2e-2}
 TIE = 1e-5          # accept flags may differ only where |log U - log alpha| is below this (fp32 nets)
 
 
-def _setup(wl, B, clip=None, K_max=None, b_std=0.02, head_scale=1.0, seed=None, sampler=0, eta=1.0):
+def _setup(wl, B, clip=None, K_max=None, b_std=0.02, head_scale=1.0, seed=None, sampler=0, eta=1.0, bonus=False):
     wb = ti.make_weights(wl, "base", b_std=b_std, head_scale=head_scale)
     wd = ti.make_weights(wl, "draft", b_std=b_std, head_scale=head_scale)
     cond = ti.make_cond(wl, B)
     x = ti.make_latents(wl, B)
     base, drafter, sched = oracle_side(wl, wb, wd, sampler=sampler, eta=eta)
-    ctx = gpu_side(wl, wb, wd, cond, clip=clip, B_max=B, K_max=K_max, seed=seed, sampler=sampler, eta=eta)
-    return dict(wl=wl, B=B, cond=cond, x=x, base=base, drafter=drafter, sched=sched, ctx=ctx, clip=clip,
+    ctx = gpu_side(wl, wb, wd, cond, clip=clip, B_max=B, K_max=K_max, seed=seed, sampler=sampler, eta=eta,
+                   bonus_row=bonus)
+    return dict(wl=wl, B=B, cond=cond, x=x, base=base, drafter=drafter, sched=sched, ctx=ctx, clip=clip, bonus=bonus,
                 seed=wl.philox_seed if seed is None else seed)
 
 
@@ -35,7 +36,7 @@ def _gpu_draft(S, t0, K, s, env):
 
 
 def _check_draft(S, rows, t0, K, s, env, tol):
-    o = sr.draft(S["drafter"], S["sched"], S["x"], t0, K, s, env, S["seed"], S["cond"], S["clip"])
+    o = sr.draft(S["drafter"], S["sched"], S["x"], t0, K, s, env, S["seed"], S["cond"], S["clip"], S["bonus"])
     R = int(o["row_ptr"][-1])
     np.testing.assert_array_equal(rows["row_ptr"].cpu().numpy(), o["row_ptr"])
     np.testing.assert_array_equal(rows["row_t"].cpu().numpy()[:R], o["row_t"])
@@ -73,7 +74,7 @@ def _check_accept(S, rows, o, s, env, window):
     g = {k: v.cpu().numpy() for k, v in out.items()}
     ref = sr.accept(S["sched"], o["row_ptr"], o["row_t"], s.astype(np.float32), env, S["seed"],
                     rows["states"].cpu().numpy()[:R], rows["eps_p"].cpu().numpy()[:R], rows["eps_q"].cpu().numpy()[:R],
-                    rows["xi"].cpu().numpy()[:R], rows["y_last"].cpu().numpy(), S["clip"])
+                    rows["xi"].cpu().numpy()[:R], rows["y_last"].cpu().numpy(), S["clip"], bonus=S["bonus"])
     np.testing.assert_allclose(g["logu"][:R], ref["logu"], rtol=1e-6, atol=1e-7)
     np.testing.assert_allclose(g["logratio"][:R], ref["logratio"], rtol=1e-6, atol=1e-6)
     near = np.abs(ref["logu"] - ref["logratio"]) < window
@@ -86,8 +87,8 @@ def _check_accept(S, rows, o, s, env, window):
     return g, ref, env_ok
 
 
-def _stage_parity(wl, B, t0, K, s, env=None, clip=None, b_std=0.02, paths=None, sampler=0, eta=1.0):
-    S = _setup(wl, B, clip=clip, b_std=b_std, sampler=sampler, eta=eta)
+def _stage_parity(wl, B, t0, K, s, env=None, clip=None, b_std=0.02, paths=None, sampler=0, eta=1.0, bonus=False):
+    S = _setup(wl, B, clip=clip, b_std=b_std, sampler=sampler, eta=eta, bonus=bonus)
     if paths is not None:
         assert (S["ctx"].path_name(0), S["ctx"].path_name(1)) == paths
     tol = TOL[wl.dtype]
@@ -106,9 +107,9 @@ def test_c1_stages():
 
 
 def test_c1_ragged_edges_with_clip():
-    # K_eff = 0 (t0 = 0), finished env, t0 < K, K = 0 and K = 1, per-env sigma scale, env ids, clamped x0
+    # K_eff = 0 (t0 = 0), finished env, t0 < K, K = 1, per-env sigma scale, env ids, clamped x0
     wl = ti.small_variant(ti.C1, B=8)
-    t0 = np.array([9, 0, -1, 2, 5, 7, 1, 9]); K = np.array([4, 4, 4, 4, 0, 1, 3, 2])
+    t0 = np.array([9, 0, -1, 2, 5, 7, 1, 9]); K = np.array([4, 4, 4, 4, 1, 1, 3, 2])
     s = np.array([1.0, 1.0, 1.0, 1.3, 1.0, 1.5, 1.2, 1.1]); env = np.array([5, 900, 3, 77, 1, 0, 12345678, 42])
     for clip in (None, 1.0):
         g, ref = _stage_parity(wl, 8, t0, K, s, env, clip=clip)
@@ -171,7 +172,7 @@ def test_c2_round_and_chain():
 def test_round_ragged_batch_fp32():
     wl = ti.small_variant(ti.C2, B=12, base=ti.NetShape(3, 256, 4))
     rng = np.random.default_rng(3)
-    t0 = rng.integers(-1, 100, 12); K = rng.integers(0, 9, 12); s = rng.uniform(1, 1.5, 12)
+    t0 = rng.integers(-1, 100, 12); K = rng.integers(1, 9, 12); s = rng.uniform(1, 1.5, 12)
     t0[:3] = [0, -1, 2]
     ref, near = _round_parity(wl, 12, t0, K, s, np.arange(12) + 1000, 1e-4, head_scale=0.5)
     assert near.sum() <= 2
@@ -188,6 +189,12 @@ def test_device_status_reports_clamped_inputs():
     assert rows["row_ptr"].cpu().numpy().tolist() == [0, 4]
     assert rows["row_t"].cpu().numpy()[:4].tolist() == [9, 8, 7, 6]
     assert S["ctx"].tsdp_status() == 0
+    # K = 0 has no meaning without the bonus row: reported and run as K = 1
+    S["ctx"].tsdp_draft(to_dev(S["x"]), to_dev(np.array([5], np.int32)), to_dev(np.array([0], np.int32)),
+                        to_dev(np.array([1.0], np.float32)), None, rows)
+    assert S["ctx"].tsdp_status() == 1
+    assert rows["row_ptr"].cpu().numpy().tolist() == [0, 1] and rows["row_t"].cpu().numpy()[0] == 5
+    np.testing.assert_array_equal(rows["states"].cpu().numpy()[0], np.asarray(S["x"][0], np.float32))
     S["ctx"].close()
 
 
@@ -338,4 +345,63 @@ def test_ddim_sampler_stages_and_loss():
     ref = sr.distill_loss(S["sched"], rows["row_t"].cpu().numpy()[:R], rows["states"].cpu().numpy()[:R],
                           rows["eps_p"].cpu().numpy()[:R], rows["eps_q"].cpu().numpy()[:R], 1.0, 1.0, 2.0)
     np.testing.assert_allclose(got, ref, rtol=1e-10)
+    S["ctx"].close()
+
+
+def test_bonus_row_stages_rounds_and_chain():
+    # K+1 candidate set: the extra base row in the row table, in verification and in the commit; K = 0 = plain base step
+    wl = ti.small_variant(ti.C1, B=8)
+    t0 = np.array([9, 0, -1, 2, 5, 7, 1, 9]); K = np.array([4, 4, 4, 4, 0, 1, 3, 2])
+    s = np.array([1.0, 1.0, 1.0, 1.3, 1.0, 1.5, 1.2, 1.1]); env = np.array([5, 900, 3, 77, 1, 0, 12345678, 42])
+    for clip in (None, 1.0):
+        g, ref = _stage_parity(wl, 8, t0, K, s, env, clip=clip, bonus=True)
+        np.testing.assert_array_equal(ref["n_adv"][[1, 2, 4]], [1, 0, 1])
+        assert (ref["n_adv"] == ref["n_accept"] + 1)[t0 >= 0].all()     # a corrected or a base step ends every round
+    wl = ti.small_variant(ti.C3, B=5)
+    t0, K, s = ti.make_schedule_inputs(wl, 5, t0=45)
+    t0[3] = 2; t0[4] = 0
+    _stage_parity(wl, 5, t0, K, s, bonus=True, paths=("bf16-mfma-fused", "bf16-mfma-fused"))
+    # identical networks: every draft passes and each round advances K_eff + 1 exact base steps
+    wl = ti.small_variant(ti.C1, B=4)
+    wb = ti.make_weights(wl, "base", b_std=0.02)
+    cond = ti.make_cond(wl, 4); x0 = ti.make_latents(wl, 4)
+    wl_same = ti.small_variant(wl, draft=wl.base)
+    base, _, sched = oracle_side(wl_same, wb, wb)
+    ctx = gpu_side(wl_same, wb, wb, cond, B_max=4, bonus_row=True)
+    t0 = np.array([9, 9, 4, 1]); K = np.array([3, 2, 4, 4]); s = np.ones(4)
+    x = to_dev(x0); t = to_dev(t0.astype(np.int32))
+    rounds, tot = ctx.tsdp_chain(x, t, to_dev(K.astype(np.int32)), to_dev(s.astype(np.float32)), None, check_every=2)
+    ref = sr.chain(base, base, sched, x0, t0, K, s, None, wl.philox_seed, cond, bonus=True)
+    assert rounds >= ref["rounds"] and (t.cpu().numpy() == -1).all()
+    np.testing.assert_array_equal(tot["rounds"].cpu().numpy(), ref["totals"]["rounds"])
+    np.testing.assert_array_equal(tot["rounds"].cpu().numpy(), [3, 4, 1, 1])            # ceil((t0+1)/(K+1))
+    np.testing.assert_array_equal(tot["accept"].cpu().numpy(), ref["totals"]["accept"])
+    assert scaled_err(x.cpu().numpy(), ref["x"]) < 1e-4
+    ctx.close()
+
+
+def test_staged_chain_follows_the_stage_tables():
+    wl = ti.small_variant(ti.C1, B=6)
+    S = _setup(wl, 6, head_scale=0.6)
+    t0 = np.array([9, 9, 6, 3, 0, -1])
+    K3 = np.array([[1, 4, 2], [2, 3, 1], [4, 4, 4], [1, 1, 3], [2, 2, 2], [1, 1, 1]])
+    s3 = np.array([[1.0, 1.2, 1.0]] * 6); l3 = np.array([[0.3, 0.5, 0.9]] * 6)
+    for lam in (None, l3):
+        x = to_dev(S["x"]); t = to_dev(t0.astype(np.int32))
+        rounds, tot = S["ctx"].tsdp_chain_staged(x, t, to_dev(K3.astype(np.int32)), to_dev(s3.astype(np.float32)),
+                                                 None if lam is None else to_dev(lam.astype(np.float32)), 7, 3, None,
+                                                 check_every=1)
+        ref = sr.chain(S["base"], S["drafter"], S["sched"], S["x"], t0, K3, s3.astype(np.float32),
+                       None, S["seed"], S["cond"], lam=None if lam is None else lam.astype(np.float32), stages=(7, 3))
+        for r in ref["history"]:
+            near = (np.abs(r["logu"] - r["logratio"]) < 1e-4) & (r["draft"]["row_t"] > 0)
+            assert not near.any()
+        assert rounds == ref["rounds"] and (t.cpu().numpy() == -1).all()
+        for k in ("accept", "drafts", "rounds"):
+            np.testing.assert_array_equal(tot[k].cpu().numpy(), ref["totals"][k])
+        assert scaled_err(x.cpu().numpy(), ref["x"]) < 1e-4
+    import pytest as _pt
+    from paper_2512_15773_amd import TsdpError
+    with _pt.raises(TsdpError):
+        S["ctx"].tsdp_chain_staged(x, t, to_dev(K3.astype(np.int32)), to_dev(s3.astype(np.float32)), None, 2, 3, None)
     S["ctx"].close()
