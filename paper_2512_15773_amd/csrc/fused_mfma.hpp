@@ -170,7 +170,16 @@ struct FragGemm {
     for (int mb = 0; mb < MB; ++mb) a[0][mb] = wl[(size_t)mb * kst * 64];
   }
 
+  struct NoSide { __device__ __forceinline__ void operator()(int) const {} };
+
   __device__ __forceinline__ void run(const elem* act, int stride, f32x4 (&acc)[MB][NB], int lane) {
+    run(act, stride, acc, lane, NoSide{});
+  }
+
+  // side(k) is called once per k-step after its MFMAs have been issued: independent vector work placed there
+  // (an epilogue of the previous product) executes while the matrix pipeline is busy.
+  template <class Side>
+  __device__ __forceinline__ void run(const elem* act, int stride, f32x4 (&acc)[MB][NB], int lane, Side&& side) {
     const elem* al = act + (lane & 15) * stride + (lane >> 4) * TT::VW;
     frag b[BD][NB];
 #pragma unroll
@@ -200,6 +209,7 @@ struct FragGemm {
           for (int nb = 0; nb < NB; ++nb)
             TT::mma(a[k % (PF + 1)][mb], b[k % BD][nb], acc[mb][nb]);
       }
+      side(k);
       if (BD == 1 && k + 1 < NKS) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) b[0][nb] = *reinterpret_cast<const frag*>(al + nb * 16 * stride + (k + 1) * TT::KSTEP);
@@ -210,19 +220,20 @@ struct FragGemm {
 };
 
 // D model width, NT tokens per workgroup, H tokens per row, HEADS attention heads, CM conditioning mode,
-// CH hidden-chunk width of the MLP, SX observation tokens (cross-attention), HP heads per attention phase,
+// CH hidden-chunk width of the MLP, SX observation tokens (cross-attention), HP heads per self-attention phase,
+// HPX heads per cross-attention phase (it needs no key / value buffers in LDS, so it can take more heads at once),
 // NW wavefronts per workgroup; every wavefront owns D/NW residual features of every token of the tile.
-template <class TT_, int D_, int NT_, int H_, int HEADS_, int CM_, int CH_, int SX_, int HP_, int NW_>
+template <class TT_, int D_, int NT_, int H_, int HEADS_, int CM_, int CH_, int SX_, int HP_, int NW_, int HPX_ = HP_>
 struct FusedCfg {
   typedef TT_ TT;
   static constexpr int ES = sizeof(typename TT_::elem), KSTEP = TT_::KSTEP;
-  static constexpr int D = D_, NT = NT_, H = H_, HEADS = HEADS_, CM = CM_, CH = CH_, SX = SX_, HP = HP_, NW = NW_;
+  static constexpr int D = D_, NT = NT_, H = H_, HEADS = HEADS_, CM = CM_, CH = CH_, SX = SX_, HP = HP_, NW = NW_, HPX = HPX_;
   static constexpr int THREADS = NW * 64;
   static constexpr int DH = D / HEADS;
   static constexpr int NB = NT / 16;                    // token fragments
   static constexpr int MBH = D / 16 / NW;               // residual feature fragments per wave
   static constexpr int MBQ = HP * 3 * DH / 16 / NW;     // q|k|v feature fragments per wave and phase
-  static constexpr int MBC = HP * DH / 16 / NW;         // cross-attention query fragments per wave and phase
+  static constexpr int MBC = HPX * DH / 16 / NW;        // cross-attention query fragments per wave and phase
   static constexpr int MBU = CH / 16 / NW;
   static constexpr int RPT = NT / H;                    // rows per tile
   static constexpr int NKF = H / 16;                    // key / query fragments of self-attention
@@ -234,15 +245,14 @@ struct FusedCfg {
   static constexpr int ACT_B = NT * AS * ES;
   static constexpr int Q_B = HP * NT * QS * ES;
   static constexpr int VT_B = HP * RPT * DH * VS * ES;
-  static constexpr int QKV_B = 2 * Q_B + VT_B;
+  static constexpr int QKV0_B = 2 * Q_B + VT_B;
+  static constexpr int QX_B = CM_ == 1 ? NT * (HPX * DH + TT_::PAD) * ES : 0;   // queries of one cross-attention phase
+  static constexpr int QKV_B = QKV0_B > QX_B ? QKV0_B : QX_B;
   static constexpr int U_B = NT * US * ES;
   static constexpr int XT_B = NT * 64 * 4;              // fp32 latent staging of the verify kernel (A <= 64)
   // two hidden-chunk buffers (one barrier per chunk instead of two) when a single workgroup owns the CU's LDS
 #ifndef TSDP_UDB_OK
 #define TSDP_UDB_OK 1
-#endif
-#ifndef TSDP_XLOAD_EARLY
-#define TSDP_XLOAD_EARLY 0   /* requesting the cross-attention operands a phase early costs more registers than it hides */
 #endif
   static constexpr bool UDB = TSDP_UDB_OK && (NW == 8) && (ACT_B + 2 * U_B + 2 * NW * NT * 4 <= 160 * 1024) && (2 * U_B >= QKV_B);
   static constexpr int UU_B = UDB ? 2 * U_B : U_B;
@@ -264,7 +274,8 @@ struct FusedCfg {
 #endif
   static_assert(D % (16 * NW) == 0 && NT % 16 == 0 && H % 16 == 0 && NT % H == 0 && DH % KSTEP == 0, "shape");
   static_assert(D % KSTEP == 0 && CH % KSTEP == 0, "shape");
-  static_assert((HEADS % HP) == 0 && (HP * 3 * DH) % (16 * NW) == 0 && (HP * DH) % (16 * NW) == 0, "shape");
+  static_assert((HEADS % HP) == 0 && (HP * 3 * DH) % (16 * NW) == 0 && (HPX * DH) % (16 * NW) == 0 &&
+                (HEADS % HPX) == 0, "shape");
   static_assert(CH % (16 * NW) == 0 && (4 * D) % CH == 0, "shape");
   static_assert(CM == 0 || (SX % 16 == 0 && SX >= 16 && ES == 2), "cross-attention: bf16 only, tokens a multiple of 16");
 };
@@ -467,15 +478,15 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         for (int kf = 0; kf < SF; ++kf) va[cf][kf] = vcp[(cf * SF + kf) * 64];
     }
   };
-  auto cross_attend = [&](int r, int hh, int qf, const bf16x8 (&ka)[KHc][SFc], const bf16x4 (&va)[DH / 16][SFc]) {
+  // qp: the 16 queries of the task, row stride qs; the result overwrites them
+  auto cross_attend = [&](__bf16* qp, int qs, const bf16x8 (&ka)[KHc][SFc], const bf16x4 (&va)[DH / 16][SFc]) {
     if constexpr (CM == 1) {
-      __bf16* qp = reinterpret_cast<__bf16*>(qbuf) + (hh * NT + r * H + qf * 16) * QS;
       f32x4 s[SF];
 #pragma unroll
       for (int kf = 0; kf < SF; ++kf) s[kf] = f32x4{0, 0, 0, 0};
 #pragma unroll
       for (int ks = 0; ks < KH; ++ks) {
-        const bf16x8 qb = *reinterpret_cast<const bf16x8*>(qp + l16 * QS + ks * 32 + lg * 8);
+        const bf16x8 qb = *reinterpret_cast<const bf16x8*>(qp + l16 * qs + ks * 32 + lg * 8);
 #pragma unroll
         for (int kf = 0; kf < SF; ++kf) s[kf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks][kf], qb, s[kf], 0, 0, 0);
       }
@@ -493,7 +504,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         for (int kf = 0; kf < SF; ++kf)
           o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, va[cf][kf]),
                                                         __builtin_bit_cast(s16x4, p[kf]), o, 0, 0, 0);
-        *reinterpret_cast<bf16x4*>(qp + l16 * QS + cf * 16 + lg * 4) = to_bf16x4(o);
+        *reinterpret_cast<bf16x4*>(qp + l16 * qs + cf * 16 + lg * 4) = to_bf16x4(o);
       }
     }
   };
@@ -576,67 +587,135 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
     add_bias_h(W.o_b);
     // ================= cross-attention block (observation tokens) =================
     if constexpr (CM == 1) {
+      // HPX heads per phase; the queries of a phase are one token-major LDS matrix [NT][HPX*DH], so the output
+      // projection contracts all its heads in one product.  Keys / values come from global memory in fragment
+      // order; a wave requests the operands of its next task before it works on the current one.
+      constexpr int HPX = C::HPX, NGX = HEADS / HPX, QXS = HPX * DH + TT::PAD;
+      constexpr int NTASK = RPT * HPX * NKF, TPW = (NTASK + NW - 1) / NW;
+      typedef FragGemm<TT, MBH, NB, HPX * KH, BD> GOX;
       GC gc;
       if (XPF) gc.issue(W.cq, KD, wave * MBC, 0, lane);
       TSDP_TICK(11)
       write_ln(layer, -1);                               // its barriers order the O-projection reads before qbuf writes
       TSDP_TICK(0)
-      for (int g = 0; g < NG; ++g) {
+      for (int g = 0; g < NGX; ++g) {
         TSDP_FENCE_IDS();
-        GO go;
-        // operands of this wave's first attention task of the group: requested before the query projection
-        bf16x8 ka[KHc][SFc];
-        bf16x4 va[DH / 16][SFc];
-        constexpr int NTASK = RPT * HP * NKF;
-        if (TSDP_XLOAD_EARLY && wave < NTASK) cross_load((wave / NKF) % RPT, layer, g * HP + wave / (NKF * RPT), ka, va);
+        GOX go;
+        bf16x8 ka[2][KHc][SFc];
+        bf16x4 va[2][DH / 16][SFc];
+        // task -> (row, head of the phase, query fragment)
+        auto task_row = [&](int task) { return (task / NKF) % RPT; };
+        auto task_head = [&](int task) { return task / (NKF * RPT); };
         {
           f32x4 acc[MBC][NB];
           f32x4 bias[MBC];
 #pragma unroll
           for (int mb = 0; mb < MBC; ++mb) {
-            bias[mb] = *reinterpret_cast<const f32x4*>(W.cq_b + g * (HP * DH) + (wave * MBC + mb) * 16 + lg * 4);
+            bias[mb] = *reinterpret_cast<const f32x4*>(W.cq_b + g * (HPX * DH) + (wave * MBC + mb) * 16 + lg * 4);
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
           }
-          if (!XPF) gc.issue(W.cq, KD, g * (HP * DH / 16) + wave * MBC, 0, lane);
+          if (!XPF) gc.issue(W.cq, KD, g * (HPX * DH / 16) + wave * MBC, 0, lane);
           gc.run(act, AS, acc, lane);
           TSDP_TICK(1)
-          if (XPF) go.issue(W.co, KD, wave * MBH, g * HP * KH, lane);
+          // the first task's keys / values travel while the queries are written and the barrier is reached
+          if (wave < NTASK) cross_load(task_row(wave), layer, g * HPX + task_head(wave), ka[0], va[0]);
+          if (XPF) go.issue(W.co, KD, wave * MBH, g * HPX * KH, lane);
           if (g > 0) __syncthreads();
           TSDP_TICK(2)
 #pragma unroll
           for (int mb = 0; mb < MBC; ++mb) {
-            const int lr = (wave * MBC + mb) * 16, hh = lr / DH, c0 = lr % DH + lg * 4;
+            const int c0 = (wave * MBC + mb) * 16 + lg * 4;      // column = head-of-phase * DH + feature
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
-              *reinterpret_cast<vec4*>(qbuf + (hh * NT + nb * 16 + l16) * QS + c0) = TT::cvt(acc[mb][nb] + bias[mb]);
+              *reinterpret_cast<vec4*>(qbuf + (nb * 16 + l16) * QXS + c0) = TT::cvt(acc[mb][nb] + bias[mb]);
           }
         }
         TSDP_TICK(3)
         __syncthreads();
         TSDP_TICK(2)
-        if (!(TSDP_ABL & 8))
-          for (int task = wave; task < NTASK; task += NW) {
-            const int hh = task / (NKF * RPT);
-            if (!TSDP_XLOAD_EARLY || task != wave) cross_load((task / NKF) % RPT, layer, g * HP + hh, ka, va);
-            cross_attend((task / NKF) % RPT, hh, task % NKF, ka, va);
+        if (!(TSDP_ABL & 8)) {
+#pragma unroll
+          for (int i = 0; i < TPW; ++i) {
+            const int task = wave + i * NW;
+            if (i + 1 < TPW && task + NW < NTASK)
+              cross_load(task_row(task + NW), layer, g * HPX + task_head(task + NW), ka[(i + 1) & 1], va[(i + 1) & 1]);
+            if (task < NTASK)
+              cross_attend(reinterpret_cast<__bf16*>(qbuf) + (task_row(task) * H + (task % NKF) * 16) * QXS + task_head(task) * DH,
+                           QXS, ka[i & 1], va[i & 1]);
           }
+        }
         TSDP_TICK(10)
         __syncthreads();
         TSDP_TICK(2)
-        if (XPF && g + 1 < NG) gc.issue(W.cq, KD, (g + 1) * (HP * DH / 16) + wave * MBC, 0, lane);
-        if (!XPF) go.issue(W.co, KD, wave * MBH, g * HP * KH, lane);
-        go.run(qbuf, QS, h, lane);
-#pragma unroll
-        for (int hh = 1; hh < HP; ++hh) {
-          go.issue(W.co, KD, wave * MBH, (g * HP + hh) * KH, lane);
-          go.run(qbuf + hh * NT * QS, QS, h, lane);
-        }
+        if (XPF && g + 1 < NGX) gc.issue(W.cq, KD, (g + 1) * (HPX * DH / 16) + wave * MBC, 0, lane);
+        if (!XPF) go.issue(W.co, KD, wave * MBH, g * HPX * KH, lane);
+        go.run(qbuf, QXS, h, lane);
         TSDP_TICK(5)
       }
       add_bias_h(W.co_b);
     }
     // ================= MLP block =================
+    if constexpr (C::UDB && !XPF && (NC % 2 == 0)) {
+      // Two hidden-chunk buffers: the GELU epilogue of chunk c is spread over the k-steps of the up-projection of
+      // chunk c+1, so its vector work runs while the matrix pipeline is busy; one barrier per chunk.
+      TSDP_TICK(11)
+      write_ln(layer, 2);
+      TSDP_TICK(0)
+      f32x4 accA[MBU][NB], accB[MBU][NB];
+      constexpr int PARTS = MBU * NB;
+      auto up_gemm = [&](int c, f32x4 (&acc)[MBU][NB], auto&& side) {
+        GU gu;
+#pragma unroll
+        for (int mb = 0; mb < MBU; ++mb)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
+        gu.issue(W.up, KD, c * (CH / 16) + wave * MBU, 0, lane);
+        gu.run(act, AS, acc, lane, side);
+      };
+      // GELU(acc + bias) of accumulator part idx of chunk c -> hidden buffer c & 1
+      auto gelu_part = [&](int c, const f32x4 (&acc)[MBU][NB], const f32x4 (&bias)[MBU], int idx) {
+        const int mb = idx / NB, nb = idx % NB;
+        const int f0 = (wave * MBU + mb) * 16 + lg * 4;
+        f32x4 v = acc[mb][nb] + bias[mb];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = (TSDP_ABL & 16) ? v[i] : gelu_fast(v[i]);
+        *reinterpret_cast<vec4*>(ubuf + (c & 1) * NT * US + (nb * 16 + l16) * US + f0) = TT::cvt(v);
+      };
+      auto load_bias = [&](int c, f32x4 (&bias)[MBU]) {
+#pragma unroll
+        for (int mb = 0; mb < MBU; ++mb)
+          bias[mb] = *reinterpret_cast<const f32x4*>(W.up_b + c * CH + (wave * MBU + mb) * 16 + lg * 4);
+      };
+      // chunk c: accumulator `cur` holds its pre-activations; `nxt` receives those of chunk c+1
+      auto chunk = [&](int c, f32x4 (&cur)[MBU][NB], f32x4 (&nxt)[MBU][NB]) {
+        TSDP_FENCE_IDS();
+        f32x4 bias[MBU];
+        load_bias(c, bias);
+        if (c + 1 < NC) {
+          up_gemm(c + 1, nxt, [&](int k) {
+#pragma unroll
+            for (int idx = k * PARTS / KD; idx < (k + 1) * PARTS / KD; ++idx) gelu_part(c, cur, bias, idx);
+          });
+        } else {
+#pragma unroll
+          for (int idx = 0; idx < PARTS; ++idx) gelu_part(c, cur, bias, idx);
+        }
+        TSDP_TICK(6)
+        __syncthreads();
+        TSDP_TICK(7)
+        GD gd;
+        gd.issue(W.dn, KM, wave * MBH, c * (KC), lane);
+        gd.run(ubuf + (c & 1) * NT * US, US, h, lane);
+        TSDP_TICK(9)
+      };
+      up_gemm(0, accA, [](int) {});
+      TSDP_TICK(6)
+      for (int c = 0; c < NC; c += 2) {
+        chunk(c, accA, accB);
+        chunk(c + 1, accB, accA);
+      }
+    } else {
     GU gu;
     if (XPF) gu.issue(W.up, KD, wave * MBU, 0, lane);
     TSDP_TICK(11)
@@ -686,6 +765,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       }
       gd.run(ubuf + (C::UDB ? (c & 1) * NT * US : 0), US, h, lane);
       TSDP_TICK(9)
+    }
     }
     add_bias_h(W.dn_b);
   }

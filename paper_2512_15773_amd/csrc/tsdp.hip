@@ -210,12 +210,18 @@ struct FusedKernels {
   int rpt_small = 0, rpt_big = 0;
 };
 
+#ifndef TSDP_V512_HPX
+#define TSDP_V512_HPX 8    /* heads per cross-attention phase of the d = 512 verify kernel */
+#endif
+#ifndef TSDP_V512_CH
+#define TSDP_V512_CH 256   /* hidden-chunk width of the d = 512 verify kernel */
+#endif
 // shapes with compiled fused kernels
 bool find_fused(int dtype, int D, int H, int heads, int cm, int S, int mlp_ratio, int L, FusedKernels& k) {
   if (mlp_ratio != 4 || L > FUSED_MAX_LAYERS) return false;
-#define TSDP_SHAPE(TT_, DT_, D_, H_, HD_, CM_, SX_, NTV, CHV, HPV, NWV, NTS, CHS, HPS, NTB, CHB, HPB, NWD)        \
+#define TSDP_SHAPE(TT_, DT_, D_, H_, HD_, CM_, SX_, NTV, CHV, HPV, NWV, HPXV, NTS, CHS, HPS, NTB, CHB, HPB, NWD)  \
   if (dtype == DT_ && D == D_ && H == H_ && heads == HD_ && cm == CM_ && (CM_ == 0 || S == SX_)) {             \
-    k.verify = launch_verify<FusedCfg<TT_, D_, NTV, H_, HD_, CM_, CHV, SX_, HPV, NWV>>;                        \
+    k.verify = launch_verify<FusedCfg<TT_, D_, NTV, H_, HD_, CM_, CHV, SX_, HPV, NWV, HPXV>>;                  \
     k.rpt_verify = NTV / H_;                                                                                   \
     k.mod = DT_ == 1 ? launch_mod<D_> : nullptr;                                                               \
     k.draft_small = launch_draft<FusedCfg<TT_, D_, NTS, H_, HD_, CM_, CHS, SX_, HPS, NWD>>; k.rpt_small = NTS / H_; \
@@ -224,22 +230,22 @@ bool find_fused(int dtype, int D, int H, int heads, int cm, int S, int mlp_ratio
   }
   // The drafter's small tile (one environment per workgroup) is latency-bound: it takes all heads in one attention
   // phase and the whole MLP hidden layer in one chunk, which minimises the number of barrier-separated phases.
-  //         type dtype  D   H heads cm  S | verify: NT  CH  HP NW | draft small: NT CH HP | big: NT CH HP | NW
+  //         type dtype  D   H heads cm  S | verify: NT  CH  HP NW HPX | draft small: NT CH HP | big: NT CH HP | NW
   if (dtype == 1 && D == 256 && H == 16 && heads == 4 && cm == 0)
     k.verify_few = launch_verify<FusedCfg<TBF16, 256, 64, 16, 4, 0, 256, 0, 2, 8>>;
   if (dtype == 1 && D == 384 && H == 16 && heads == 6 && cm == 0)
     k.verify_few = launch_verify<FusedCfg<TBF16, 384, 64, 16, 6, 0, 256, 0, 2, 8>>;
-  TSDP_SHAPE(TBF16, 1, 256, 16, 4, 0, 0, 64, 128, 1, 4, 16, 128, 1, 64, 128, 1, 4)
-  TSDP_SHAPE(TBF16, 1, 384, 16, 6, 0, 0, 64, 192, 1, 4, 16, 128, 1, 64, 128, 1, 4)
-  TSDP_SHAPE(TBF16, 1, 128, 16, 4, 0, 0, 128, 128, 2, 4, 16, 512, 4, 64, 128, 2, 4)
-  TSDP_SHAPE(TBF16, 1, 192, 16, 6, 0, 0, 128, 128, 2, 4, 16, 768, 6, 64, 128, 2, 4)
-  TSDP_SHAPE(TBF16, 1, 512, 32, 8, 1, 64, 64, 256, 2, 8, 32, 128, 1, 64, 128, 1, 4)
-  TSDP_SHAPE(TBF16, 1, 256, 32, 8, 1, 64, 64, 256, 2, 4, 32, 128, 2, 64, 128, 2, 4)
+  TSDP_SHAPE(TBF16, 1, 256, 16, 4, 0, 0, 64, 128, 1, 4, 1, 16, 128, 1, 64, 128, 1, 4)
+  TSDP_SHAPE(TBF16, 1, 384, 16, 6, 0, 0, 64, 192, 1, 4, 1, 16, 128, 1, 64, 128, 1, 4)
+  TSDP_SHAPE(TBF16, 1, 128, 16, 4, 0, 0, 128, 128, 2, 4, 2, 16, 512, 4, 64, 128, 2, 4)
+  TSDP_SHAPE(TBF16, 1, 192, 16, 6, 0, 0, 128, 128, 2, 4, 2, 16, 768, 6, 64, 128, 2, 4)
+  TSDP_SHAPE(TBF16, 1, 512, 32, 8, 1, 64, 64, TSDP_V512_CH, 2, 8, TSDP_V512_HPX, 32, 128, 1, 64, 128, 1, 4)
+  TSDP_SHAPE(TBF16, 1, 256, 32, 8, 1, 64, 64, 256, 2, 4, 2, 32, 128, 2, 64, 128, 2, 4)
   // fp32 networks on the fp32 matrix cores: one row (16 tokens) per workgroup, weights streamed per workgroup
-  TSDP_SHAPE(TF32, 0, 256, 16, 4, 0, 0, 16, 128, 1, 4, 16, 128, 1, 16, 128, 1, 4)
-  TSDP_SHAPE(TF32, 0, 128, 16, 4, 0, 0, 16, 128, 2, 4, 16, 512, 4, 16, 512, 4, 4)
-  TSDP_SHAPE(TF32, 0, 64, 16, 2, 0, 0, 16, 64, 2, 4, 16, 64, 2, 16, 64, 2, 4)
-  TSDP_SHAPE(TF32, 0, 32, 16, 2, 0, 0, 16, 32, 2, 2, 16, 128, 2, 16, 128, 2, 2)
+  TSDP_SHAPE(TF32, 0, 256, 16, 4, 0, 0, 16, 128, 1, 4, 1, 16, 128, 1, 16, 128, 1, 4)
+  TSDP_SHAPE(TF32, 0, 128, 16, 4, 0, 0, 16, 128, 2, 4, 2, 16, 512, 4, 16, 512, 4, 4)
+  TSDP_SHAPE(TF32, 0, 64, 16, 2, 0, 0, 16, 64, 2, 4, 2, 16, 64, 2, 16, 64, 2, 4)
+  TSDP_SHAPE(TF32, 0, 32, 16, 2, 0, 0, 16, 32, 2, 2, 2, 16, 128, 2, 16, 128, 2, 2)
 #undef TSDP_SHAPE
   return false;
 }
