@@ -138,6 +138,9 @@ __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
 #ifndef TSDP_INFLIGHT_CLK
 #define TSDP_INFLIGHT_CLK 384
 #endif
+#ifndef TSDP_LN_PREFETCH
+#define TSDP_LN_PREFETCH 1   /* request the FiLM vectors before the LayerNorm statistics are reduced */
+#endif
 #ifndef TSDP_PFMAX
 #define TSDP_PFMAX 4
 #endif
@@ -364,6 +367,22 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   // Statistics: per-wave partial sums of x and x^2 (fp32) exchanged through LDS, one barrier.
   auto write_ln = [&](int layer, int which) {
     TSDP_FENCE_IDS();
+    // FiLM vectors of the tile's rows: requested first, so they arrive while the statistics are reduced
+    // (only where they fit in 64 registers; otherwise they are read fragment row by fragment row)
+    constexpr bool LNPF = TSDP_LN_PREFETCH && MBH * RPT * 2 <= 16;
+    constexpr int FR = LNPF ? RPT : 1;
+    f32x4 fg[MBH][FR], fb[MBH][FR];
+    if (LNPF && which >= 0) {
+#pragma unroll
+      for (int mb = 0; mb < MBH; ++mb)
+#pragma unroll
+        for (int r = 0; r < RPT; ++r) {
+          const float* mp = modp + (size_t)min(r, mod_rows - 1) * mod_stride + layer * 4 * D + which * D +
+                            (wave * MBH + mb) * 16 + lg * 4;
+          fg[mb][r] = *reinterpret_cast<const f32x4*>(mp);
+          fb[mb][r] = *reinterpret_cast<const f32x4*>(mp + D);
+        }
+    }
     float mean[NB], rstd[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -393,15 +412,19 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       for (int nb = 0; nb < NB; ++nb) {
         f32x4 v = (h[mb][nb] - mean[nb]) * rstd[nb];
         if (which >= 0) {
-          const int row = min((nb * 16) / H, mod_rows - 1);
-          const float* mp = modp + (size_t)row * mod_stride + layer * 4 * D + which * D + f0;
-          const f32x4 g = *reinterpret_cast<const f32x4*>(mp);
-          const f32x4 b = *reinterpret_cast<const f32x4*>(mp + D);
-          v = v * (1.0f + g) + b;
+          if (LNPF) {
+            v = v * (1.0f + fg[mb][(nb * 16) / H]) + fb[mb][(nb * 16) / H];
+          } else {
+            const int row = min((nb * 16) / H, mod_rows - 1);
+            const float* mp = modp + (size_t)row * mod_stride + layer * 4 * D + which * D + f0;
+            const f32x4 g = *reinterpret_cast<const f32x4*>(mp);
+            const f32x4 b = *reinterpret_cast<const f32x4*>(mp + D);
+            v = v * (1.0f + g) + b;
+          }
         }
         *reinterpret_cast<vec4*>(act + (nb * 16 + l16) * AS + f0) = TT::cvt(v);
       }
-      __builtin_amdgcn_sched_barrier(0);                // keep the FiLM loads of one fragment row in flight, not all
+      if (!LNPF) __builtin_amdgcn_sched_barrier(0);   // keep the FiLM loads of one fragment row in flight, not all
     }
     __syncthreads();
   };
