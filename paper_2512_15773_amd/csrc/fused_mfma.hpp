@@ -46,6 +46,8 @@ struct FusedNet {
   const float* head_b;         // [A]
   const void* modw;            // [L*4D/16][D/32][64] FiLM projections of all layers (drafter kernel)
   const float* modb;           // [L*4D]
+  const float* modtab;         // [T][L*4D] FiLM vectors of every timestep when they depend on nothing else
+                               // (token conditioning: no conditioning vector enters them), else null
   const float* temb;           // [T, D]
   const float* cemb;           // [B, D] conditioning embedding (vector conditioning) or null
   // cross-attention operands of every (env, layer, head), prepared by tsdp_set_cond:
@@ -56,7 +58,9 @@ struct FusedNet {
 
 struct FusedIO {               // batched verification
   const float* x_rows;         // [R,H,A]
-  const float* mod;            // [R, L*4*D] FiLM vectors (g1,b1,g2,b2 per layer)
+  const float* mod;            // [R, L*4*D] FiLM vectors (g1,b1,g2,b2 per layer); unused when the network has modtab
+  const int32_t* row_t;        // [R] timestep of the row minus t_sub (selects the modtab row)
+  int t_sub, T;
   const int32_t* row_env;      // [R] or null (row index is the environment)
   const int32_t* d_R;          // live rows on the device, or null
   int R_cap;
@@ -131,6 +135,9 @@ __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
 #endif
 // Optional phase timing for tuning builds (-DTSDP_TRACE): per-wave cycle totals per phase category.
 #ifdef TSDP_TRACE
+#ifndef TSDP_TRACE_BLOCK
+#define TSDP_TRACE_BLOCK 300
+#endif
 #define TSDP_TICK(cat) { const long long now_ = clock64(); tacc_[cat] += now_ - tprev_; tprev_ = now_; }
 #else
 #define TSDP_TICK(cat)
@@ -295,12 +302,12 @@ struct DraftCfg : Base {
 };
 
 // One forward pass for the tile.  xt: LDS fp32 [NT][A] latent tokens (may alias the scratch region: it is
-// consumed before the first barrier-protected write).  modp: FiLM vectors of local row r at
-// modp + min(r, mod_rows-1)*mod_stride (global or LDS).  env_of_row: environment of local row r (cross-attention).
+// consumed before the first barrier-protected write).  mrow[r]: FiLM vectors of local row r, all layers (global
+// or LDS).  env_of_row: environment of local row r (cross-attention).
 // eps is written to eo[t*A + a] for local tokens t < ntok_live.
 template <class C>
 __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* lds, const float* xt, int A,
-                                           const float* modp, int mod_stride, int mod_rows,
+                                           const float* const* mrow,
                                            const int32_t* env_of_row, float* eo, int ntok_live) {
   constexpr int D = C::D, NT = C::NT, H = C::H, HEADS = C::HEADS, CM = C::CM, CH = C::CH, NW = C::NW;
   constexpr int DH = C::DH, HP = C::HP, NB = C::NB, MBH = C::MBH, MBQ = C::MBQ, MBU = C::MBU, MBC = C::MBC,
@@ -377,8 +384,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       for (int mb = 0; mb < MBH; ++mb)
 #pragma unroll
         for (int r = 0; r < RPT; ++r) {
-          const float* mp = modp + (size_t)min(r, mod_rows - 1) * mod_stride + layer * 4 * D + which * D +
-                            (wave * MBH + mb) * 16 + lg * 4;
+          const float* mp = mrow[r] + layer * 4 * D + which * D + (wave * MBH + mb) * 16 + lg * 4;
           fg[mb][r] = *reinterpret_cast<const f32x4*>(mp);
           fb[mb][r] = *reinterpret_cast<const f32x4*>(mp + D);
         }
@@ -415,8 +421,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
           if (LNPF) {
             v = v * (1.0f + fg[mb][(nb * 16) / H]) + fb[mb][(nb * 16) / H];
           } else {
-            const int row = min((nb * 16) / H, mod_rows - 1);
-            const float* mp = modp + (size_t)row * mod_stride + layer * 4 * D + which * D + f0;
+            const float* mp = mrow[(nb * 16) / H] + layer * 4 * D + which * D + f0;
             const f32x4 g = *reinterpret_cast<const f32x4*>(mp);
             const f32x4 b = *reinterpret_cast<const f32x4*>(mp + D);
             v = v * (1.0f + g) + b;
@@ -820,7 +825,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   }
 #ifdef TSDP_TRACE
   TSDP_TICK(10)
-  if (blockIdx.x == 300 && lane == 0 && net.trace && wave < 8)
+  if (blockIdx.x == TSDP_TRACE_BLOCK && lane == 0 && net.trace && wave < 8)
     for (int i = 0; i < 12; ++i) net.trace[wave * 12 + i] = tacc_[i];
 #endif
 }
@@ -831,6 +836,7 @@ __global__ __launch_bounds__(C::THREADS, C::WG_PER_CU) void k_fused_forward(Fuse
   constexpr int D = C::D, NT = C::NT, H = C::H;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   __shared__ int32_t envs[C::RPT];
+  __shared__ const float* mrow[C::RPT];
   const int R = io.d_R ? min(*io.d_R, io.R_cap) : io.R_cap;
   const int row0 = blockIdx.x * C::RPT;
   if (row0 >= R) return;
@@ -841,11 +847,17 @@ __global__ __launch_bounds__(C::THREADS, C::WG_PER_CU) void k_fused_forward(Fuse
   if (threadIdx.x < C::RPT) {
     const int r = min(row0 + (int)threadIdx.x, R - 1);
     envs[threadIdx.x] = io.row_env ? io.row_env[r] : r;
+    const int mod_stride = net.L * 4 * D;
+    if (net.modtab) {
+      int t = io.row_t[r] - io.t_sub;
+      t = t < 0 ? 0 : (t >= io.T ? io.T - 1 : t);
+      mrow[threadIdx.x] = net.modtab + (size_t)t * mod_stride;
+    } else {
+      mrow[threadIdx.x] = io.mod + (size_t)r * mod_stride;
+    }
   }
   __syncthreads();
-  const int mod_stride = net.L * 4 * D;
-  fused_body<C>(net, lds, xt, A, io.mod + (size_t)row0 * mod_stride, mod_stride, R - row0, envs, io.eps_out + tok0 * A,
-                ntok_live);
+  fused_body<C>(net, lds, xt, A, mrow, envs, io.eps_out + tok0 * A, ntok_live);
 }
 
 // Drafter rollout: the workgroup keeps the latents of RPT environments in LDS and runs their drafted
@@ -860,6 +872,7 @@ __global__ __launch_bounds__(C::THREADS) void k_fused_draft(FusedNet net, DraftI
   constexpr int RPT = C::RPT;
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   __shared__ int32_t envs[RPT], s_t0[RPT], s_keff[RPT], s_rowp[RPT], s_kmax;
+  __shared__ const float* mrow[RPT];
   const int DE = H * A;                                 // elements of one latent
   const int mod_stride = net.L * 4 * D;
   float* yt = reinterpret_cast<float*>(lds + C::LDS_B);              // [NT*A] latents
@@ -890,6 +903,14 @@ __global__ __launch_bounds__(C::THREADS) void k_fused_draft(FusedNet net, DraftI
   __syncthreads();
   const int kmax = s_kmax;
   for (int k = 1; k <= kmax; ++k) {
+    if (net.modtab) {                                   // FiLM vectors of timestep t_k straight from the table
+      if (threadIdx.x < RPT) {
+        int t = s_t0[threadIdx.x] - k + 1;
+        t = t < 0 ? 0 : t;
+        mrow[threadIdx.x] = net.modtab + (size_t)t * mod_stride;
+      }
+    } else {
+    if (threadIdx.x < RPT) mrow[threadIdx.x] = modbuf + threadIdx.x * mod_stride;
     // FiLM input of this step: SiLU(temb[t_k] + cemb[env]) as bf16 rows of the mod product's B operand
     for (int i = threadIdx.x; i < RPT * D; i += TH) {
       const int r = i / D, c = i % D;
@@ -920,8 +941,9 @@ __global__ __launch_bounds__(C::THREADS) void k_fused_draft(FusedNet net, DraftI
         }
       }
     }
+    }
     __syncthreads();
-    fused_body<DraftCfg<C>>(net, lds, yt, A, modbuf, mod_stride, RPT, envs, et, NT);
+    fused_body<DraftCfg<C>>(net, lds, yt, A, mrow, envs, et, NT);
     __syncthreads();
     // DDPM step of transition k for the environments that still draft
     const int nblk = DE >> 2;

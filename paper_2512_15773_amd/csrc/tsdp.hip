@@ -30,6 +30,8 @@ struct Net {
   std::vector<LayerOff> lay;
   float* blob = nullptr;        // device copy of the (rounded) canonical blob
   float* temb = nullptr;        // [T, d] timestep embedding of every timestep
+  float* modtab = nullptr;      // [T, L*4d] FiLM vectors of every timestep (token conditioning, fused bf16 path)
+  int32_t* t_iota = nullptr;    // [T] 0..T-1, the row timesteps of the table build
   float* modw = nullptr;        // [L*4d, d] FiLM projections of all layers, concatenated
   float* modb = nullptr;        // [L*4d]
   float* cemb = nullptr;        // [B_max, d] conditioning embedding (mode 0)
@@ -339,6 +341,7 @@ int build_fused(tsdp_ctx* c, Net& n, const std::vector<float>& w, const std::vec
   }
   f.tok_w = n.blob + n.tok_w; f.tok_b = n.blob + n.tok_b; f.pos = n.blob + n.pos;
   f.head = P(head_off); f.head_b = n.blob + n.head_b;
+  f.modtab = nullptr;
   f.modw = P(mod_off); f.modb = n.modb; f.temb = n.temb; f.cemb = cf.cond_mode == 0 ? n.cemb : nullptr;
   if (cf.cond_mode == 1) {
     const size_t S = cf.cond_tokens, cnt = (size_t)cf.B_max * L * S * d;
@@ -420,7 +423,9 @@ void forward(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t*
     return;
   }
   const tsdp_config& cf = c->cfg;
-  if (n.fused_mod) {
+  if (n.fnet.modtab) {
+    // token conditioning: the FiLM vectors are a function of the timestep only and were tabulated at load time
+  } else if (n.fused_mod) {
     n.fused_mod(n.fnet, t_arr, t_sub, env_arr, cf.T, d_R, R_cap, c->mod, s);
   } else {                                            // fp32 networks: exact fp32 FiLM vectors from the operator kernels
     hipLaunchKernelGGL(k_gvec, grid1((long long)R_cap * n.d, 256), dim3(256), 0, s, t_arr, t_sub, env_arr, n.temb,
@@ -428,7 +433,7 @@ void forward(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t*
     linear<0>(s, c->sg, n.modw, n.modb, c->mod, R_cap, 1, n.L * 4 * n.d, n.d, d_R);
   }
   FusedIO io;
-  io.x_rows = x_rows; io.mod = c->mod; io.row_env = env_arr; io.d_R = d_R; io.R_cap = R_cap; io.eps_out = eps_out;
+  io.x_rows = x_rows; io.mod = c->mod; io.row_t = t_arr; io.t_sub = t_sub; io.T = cf.T; io.row_env = env_arr; io.d_R = d_R; io.R_cap = R_cap; io.eps_out = eps_out;
   const int stage = (&n == &c->net[0]) ? 1 : -1;          // only the base network's forward is the verify stage
   if (stage == 1) tick(c, 1, 0, s);
   const bool few = n.fused_verify_few && (R_cap + n.verify_rpt - 1) / n.verify_rpt <= 288;
@@ -648,6 +653,22 @@ int tsdp_load_weights(tsdp_ctx* c, int which, const float* h_blob, size_t nbytes
     if (find_fused(cf.dtype, n.d, cf.H, n.heads, cf.cond_mode, cf.cond_tokens, n.m / n.d, n.L, fk) &&
         (rc = build_fused(c, n, w, modw, fk)))
       return rc;
+  }
+  if (n.fused && n.fused_mod && cf.cond_mode == 1) {
+    // With token conditioning no conditioning vector enters the FiLM projections: they depend on the timestep
+    // alone, so the vectors of all T timesteps are computed once, by the kernel that otherwise computes them per row.
+    const int T = cf.T;
+    if (!n.modtab) {
+      if ((rc = dev_alloc(c, &n.modtab, (size_t)T * L * 4 * d))) return rc;
+      if ((rc = dev_alloc(c, &n.t_iota, (size_t)T))) return rc;
+      std::vector<int32_t> iota(T);
+      for (int t = 0; t < T; ++t) iota[t] = t;
+      HIPCHK(c, hipMemcpy(n.t_iota, iota.data(), sizeof(int32_t) * T, hipMemcpyHostToDevice));
+    }
+    n.fused_mod(n.fnet, n.t_iota, 0, nullptr, T, nullptr, T, n.modtab, nullptr);
+    HIPCHK(c, hipGetLastError());
+    HIPCHK(c, hipDeviceSynchronize());
+    n.fnet.modtab = n.modtab;
   }
   return TSDP_OK;
 }
