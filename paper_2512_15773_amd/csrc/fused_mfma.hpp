@@ -326,7 +326,8 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   float* red1 = reinterpret_cast<float*>(lds + C::ACT_B + C::SCR_B);
   float* red2 = red1 + NW * NT;
 
-  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index as a scalar
+  __builtin_assume(wave >= 0 && wave < NW);
   int l16 = lane & 15, lg = lane >> 4;
   // Makes the lane coordinates opaque at phase boundaries: addresses derived from them are then recomputed
   // where they are used instead of being hoisted out of the layer loop and spilled to scratch.
@@ -491,23 +492,29 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   // (it needs nothing from this phase, so it runs before the query projection) and cross_attend consumes them.
   constexpr int SFc = SF > 0 ? SF : 1;
   constexpr int KHc = KH > 0 ? KH : 1;
-  auto cross_load = [&](int r, int layer, int head, bf16x8 (&ka)[KHc][SFc], bf16x4 (&va)[DH / 16][SFc]) {
+  // keys of (row r, head) as 16x16x32 A fragments, transposed values as 16x16x16 A fragments
+  auto cross_load_k = [&](int r, int layer, int head, bf16x8 (&ka)[KHc][SFc]) {
     if constexpr (CM == 1) {
       const size_t eh = ((size_t)env_of_row[r] * net.L + layer) * HEADS + head;
       const bf16x8* kcp = net.kc + eh * (SF * (KH)) * 64 + lane;
-      const bf16x4* vcp = net.vct + eh * ((DH / 16) * SF) * 64 + lane;
 #pragma unroll
       for (int ks = 0; ks < KH; ++ks)
 #pragma unroll
         for (int kf = 0; kf < SF; ++kf) ka[ks][kf] = kcp[(kf * (KH) + ks) * 64];
+    }
+  };
+  auto cross_load_v = [&](int r, int layer, int head, bf16x4 (&va)[DH / 16][SFc]) {
+    if constexpr (CM == 1) {
+      const size_t eh = ((size_t)env_of_row[r] * net.L + layer) * HEADS + head;
+      const bf16x4* vcp = net.vct + eh * ((DH / 16) * SF) * 64 + lane;
 #pragma unroll
       for (int cf = 0; cf < DH / 16; ++cf)
 #pragma unroll
         for (int kf = 0; kf < SF; ++kf) va[cf][kf] = vcp[(cf * SF + kf) * 64];
     }
   };
-  // qp: the 16 queries of the task, row stride qs; the result overwrites them
-  auto cross_attend = [&](__bf16* qp, int qs, const bf16x8 (&ka)[KHc][SFc], const bf16x4 (&va)[DH / 16][SFc]) {
+  // qp: the 16 queries of the task, row stride qs.  scores: p = softmax over the keys of (k q^T)
+  auto cross_scores = [&](const __bf16* qp, int qs, const bf16x8 (&ka)[KHc][SFc], bf16x4 (&p)[SFc]) {
     if constexpr (CM == 1) {
       f32x4 s[SF];
 #pragma unroll
@@ -518,13 +525,15 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
 #pragma unroll
         for (int kf = 0; kf < SF; ++kf) s[kf] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[ks][kf], qb, s[kf], 0, 0, 0);
       }
-      bf16x4 p[SF];
-      {
-        vec4 pv[SF];
-        softmax_col(s, pv, std::integral_constant<int, SF>{});
+      vec4 pv[SF];
+      softmax_col(s, pv, std::integral_constant<int, SF>{});
 #pragma unroll
-        for (int kf = 0; kf < SF; ++kf) p[kf] = __builtin_bit_cast(bf16x4, pv[kf]);
-      }
+      for (int kf = 0; kf < SF; ++kf) p[kf] = __builtin_bit_cast(bf16x4, pv[kf]);
+    }
+  };
+  // the attention output p v overwrites the task's queries
+  auto cross_pv = [&](__bf16* qp, int qs, const bf16x4 (&p)[SFc], const bf16x4 (&va)[DH / 16][SFc]) {
+    if constexpr (CM == 1) {
 #pragma unroll
       for (int cf = 0; cf < DH / 16; ++cf) {
         f32x4 o = f32x4{0, 0, 0, 0};
@@ -617,7 +626,8 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
     if constexpr (CM == 1) {
       // HPX heads per phase; the queries of a phase are one token-major LDS matrix [NT][HPX*DH], so the output
       // projection contracts all its heads in one product.  Keys / values come from global memory in fragment
-      // order; a wave requests the operands of its next task before it works on the current one.
+      // order; the keys of a wave's next task are requested once the scores of the current one are formed, its
+      // values once the current values are consumed (one buffer each: double buffers would spill).
       constexpr int HPX = C::HPX, NGX = HEADS / HPX, QXS = HPX * DH + TT::PAD;
       constexpr int NTASK = RPT * HPX * NKF, TPW = (NTASK + NW - 1) / NW;
       typedef FragGemm<TT, MBH, NB, HPX * KH, BD> GOX;
@@ -629,8 +639,8 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       for (int g = 0; g < NGX; ++g) {
         TSDP_FENCE_IDS();
         GOX go;
-        bf16x8 ka[2][KHc][SFc];
-        bf16x4 va[2][DH / 16][SFc];
+        bf16x8 ka[KHc][SFc];
+        bf16x4 va[DH / 16][SFc];
         // task -> (row, head of the phase, query fragment)
         auto task_row = [&](int task) { return (task / NKF) % RPT; };
         auto task_head = [&](int task) { return task / (NKF * RPT); };
@@ -646,8 +656,6 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
           if (!XPF) gc.issue(W.cq, KD, g * (HPX * DH / 16) + wave * MBC, 0, lane);
           gc.run(act, AS, acc, lane);
           TSDP_TICK(1)
-          // the first task's keys / values travel while the queries are written and the barrier is reached
-          if (wave < NTASK) cross_load(task_row(wave), layer, g * HPX + task_head(wave), ka[0], va[0]);
           if (XPF) go.issue(W.co, KD, wave * MBH, g * HPX * KH, lane);
           if (g > 0) __syncthreads();
           TSDP_TICK(2)
@@ -659,6 +667,13 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
               *reinterpret_cast<vec4*>(qbuf + (nb * 16 + l16) * QXS + c0) = TT::cvt(acc[mb][nb] + bias[mb]);
           }
         }
+        // the first task's keys / values travel while the barrier is reached (requested only now: with the
+        // projection's accumulators still live they would not fit in registers)
+        __builtin_amdgcn_sched_barrier(0);
+        if (wave < NTASK) {
+          cross_load_k(task_row(wave), layer, g * HPX + task_head(wave), ka);
+          cross_load_v(task_row(wave), layer, g * HPX + task_head(wave), va);
+        }
         TSDP_TICK(3)
         __syncthreads();
         TSDP_TICK(2)
@@ -666,11 +681,20 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
 #pragma unroll
           for (int i = 0; i < TPW; ++i) {
             const int task = wave + i * NW;
-            if (i + 1 < TPW && task + NW < NTASK)
-              cross_load(task_row(task + NW), layer, g * HPX + task_head(task + NW), ka[(i + 1) & 1], va[(i + 1) & 1]);
-            if (task < NTASK)
-              cross_attend(reinterpret_cast<__bf16*>(qbuf) + (task_row(task) * H + (task % NKF) * 16) * QXS + task_head(task) * DH,
-                           QXS, ka[i & 1], va[i & 1]);
+            const bool more = i + 1 < TPW && task + NW < NTASK;
+            if (task < NTASK) {
+              __bf16* qp = reinterpret_cast<__bf16*>(qbuf) + (task_row(task) * H + (task % NKF) * 16) * QXS + task_head(task) * DH;
+              bf16x4 p[SFc];
+              // scheduling fences: the requests must not be moved ahead of the products that free their registers
+              cross_scores(qp, QXS, ka, p);
+              __builtin_amdgcn_sched_barrier(0);
+              if (more) cross_load_k(task_row(task + NW), layer, g * HPX + task_head(task + NW), ka);
+              __builtin_amdgcn_sched_barrier(0);
+              cross_pv(qp, QXS, p, va);
+              __builtin_amdgcn_sched_barrier(0);
+              if (more) cross_load_v(task_row(task + NW), layer, g * HPX + task_head(task + NW), va);
+              __builtin_amdgcn_sched_barrier(0);
+            }
           }
         }
         TSDP_TICK(10)

@@ -733,7 +733,8 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
   Net& dn = c->net[1];
   if (dn.fused) {
     // persistent drafter kernel: pick the tile (environments per workgroup) that fills the chip best
-    const bool big = (B + dn.draft_rpt_big - 1) / dn.draft_rpt_big >= 192;
+    bool big = (B + dn.draft_rpt_big - 1) / dn.draft_rpt_big >= 192;
+    if (const char* e = std::getenv("TSDP_DRAFT_TILE")) big = e[0] == 'b';
     const int rpt = big ? dn.draft_rpt_big : dn.draft_rpt_small;
     const size_t lds = fused_draft_lds(dn, cf, rpt);
     if (lds <= 160 * 1024) {
