@@ -271,10 +271,10 @@ struct FusedCfg {
   static constexpr int RED_B = 2 * NW * NT * 4;
   static constexpr int LDS_B = ACT_B + SCR_B + RED_B;   // body; the drafter kernel appends its own regions
   static constexpr int WG_PER_CU = LDS_B <= 80 * 1024 && NW <= 4 ? 2 : 1;
+  static constexpr int WAVES_PER_SIMD = (WG_PER_CU * NW + 3) / 4;
 #ifdef TSDP_FORCE_BD
   static constexpr int BD = TSDP_FORCE_BD;
 #else
-  static constexpr int WAVES_PER_SIMD = (WG_PER_CU * NW + 3) / 4;
   static constexpr int BD = WAVES_PER_SIMD >= 2 ? 1 : 2; // LDS operand buffers: a second wave on the SIMD hides LDS latency
 #endif
 #ifdef TSDP_FORCE_XPF
@@ -451,7 +451,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
 #pragma unroll
       for (int i = 0; i < 4; ++i) { s[kf][i] = __expf(s[kf][i] - mx); sum += s[kf][i]; }
     sum += __shfl_xor(sum, 16); sum += __shfl_xor(sum, 32);
-    const float inv = 1.0f / sum;
+    const float inv = __builtin_amdgcn_rcpf(sum);     // one approximate reciprocal (1 ulp) instead of an IEEE division
 #pragma unroll
     for (int kf = 0; kf < NK; ++kf) p[kf] = TT::cvt(s[kf] * inv);
   };
