@@ -212,6 +212,13 @@ struct FusedKernels {
   int rpt_small = 0, rpt_big = 0;
 };
 
+#ifndef TSDP_NWS128
+#define TSDP_NWS128 8      /* waves of the one-environment drafter tile, d = 128 */
+#endif
+#ifndef TSDP_NWS256X
+#define TSDP_NWS256X 8     /* waves and heads per phase of the one-environment drafter tile, d = 256 with cross-attention */
+#define TSDP_HPS256X 4
+#endif
 #ifndef TSDP_V512_HPX
 #define TSDP_V512_HPX 8    /* heads per cross-attention phase of the d = 512 verify kernel */
 #endif
@@ -221,33 +228,33 @@ struct FusedKernels {
 // shapes with compiled fused kernels
 bool find_fused(int dtype, int D, int H, int heads, int cm, int S, int mlp_ratio, int L, FusedKernels& k) {
   if (mlp_ratio != 4 || L > FUSED_MAX_LAYERS) return false;
-#define TSDP_SHAPE(TT_, DT_, D_, H_, HD_, CM_, SX_, NTV, CHV, HPV, NWV, HPXV, NTS, CHS, HPS, NTB, CHB, HPB, NWD)  \
+#define TSDP_SHAPE(TT_, DT_, D_, H_, HD_, CM_, SX_, NTV, CHV, HPV, NWV, HPXV, NTS, CHS, HPS, NWS, NTB, CHB, HPB, NWD)  \
   if (dtype == DT_ && D == D_ && H == H_ && heads == HD_ && cm == CM_ && (CM_ == 0 || S == SX_)) {             \
     k.verify = launch_verify<FusedCfg<TT_, D_, NTV, H_, HD_, CM_, CHV, SX_, HPV, NWV, HPXV>>;                  \
     k.rpt_verify = NTV / H_;                                                                                   \
     k.mod = DT_ == 1 ? launch_mod<D_> : nullptr;                                                               \
-    k.draft_small = launch_draft<FusedCfg<TT_, D_, NTS, H_, HD_, CM_, CHS, SX_, HPS, NWD>>; k.rpt_small = NTS / H_; \
+    k.draft_small = launch_draft<FusedCfg<TT_, D_, NTS, H_, HD_, CM_, CHS, SX_, HPS, NWS>>; k.rpt_small = NTS / H_; \
     k.draft_big = launch_draft<FusedCfg<TT_, D_, NTB, H_, HD_, CM_, CHB, SX_, HPB, NWD>>;   k.rpt_big = NTB / H_;   \
     return true;                                                                                               \
   }
   // The drafter's small tile (one environment per workgroup) is latency-bound: it takes all heads in one attention
   // phase and the whole MLP hidden layer in one chunk, which minimises the number of barrier-separated phases.
-  //         type dtype  D   H heads cm  S | verify: NT  CH  HP NW HPX | draft small: NT CH HP | big: NT CH HP | NW
+  //         type dtype  D   H heads cm  S | verify: NT  CH  HP NW HPX | draft small: NT CH HP NW | big: NT CH HP | NW
   if (dtype == 1 && D == 256 && H == 16 && heads == 4 && cm == 0)
     k.verify_few = launch_verify<FusedCfg<TBF16, 256, 64, 16, 4, 0, 256, 0, 2, 8>>;
   if (dtype == 1 && D == 384 && H == 16 && heads == 6 && cm == 0)
     k.verify_few = launch_verify<FusedCfg<TBF16, 384, 64, 16, 6, 0, 256, 0, 2, 8>>;
-  TSDP_SHAPE(TBF16, 1, 256, 16, 4, 0, 0, 64, 128, 1, 4, 1, 16, 128, 1, 64, 128, 1, 4)
-  TSDP_SHAPE(TBF16, 1, 384, 16, 6, 0, 0, 64, 192, 1, 4, 1, 16, 128, 1, 64, 128, 1, 4)
-  TSDP_SHAPE(TBF16, 1, 128, 16, 4, 0, 0, 128, 128, 2, 4, 2, 16, 512, 4, 64, 128, 2, 4)
-  TSDP_SHAPE(TBF16, 1, 192, 16, 6, 0, 0, 128, 128, 2, 4, 2, 16, 768, 6, 64, 128, 2, 4)
-  TSDP_SHAPE(TBF16, 1, 512, 32, 8, 1, 64, 64, TSDP_V512_CH, 2, 8, TSDP_V512_HPX, 32, 128, 1, 64, 128, 1, 4)
-  TSDP_SHAPE(TBF16, 1, 256, 32, 8, 1, 64, 64, 256, 2, 4, 2, 32, 128, 2, 64, 128, 2, 4)
+  TSDP_SHAPE(TBF16, 1, 256, 16, 4, 0, 0, 64, 128, 1, 4, 1, 16, 128, 1, 4, 64, 128, 1, 4)
+  TSDP_SHAPE(TBF16, 1, 384, 16, 6, 0, 0, 64, 192, 1, 4, 1, 16, 128, 1, 4, 64, 128, 1, 4)
+  TSDP_SHAPE(TBF16, 1, 128, 16, 4, 0, 0, 128, 128, 2, 4, 2, 16, 512, 4, TSDP_NWS128, 64, 128, 2, 4)
+  TSDP_SHAPE(TBF16, 1, 192, 16, 6, 0, 0, 128, 128, 2, 4, 2, 16, 768, 6, 4, 64, 128, 2, 4)
+  TSDP_SHAPE(TBF16, 1, 512, 32, 8, 1, 64, 64, TSDP_V512_CH, 2, 8, TSDP_V512_HPX, 32, 128, 1, 4, 64, 128, 1, 4)
+  TSDP_SHAPE(TBF16, 1, 256, 32, 8, 1, 64, 64, 256, 2, 4, 2, 32, 128, TSDP_HPS256X, TSDP_NWS256X, 64, 128, 2, 4)
   // fp32 networks on the fp32 matrix cores: one row (16 tokens) per workgroup, weights streamed per workgroup
-  TSDP_SHAPE(TF32, 0, 256, 16, 4, 0, 0, 16, 128, 1, 4, 1, 16, 128, 1, 16, 128, 1, 4)
-  TSDP_SHAPE(TF32, 0, 128, 16, 4, 0, 0, 16, 128, 2, 4, 2, 16, 512, 4, 16, 512, 4, 4)
-  TSDP_SHAPE(TF32, 0, 64, 16, 2, 0, 0, 16, 64, 2, 4, 2, 16, 64, 2, 16, 64, 2, 4)
-  TSDP_SHAPE(TF32, 0, 32, 16, 2, 0, 0, 16, 32, 2, 2, 2, 16, 128, 2, 16, 128, 2, 2)
+  TSDP_SHAPE(TF32, 0, 256, 16, 4, 0, 0, 16, 128, 1, 4, 1, 16, 128, 1, 4, 16, 128, 1, 4)
+  TSDP_SHAPE(TF32, 0, 128, 16, 4, 0, 0, 16, 128, 2, 4, 2, 16, 512, 4, TSDP_NWS128, 16, 512, 4, 4)
+  TSDP_SHAPE(TF32, 0, 64, 16, 2, 0, 0, 16, 64, 2, 4, 2, 16, 64, 2, 4, 16, 64, 2, 4)
+  TSDP_SHAPE(TF32, 0, 32, 16, 2, 0, 0, 16, 32, 2, 2, 2, 16, 128, 2, 2, 16, 128, 2, 2)
 #undef TSDP_SHAPE
   return false;
 }
@@ -436,7 +443,8 @@ void forward(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t*
   io.x_rows = x_rows; io.mod = c->mod; io.row_t = t_arr; io.t_sub = t_sub; io.T = cf.T; io.row_env = env_arr; io.d_R = d_R; io.R_cap = R_cap; io.eps_out = eps_out;
   const int stage = (&n == &c->net[0]) ? 1 : -1;          // only the base network's forward is the verify stage
   if (stage == 1) tick(c, 1, 0, s);
-  const bool few = n.fused_verify_few && (R_cap + n.verify_rpt - 1) / n.verify_rpt <= 288;
+  bool few = n.fused_verify_few && (R_cap + n.verify_rpt - 1) / n.verify_rpt <= 288;
+  if (const char* e = std::getenv("TSDP_VERIFY_FEW")) few = n.fused_verify_few && e[0] == '1';
   (few ? n.fused_verify_few : n.fused_verify)(n.fnet, io, cf.A, R_cap, s);
   if (stage == 1) tick(c, 1, 1, s);
 }
@@ -448,7 +456,7 @@ size_t fused_draft_lds(const Net& n, const tsdp_config& cf, int rpt) {
   const size_t CH = 4 * D;                                                             // compiled tile variants
   const size_t act = NT * (D + PAD) * ES, q = HP * NT * (DH + PAD) * ES, vt = HP * rpt * DH * (cf.H + 4) * ES;
   const size_t scr = std::max(std::max(2 * q + vt, NT * (CH + PAD) * ES), NT * 64 * 4);
-  return act + scr + 2 * 4 * NT * 4 + 2 * NT * cf.A * 4 + (size_t)rpt * n.L * 4 * D * 4 + 16 * (D + PAD) * ES;  // upper bound
+  return act + scr + 2 * 8 * NT * 4 + 2 * NT * cf.A * 4 + (size_t)rpt * n.L * 4 * D * 4 + 16 * (D + PAD) * ES;  // upper bound
 }
 
 // rows of the ragged batch a context must hold: K_max per environment, one more with the bonus row
