@@ -284,7 +284,7 @@ struct FusedCfg {
 #endif
   static_assert(D % (16 * NW) == 0 && NT % 16 == 0 && H % 16 == 0 && NT % H == 0 && DH % KSTEP == 0, "shape");
   static_assert(D % KSTEP == 0 && CH % KSTEP == 0, "shape");
-  static_assert((HEADS % HP) == 0 && (HP * 3 * DH) % (16 * NW) == 0 && (HPX * DH) % (16 * NW) == 0 &&
+  static_assert((HEADS % HP) == 0 && (HP * 3 * DH) % (16 * NW) == 0 && (CM == 0 || (HPX * DH) % (16 * NW) == 0) &&
                 (HEADS % HPX) == 0, "shape");
   static_assert(CH % (16 * NW) == 0 && (4 * D) % CH == 0, "shape");
   static_assert(CM == 0 || (SX % 16 == 0 && SX >= 16 && ES == 2), "cross-attention: bf16 only, tokens a multiple of 16");
