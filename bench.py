@@ -147,6 +147,45 @@ def accept_xl(torch, Tsdp, dev, iters=20):
             "algorithmic_bytes": alg, "mean_accepted_drafts": acc}
 
 
+def operating_points(ctx, wl, torch, dev, round_ms):
+    """Acceptance-dependent part of the metric at the other operating points (kernel time does not depend on the
+    data, so steps/s = steps advanced per round / the measured round latency): natural = independent random-init
+    pair; the two bounds: every draft accepted (a drafter identical to the base: K_eff steps per environment and
+    round) and every first draft rejected (one step per environment and round); then the calibrated pair with every environment at the same timestep."""
+    out = {}
+    na = torch.zeros(wl.B, dtype=torch.int32, device=dev); nd = torch.zeros_like(na)
+
+    def one_round(x, t0, K, s):
+        xd, td = torch.from_numpy(x).to(dev), torch.from_numpy(t0.astype(np.int32)).to(dev)
+        ctx.tsdp_round(xd, td, torch.from_numpy(K).to(dev), torch.from_numpy(s).to(dev), None, na, nd)
+        keff = np.minimum(K, np.maximum(t0, 0))
+        a = na.cpu().numpy()
+        tested = int(np.minimum(a + 1, keff).sum())
+        adv = int(nd.sum().item())
+        return {"steps_advanced_per_round": adv, "acceptance_of_tested_drafts": int(a.sum()) / max(tested, 1),
+                "acceptance_of_all_drafts": int(a.sum()) / max(int(keff.sum()), 1),
+                "accepted_steps_per_s": adv / (round_ms * 1e-3)}
+
+    wb, wd, cond, x, t0, K, s = make_problem(wl, "natural")
+    ctx.tsdp_load_weights(0, ti.pack_blob(wb)); ctx.tsdp_load_weights(1, ti.pack_blob(wd))
+    ctx.tsdp_set_cond(torch.from_numpy(cond).to(dev))
+    out["natural"] = one_round(x, t0, K, s)
+    keff = np.minimum(K, np.maximum(t0, 0))
+    all_acc = int(np.where(t0 >= 0, np.maximum(keff, 1), 0).sum())    # identical drafter: every draft passes
+    out["all_accept_bound"] = {"steps_advanced_per_round": all_acc, "accepted_steps_per_s": all_acc / (round_ms * 1e-3)}
+    live = int((make_problem(wl, "calibrated")[4] >= 0).sum())
+    out["all_reject_bound"] = {"steps_advanced_per_round": live, "accepted_steps_per_s": live / (round_ms * 1e-3)}
+    wb, wd, cond, x, t0, K, s = make_problem(wl, "calibrated")
+    ctx.tsdp_load_weights(0, ti.pack_blob(wb)); ctx.tsdp_load_weights(1, ti.pack_blob(wd))
+    ctx.tsdp_set_cond(torch.from_numpy(cond).to(dev))
+    sweep = {}
+    for tt in sorted({wl.T - 1, 3 * wl.T // 4, wl.T // 2, wl.T // 4, wl.K_max}, reverse=True):
+        r = one_round(x, np.full(wl.B, tt, dtype=np.int32), K, s)
+        sweep[str(tt)] = {k: r[k] for k in ("steps_advanced_per_round", "acceptance_of_tested_drafts")}
+    out["calibrated_by_start_timestep"] = sweep
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -157,6 +196,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-chain", action="store_true", help="skip the whole-chain (action prediction) measurement")
     ap.add_argument("--no-accept-xl", action="store_true", help="skip the acceptance-kernel HBM stress shape")
+    ap.add_argument("--no-points", action="store_true", help="skip the other acceptance operating points")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="end with one 1 GiB device-to-device copy (known traffic that scales rocprofv3's byte counters)")
     ap.add_argument("--cpu-envs", type=int, default=0, help="environments of the oracle sample (0 = by workload)")
@@ -290,6 +330,8 @@ def main():
     if not args.no_cpu:
         n_env = args.cpu_envs or {"C1": 1, "C2": 1, "C3": 4, "C4": 1, "C5": 4}[wl.name]
         res["cpu_baseline"] = cpu_baseline(wl, wb, wd, cond, x, t0, K, s, n_env)
+    if not args.no_points and args.point == "calibrated":
+        res["operating_points"] = operating_points(ctx, wl, torch, dev, t_round[0])
     print(json.dumps(res))
     ctx.close()
     if args.pmc_copy:
