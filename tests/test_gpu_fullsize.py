@@ -154,3 +154,48 @@ def test_round_is_deterministic_and_handles_empty_and_finished_batches():
     e = torch.zeros(0, wl.H, wl.A, device="cuda"); ei = torch.zeros(0, dtype=torch.int32, device="cuda")
     ctx.tsdp_round(e, ei, ei, torch.zeros(0, device="cuda"), None, None, None)
     ctx.close()
+
+
+def test_full_size_bonus_row_with_ddim_sampler():
+    # the K+1 candidate set and the DDIM(eta) transition together, at the full C3 size (64 envs x (16 + 1) rows)
+    wl = ti.WORKLOADS["C3"]
+    wb, wd, cond, x, t0, K, s = bench.make_problem(wl, "calibrated")
+    t0 = t0.copy(); t0[:4] = [0, 3, 16, 99]                            # base step only, t0 < K, t0 = K, chain start
+    base, drafter, sched = oracle_side(wl, wb, wd, sampler=1, eta=0.8)
+    ctx = gpu_side(wl, wb, wd, cond, sampler=1, eta=0.8, bonus_row=True)
+    B = wl.B
+    rows = ctx.alloc_rows(B)
+    sd = to_dev(s)
+    ctx.tsdp_draft(to_dev(x), to_dev(t0), to_dev(K), sd, None, rows)
+    ctx.tsdp_verify(B, rows)
+    out = ctx.tsdp_accept(B, sd, None, rows)
+    g = {k: v.cpu().numpy() for k, v in {**rows, **out}.items()}
+    K_eff, row_ptr, row_env, row_t = sr.plan_rows(t0, K, bonus=True)
+    R = int(row_ptr[-1])
+    assert R == int((K_eff + 1).sum())
+    np.testing.assert_array_equal(g["row_ptr"], row_ptr)
+    np.testing.assert_array_equal(g["row_t"][:R], row_t)
+    np.testing.assert_array_equal(g["row_env"][:R], row_env)
+    envs = np.array([0, 1, 2, 3, 40])
+    o = sr.draft(drafter, sched, x[envs], t0[envs], K[envs], s[envs], envs, wl.philox_seed, cond[envs], bonus=True)
+    for j, b in enumerate(envs):
+        gs = slice(row_ptr[b], row_ptr[b + 1]); os_ = slice(o["row_ptr"][j], o["row_ptr"][j + 1])
+        np.testing.assert_allclose(g["xi"][gs], o["xi"][os_], rtol=1e-5, atol=2e-6)
+        for nm in ("states", "eps_p"):
+            assert scaled_err(g[nm][gs], o[nm][os_]) < TOL["bf16"], (nm, int(b))
+        ref = sr.verify(base, np.full(gs.stop - gs.start, b), g["row_t"][gs], g["states"][gs], cond)
+        assert scaled_err(g["eps_q"][gs], ref) < TOL["bf16"], ("eps_q", int(b))
+    ref = sr.accept(sched, row_ptr, row_t, s, None, wl.philox_seed, g["states"][:R], g["eps_p"][:R], g["eps_q"][:R],
+                    g["xi"][:R], g["y_last"], bonus=True)
+    near = np.abs(ref["logu"] - ref["logratio"]) < 1e-5
+    diff = g["flags"][:R] != ref["flags"]
+    assert not np.any(diff & ~near)
+    ok = np.array([not np.any(diff[row_ptr[b]:row_ptr[b + 1]]) for b in range(B)])
+    for k in ("n_accept", "n_adv", "t_next"):
+        np.testing.assert_array_equal(g[k][ok], ref[k][ok])
+    np.testing.assert_allclose(g["x_out"][ok], ref["x_out"][ok], rtol=1e-5, atol=1e-6)
+    # every running environment ends its round with a corrected or an exact base step
+    live = t0 >= 0
+    assert (ref["n_adv"][live] == ref["n_accept"][live] + 1).all() and ref["n_adv"][0] == 1
+    assert (ref["n_accept"] == K_eff).any()                            # some environment took its bonus step
+    ctx.close()
