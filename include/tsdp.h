@@ -75,6 +75,9 @@ int tsdp_create(const tsdp_config* cfg, tsdp_ctx** out_ctx);
 /* Frees everything the context owns.  Synchronises the device.  NULL is allowed. */
 void tsdp_destroy(tsdp_ctx* ctx);
 
+/* Environment: TSDP_DISABLE_FUSED (any value), read by tsdp_load_weights, keeps a network on the general fp32
+ * operator kernels even where a fused kernel exists for its shape (a diagnostic; tsdp_path_name reports the path). */
+
 /* Loads one denoiser (which: 0 = base, 1 = drafter) from a HOST blob of fp32 values: the tensors
  * tok_w[d,A] tok_b[d] pos[H,d] t_w1[d,d] t_b1[d] t_w2[d,d] t_b2[d] (mode 0: c_w[d,C] c_b[d]) then per
  * layer mod_w[4d,d] mod_b[4d] qkv_w[3d,d] qkv_b[3d] o_w[d,d] o_b[d] (mode 1: cq_w[d,d] cq_b[d]

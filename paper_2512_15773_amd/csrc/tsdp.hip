@@ -443,8 +443,7 @@ void forward(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t*
   io.x_rows = x_rows; io.mod = c->mod; io.row_t = t_arr; io.t_sub = t_sub; io.T = cf.T; io.row_env = env_arr; io.d_R = d_R; io.R_cap = R_cap; io.eps_out = eps_out;
   const int stage = (&n == &c->net[0]) ? 1 : -1;          // only the base network's forward is the verify stage
   if (stage == 1) tick(c, 1, 0, s);
-  bool few = n.fused_verify_few && (R_cap + n.verify_rpt - 1) / n.verify_rpt <= 288;
-  if (const char* e = std::getenv("TSDP_VERIFY_FEW")) few = n.fused_verify_few && e[0] == '1';
+  const bool few = n.fused_verify_few && (R_cap + n.verify_rpt - 1) / n.verify_rpt <= 288;
   (few ? n.fused_verify_few : n.fused_verify)(n.fnet, io, cf.A, R_cap, s);
   if (stage == 1) tick(c, 1, 1, s);
 }
@@ -741,8 +740,7 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
   Net& dn = c->net[1];
   if (dn.fused) {
     // persistent drafter kernel: pick the tile (environments per workgroup) that fills the chip best
-    bool big = (B + dn.draft_rpt_big - 1) / dn.draft_rpt_big >= 192;
-    if (const char* e = std::getenv("TSDP_DRAFT_TILE")) big = e[0] == 'b';
+    const bool big = (B + dn.draft_rpt_big - 1) / dn.draft_rpt_big >= 192;
     const int rpt = big ? dn.draft_rpt_big : dn.draft_rpt_small;
     const size_t lds = fused_draft_lds(dn, cf, rpt);
     if (lds <= 160 * 1024) {
