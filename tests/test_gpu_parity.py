@@ -405,3 +405,17 @@ def test_staged_chain_follows_the_stage_tables():
     with _pt.raises(TsdpError):
         S["ctx"].tsdp_chain_staged(x, t, to_dev(K3.astype(np.int32)), to_dev(s3.astype(np.float32)), None, 2, 3, None)
     S["ctx"].close()
+
+
+def test_maximum_sizes_on_the_general_path():
+    # the limits of the configuration: H*A = 512 elements per latent, K_max = 64 drafts, T = 4096 timesteps
+    wl = ti.small_variant(ti.C1, B=3, H=32, A=16, T=4096, K_max=64, base=ti.NetShape(1, 96, 3), draft=ti.NetShape(1, 48, 3))
+    t0 = np.array([4095, 2000, 40]); K = np.array([64, 64, 64]); s = np.array([1.0, 1.2, 1.0])
+    g, ref = _stage_parity(wl, 3, t0, K, s, paths=("f32-ops", "f32-ops"))
+    assert (ref["n_adv"] >= 1).all() and (ref["n_adv"] <= [64, 64, 40]).all()
+    # past the limits the context is refused
+    from paper_2512_15773_amd import Tsdp, TsdpError
+    for kw in (dict(K_max=65), dict(T=4097), dict(A=17)):
+        bad = ti.small_variant(wl, **kw)
+        with pytest.raises(TsdpError):
+            Tsdp.from_workload(bad, B_max=1)
