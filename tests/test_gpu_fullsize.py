@@ -199,3 +199,45 @@ def test_full_size_bonus_row_with_ddim_sampler():
     assert (ref["n_adv"][live] == ref["n_accept"][live] + 1).all() and ref["n_adv"][0] == 1
     assert (ref["n_accept"] == K_eff).any()                            # some environment took its bonus step
     ctx.close()
+
+
+def test_speculative_chain_on_the_gpu_has_the_law_of_the_base_chain():
+    # Losslessness end to end on the device: final actions of whole chains driven by an imperfect drafter against
+    # final actions of the plain base chain (drafter = base, every draft accepted, which the identity test above
+    # ties to plain DDPM steps).  Same conditioning for all environments, independent noise seeds and initial
+    # latents for the two runs; per-dimension two-sample Kolmogorov-Smirnov tests with a Bonferroni bound.
+    from scipy import stats
+    n = 4096
+    wl = ti.small_variant(ti.C1, B=n)
+    wb = ti.make_weights(wl, "base", b_std=0.02, head_scale=1.5)
+    wd = ti.make_weights(wl, "draft", b_std=0.02, head_scale=1.5)
+    cond = np.repeat(ti.make_cond(wl, 1), n, axis=0)
+    K = to_dev(np.full(n, 4, np.int32)); s = to_dev(np.ones(n, np.float32))
+    finals = []
+    rates = []
+    for run, (wl_run, w_draft, seed) in enumerate(((wl, wd, 11), (ti.small_variant(wl, draft=wl.base), wb, 12))):
+        ctx = gpu_side(wl_run, wb, w_draft, cond, B_max=n, seed=seed)
+        x = to_dev(np.random.default_rng(100 + run).standard_normal((n, wl.H, wl.A)).astype(np.float32))
+        t = to_dev(np.full(n, wl.T - 1, np.int32))
+        rounds, tot = ctx.tsdp_chain(x, t, K, s, None, check_every=2)
+        assert (t.cpu().numpy() == -1).all()
+        finals.append(x.cpu().numpy().reshape(n, -1))
+        rates.append(tot["accept"].sum().item() / tot["drafts"].sum().item())
+        ctx.close()
+    assert 0.2 < rates[0] < 0.98 and rates[1] == 1.0                   # rejections happen in the speculative run
+    # power of the detector: the drafter's own chain (threshold rule with a vanishing threshold accepts every
+    # draft) has a visibly different law
+    ctx = gpu_side(wl, wb, wd, cond, B_max=n, seed=13)
+    x = to_dev(np.random.default_rng(102).standard_normal((n, wl.H, wl.A)).astype(np.float32))
+    t = to_dev(np.full(n, wl.T - 1, np.int32))
+    ctx.tsdp_chain(x, t, K, s, None, lam=to_dev(np.full(n, 1e-30, np.float32)), check_every=2)
+    c = x.cpu().numpy().reshape(n, -1)
+    ctx.close()
+    assert min(stats.ks_2samp(c[:, j], finals[1][:, j]).pvalue for j in range(c.shape[1])) < 1e-6
+    a, b = finals
+    D = a.shape[1]
+    pvals = np.array([stats.ks_2samp(a[:, j], b[:, j]).pvalue for j in range(D)])
+    assert pvals.min() > 1e-3 / D, pvals.min()
+    sd = np.sqrt((a.var(0) + b.var(0)) / n)
+    assert (np.abs(a.mean(0) - b.mean(0)) < 5 * sd).all()
+    assert (np.abs(a.var(0) / b.var(0) - 1) < 6 * np.sqrt(2 / n)).all()
