@@ -325,6 +325,24 @@ def main():
                         "acceptance_of_all_drafts": a / max(d, 1e-9),
                         # paper's convention: a drafter call costs (drafter blocks / base blocks) of a base call
                         "nfe_fraction_of_plain_chain": (r + d * wl.draft.layers / wl.base.layers) / wl.T}
+        # the same chain with a three-stage draft count (the scheduler's hook): one draft per round while the
+        # noise is high and acceptance is nil, the full count in the middle, half of it for the last steps
+        K3 = np.tile(np.array([1, wl.K_max, max(1, wl.K_max // 2)], dtype=np.int32), (wl.B, 1))
+        s3 = np.repeat(s.astype(np.float32)[:, None], 3, axis=1)
+        K3d, s3d = torch.from_numpy(K3).to(dev), torch.from_numpy(np.ascontiguousarray(s3)).to(dev)
+        t_hi, t_lo = 9 * wl.T // 10, min(wl.K_max, wl.T // 4)
+        xc, tc = x0d.clone(), tT.clone()
+        ctx.tsdp_chain_staged(xc, tc, K3d, s3d, None, t_hi, t_lo, None, check_every=4, totals=False)
+        xc, tc = x0d.clone(), tT.clone()
+        torch.cuda.synchronize(); tic = time.perf_counter()
+        n_rounds, tot = ctx.tsdp_chain_staged(xc, tc, K3d, s3d, None, t_hi, t_lo, None, check_every=4)
+        torch.cuda.synchronize(); el = time.perf_counter() - tic
+        a, d, r = (float(tot[k].float().mean().item()) for k in ("accept", "drafts", "rounds"))
+        res["chain_staged"] = {"K_by_stage": [1, wl.K_max, max(1, wl.K_max // 2)], "stage_bounds": [t_hi, t_lo],
+                               "rounds_enqueued": n_rounds, "seconds": el, "action_predictions_per_s": wl.B / el,
+                               "denoising_steps_per_s": wl.B * wl.T / el, "mean_rounds_per_env": r,
+                               "mean_drafts_per_env": d, "acceptance_of_all_drafts": a / max(d, 1e-9),
+                               "nfe_fraction_of_plain_chain": (r + d * wl.draft.layers / wl.base.layers) / wl.T}
     if not args.no_accept_xl:
         res["accept_roofline"] = accept_xl(torch, Tsdp, dev)
     if not args.no_cpu:
