@@ -219,6 +219,11 @@ struct FusedKernels {
 #define TSDP_NWS256X 8     /* waves and heads per phase of the one-environment drafter tile, d = 256 with cross-attention */
 #define TSDP_HPS256X 4
 #endif
+#ifndef TSDP_F256_NW
+#define TSDP_F256_NW 8     /* fp32 d = 256 verify kernel: waves, heads per phase, hidden chunk */
+#define TSDP_F256_HP 2
+#define TSDP_F256_CH 256
+#endif
 #ifndef TSDP_V512_HPX
 #define TSDP_V512_HPX 8    /* heads per cross-attention phase of the d = 512 verify kernel */
 #endif
@@ -251,7 +256,7 @@ bool find_fused(int dtype, int D, int H, int heads, int cm, int S, int mlp_ratio
   TSDP_SHAPE(TBF16, 1, 512, 32, 8, 1, 64, 64, TSDP_V512_CH, 2, 8, TSDP_V512_HPX, 32, 128, 1, 4, 64, 128, 1, 4)
   TSDP_SHAPE(TBF16, 1, 256, 32, 8, 1, 64, 64, 256, 2, 4, 2, 32, 128, TSDP_HPS256X, TSDP_NWS256X, 64, 128, 2, 4)
   // fp32 networks on the fp32 matrix cores: one row (16 tokens) per workgroup, weights streamed per workgroup
-  TSDP_SHAPE(TF32, 0, 256, 16, 4, 0, 0, 16, 128, 1, 4, 1, 16, 128, 1, 4, 16, 128, 1, 4)
+  TSDP_SHAPE(TF32, 0, 256, 16, 4, 0, 0, 16, TSDP_F256_CH, TSDP_F256_HP, TSDP_F256_NW, TSDP_F256_HP, 16, 128, 1, 4, 16, 128, 1, 4)
   TSDP_SHAPE(TF32, 0, 128, 16, 4, 0, 0, 16, 128, 2, 4, 2, 16, 512, 4, TSDP_NWS128, 16, 512, 4, 4)
   TSDP_SHAPE(TF32, 0, 64, 16, 2, 0, 0, 16, 64, 2, 4, 2, 16, 64, 2, 4, 16, 64, 2, 4)
   TSDP_SHAPE(TF32, 0, 32, 16, 2, 0, 0, 16, 32, 2, 2, 2, 16, 128, 2, 2, 16, 128, 2, 2)
