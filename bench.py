@@ -273,6 +273,21 @@ def main():
     t_accept = time_events(lambda: ctx.tsdp_accept_into(wl.B, sd, None, rows, out), n_it, torch)
     t_round = time_events(step, n_it, torch)
 
+    # the same step replayed from a captured HIP graph (a round is a fixed launch sequence: no allocation, no host
+    # synchronisation): what launch overhead costs at the small workloads
+    ctx.tsdp_kernel_timing(False)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    graph.replay()
+    t_graph = time_events(graph.replay, n_it, torch)
+
     flops = verify_flops(wl, R)
     bf16 = wl.dtype == "bf16"
     if fused:
@@ -301,6 +316,7 @@ def main():
                        "draft": {"mean": t_draft[0], "p50": t_draft[1], "p95": t_draft[2]},
                        "verify": {"mean": t_verify[0], "p50": t_verify[1], "p95": t_verify[2]},
                        "accept": {"mean": t_accept[0], "p50": t_accept[1], "p95": t_accept[2]},
+                       "round_from_hip_graph": {"mean": t_graph[0], "p50": t_graph[1], "p95": t_graph[2]},
                        "drafter_kernel": kd_ms},
         "roofline": {"kernel": kname, "bound": "mfma" if (bf16 or fused) else "alu", "achieved": achieved, "peak": peak,
                      "unit": "TFLOP/s", "frac": achieved / peak,

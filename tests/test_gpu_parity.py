@@ -419,3 +419,46 @@ def test_maximum_sizes_on_the_general_path():
         bad = ti.small_variant(wl, **kw)
         with pytest.raises(TsdpError):
             Tsdp.from_workload(bad, B_max=1)
+
+
+def test_round_replays_from_a_captured_hip_graph():
+    # a round is a fixed sequence of kernel launches on the caller's stream (no allocation after the first call, no
+    # host synchronisation, no memset node): captured once, every replay must equal the eager round it stands for
+    import torch
+    wl = ti.small_variant(ti.C1, B=5)
+    S = _setup(wl, 5, head_scale=0.6)
+    ctx = S["ctx"]
+    t0 = np.array([9, 9, 7, 5, 9], np.int32); K = to_dev(np.array([4, 2, 3, 4, 1], np.int32))
+    s = to_dev(np.array([1.0, 1.1, 1.0, 1.2, 1.0], np.float32))
+
+    def fresh():
+        return to_dev(S["x"]), to_dev(t0), torch.zeros(5, dtype=torch.int32, device="cuda"), torch.zeros(5, dtype=torch.int32, device="cuda")
+
+    # eager reference: four rounds in a row, with the state after each
+    x, t, na, nd = fresh()
+    eager = []
+    for _ in range(4):
+        ctx.tsdp_round(x, t, K, s, None, na, nd)
+        torch.cuda.synchronize()
+        eager.append((x.clone(), t.clone(), na.clone(), nd.clone()))
+    # captured: the same buffers are updated in place by every replay
+    x, t, na, nd = fresh()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        xw, tw, naw, ndw = fresh()
+        ctx.tsdp_round(xw, tw, K, s, None, naw, ndw)              # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ctx.tsdp_round(x, t, K, s, None, na, nd)
+    x.copy_(to_dev(S["x"])); t.copy_(to_dev(t0))                   # capture does not execute: start from the inputs
+    for i in range(4):
+        graph.replay()
+        torch.cuda.synchronize()
+        _ = (x * 2).sum().item()                                   # eager work and a synchronisation between replays
+        for got, want in zip((x, t, na, nd), eager[i]):
+            assert torch.equal(got, want), f"replay {i} differs from the eager round"
+    assert ctx.tsdp_status() == 0
+    ctx.close()
