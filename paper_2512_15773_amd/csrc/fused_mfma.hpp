@@ -73,6 +73,7 @@ struct DraftIO {               // drafter rollout
   int B;
   const int32_t* t0; const int32_t* K_eff; const int32_t* row_ptr; const float* sigma_scale; const int32_t* env_id;
   SchedDev tb; int clip; float clip_val; uint64_t seed;
+  int mod_cols;                // columns of one in-kernel FiLM product: a multiple of RPT up to 16 (mod_cols/RPT steps at once)
   float* y;                    // [B,H,A]  in: the latents, out: the latents after the last drafted step
   float* states; float* eps_p; float* xi;   // [R,H,A] retained per drafted transition
 };
@@ -901,8 +902,12 @@ __global__ __launch_bounds__(C::THREADS) void k_fused_draft(FusedNet net, DraftI
   const int mod_stride = net.L * 4 * D;
   float* yt = reinterpret_cast<float*>(lds + C::LDS_B);              // [NT*A] latents
   float* et = yt + NT * A;                                           // [NT*A] drafter output
-  float* modbuf = et + NT * A;                                       // [RPT][L*4D] FiLM vectors of this step
-  elem* sgbuf = reinterpret_cast<elem*>(modbuf + RPT * mod_stride);        // [16][D+pad] SiLU(g), rows >= RPT zero
+  // The FiLM product has 16 columns (one MFMA tile): column j = environment j / SPE, step offset j % SPE.  With
+  // mod_cols = 16 it yields the vectors of SPE = 16 / RPT consecutive steps at once, so the FiLM weights stream once
+  // per SPE steps; with mod_cols = RPT (when LDS is short) one step at a time.
+  const int mod_cols = io.mod_cols, SPE = mod_cols / RPT;
+  float* modbuf = et + NT * A;                                       // [mod_cols][L*4D] FiLM vectors
+  elem* sgbuf = reinterpret_cast<elem*>(modbuf + mod_cols * mod_stride);   // [16][D+pad] SiLU(g), unused rows zero
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l16 = lane & 15, lg = lane >> 4;
   const int env0 = blockIdx.x * RPT;
   if (threadIdx.x == 0) s_kmax = 0;
@@ -934,15 +939,17 @@ __global__ __launch_bounds__(C::THREADS) void k_fused_draft(FusedNet net, DraftI
         mrow[threadIdx.x] = net.modtab + (size_t)t * mod_stride;
       }
     } else {
-    if (threadIdx.x < RPT) mrow[threadIdx.x] = modbuf + threadIdx.x * mod_stride;
-    // FiLM input of this step: SiLU(temb[t_k] + cemb[env]) as bf16 rows of the mod product's B operand
-    for (int i = threadIdx.x; i < RPT * D; i += TH) {
-      const int r = i / D, c = i % D;
-      int t = s_t0[r] - k + 1;
+    const int so = (k - 1) % SPE;                       // offset of this step in the current batch of SPE steps
+    if (threadIdx.x < RPT) mrow[threadIdx.x] = modbuf + (threadIdx.x * SPE + so) * mod_stride;
+    if (so == 0) {
+    // FiLM inputs of steps k .. k+SPE-1: SiLU(temb[t] + cemb[env]) as rows of the mod product's B operand
+    for (int i = threadIdx.x; i < mod_cols * D; i += TH) {
+      const int j = i / D, c = i % D, r = j / SPE;
+      int t = s_t0[r] - (k + j % SPE) + 1;
       t = t < 0 ? 0 : t;
       float g = net.temb[(size_t)t * D + c];
       if (net.cemb) g += net.cemb[(size_t)envs[r] * D + c];
-      sgbuf[r * SGS + c] = (elem)silu_fast(g);
+      sgbuf[j * SGS + c] = (elem)silu_fast(g);
     }
     __syncthreads();
     {
@@ -955,7 +962,7 @@ __global__ __launch_bounds__(C::THREADS) void k_fused_draft(FusedNet net, DraftI
         FragGemm<TT, MBM, 1, D / TT::KSTEP> gm;
         gm.issue(net.modw, D / TT::KSTEP, wave * fpw + f, 0, lane);
         gm.run(sgbuf, SGS, acc, lane);
-        if (l16 < RPT) {
+        if (l16 < mod_cols) {
 #pragma unroll
           for (int mb = 0; mb < MBM; ++mb) {
             const int f0 = (wave * fpw + f + mb) * 16 + lg * 4;
@@ -964,6 +971,7 @@ __global__ __launch_bounds__(C::THREADS) void k_fused_draft(FusedNet net, DraftI
           }
         }
       }
+    }
     }
     }
     __syncthreads();

@@ -178,9 +178,16 @@ void launch_verify(const FusedNet& n, const FusedIO& io, int A, int R_cap, hipSt
 }
 
 template <class C>
-void launch_draft(const FusedNet& n, const DraftIO& io, int A, hipStream_t s) {
+void launch_draft(const FusedNet& n, const DraftIO& io_in, int A, hipStream_t s) {
   auto kern = k_fused_draft<C>;
-  const int lds = C::LDS_B + 2 * C::NT * A * 4 + C::RPT * n.L * 4 * C::D * 4 + 16 * (C::D + C::TT::PAD) * C::ES;
+  DraftIO io = io_in;
+  // FiLM vectors of up to 16 / RPT steps per in-kernel product, as many as LDS has room for
+  const int fixed = C::LDS_B + 2 * C::NT * A * 4 + 16 * (C::D + C::TT::PAD) * C::ES;
+  const int per_col = n.L * 4 * C::D * 4;
+  io.mod_cols = C::RPT;
+  for (int cols = 16; cols > C::RPT; cols /= 2)
+    if (cols % C::RPT == 0 && fixed + cols * per_col <= 160 * 1024) { io.mod_cols = cols; break; }
+  const int lds = fixed + io.mod_cols * per_col;
   static int attr_lds = 0;
   if (lds > attr_lds) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
