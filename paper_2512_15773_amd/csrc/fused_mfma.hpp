@@ -149,6 +149,9 @@ __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
 #ifndef TSDP_LN_PREFETCH
 #define TSDP_LN_PREFETCH 1   /* request the FiLM vectors before the LayerNorm statistics are reduced */
 #endif
+#ifndef TSDP_LN_STAGE
+#define TSDP_LN_STAGE 1      /* LayerNorm: cooperative fetch of the FiLM vectors, handed over through LDS */
+#endif
 #ifndef TSDP_PFMAX
 #define TSDP_PFMAX 4
 #endif
@@ -272,6 +275,7 @@ struct FusedCfg {
   static constexpr int RED_B = 2 * NW * NT * 4;
   static constexpr int LDS_B = ACT_B + SCR_B + RED_B;   // body; the drafter kernel appends its own regions
   static constexpr int WG_PER_CU = LDS_B <= 80 * 1024 && NW <= 4 ? 2 : 1;
+  static constexpr bool LN_STAGE = true;                // FiLM vectors come from global memory: fetch them cooperatively
   static constexpr int WAVES_PER_SIMD = (WG_PER_CU * NW + 3) / 4;
 #ifdef TSDP_FORCE_BD
   static constexpr int BD = TSDP_FORCE_BD;
@@ -299,6 +303,7 @@ struct DraftCfg : Base {
 #define TSDP_DRAFT_XPF 1
 #endif
   static constexpr bool XPF = TSDP_DRAFT_XPF;
+  static constexpr bool LN_STAGE = false;               // the drafter's FiLM vectors are already in LDS (or a small table)
   static constexpr int BD = TSDP_DRAFT_XPF ? 2 : Base::BD;
 };
 
@@ -391,6 +396,23 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
           fb[mb][r] = *reinterpret_cast<const f32x4*>(mp + D);
         }
     }
+    // Otherwise the wave fetches its block [row][g|b][its features] cooperatively, 16 distinct bytes per lane and
+    // request (read fragment by fragment every lane would re-read what 15 others read, in MBH dependent batches),
+    // and passes it to its lanes through the scratch region, which is free between the two barriers below.
+    constexpr bool LNST = !LNPF && TSDP_LN_STAGE && C::LN_STAGE && (NW * RPT * 2 * MBH * 16 * 4 <= C::SCR_B);
+    constexpr int CHK = RPT * 2 * MBH * 4, CPL = (CHK + 63) / 64;
+    f32x4 st[LNST ? CPL : 1];
+    if (LNST && which >= 0) {
+#pragma unroll
+      for (int i = 0; i < CPL; ++i) {
+        const int c = lane + 64 * i;
+        if (c < CHK) {
+          const int r = c / (2 * MBH * 4), rem = c % (2 * MBH * 4);
+          st[i] = *reinterpret_cast<const f32x4*>(mrow[r] + layer * 4 * D + which * D + (rem / (MBH * 4)) * D +
+                                                  (wave * MBH + (rem / 4) % MBH) * 16 + (rem % 4) * 4);
+        }
+      }
+    }
     float mean[NB], rstd[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
@@ -413,6 +435,17 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       mean[nb] = s * (1.0f / D);
       rstd[nb] = rsqrtf(fmaxf(q * (1.0f / D) - mean[nb] * mean[nb], 0.0f) + 1e-5f);
     }
+    float* fs = reinterpret_cast<float*>(lds + C::ACT_B) + wave * (CHK * 4);   // this wave's staged FiLM block
+    if (LNST && which >= 0) {
+#pragma unroll
+      for (int i = 0; i < CPL; ++i) {
+        const int c = lane + 64 * i;
+        if (c < CHK) *reinterpret_cast<f32x4*>(fs + c * 4) = st[i];
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();                  // written and read by the same wave: LDS keeps its order
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
 #pragma unroll
     for (int mb = 0; mb < MBH; ++mb) {
       const int f0 = (wave * MBH + mb) * 16 + lg * 4;
@@ -422,6 +455,11 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         if (which >= 0) {
           if (LNPF) {
             v = v * (1.0f + fg[mb][(nb * 16) / H]) + fb[mb][(nb * 16) / H];
+          } else if (LNST) {
+            const int r = (nb * 16) / H;
+            const f32x4 g = *reinterpret_cast<const f32x4*>(fs + ((r * 2 + 0) * MBH + mb) * 16 + lg * 4);
+            const f32x4 b = *reinterpret_cast<const f32x4*>(fs + ((r * 2 + 1) * MBH + mb) * 16 + lg * 4);
+            v = v * (1.0f + g) + b;
           } else {
             const float* mp = mrow[(nb * 16) / H] + layer * 4 * D + which * D + f0;
             const f32x4 g = *reinterpret_cast<const f32x4*>(mp);
@@ -431,7 +469,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         }
         *reinterpret_cast<vec4*>(act + (nb * 16 + l16) * AS + f0) = TT::cvt(v);
       }
-      if (!LNPF) __builtin_amdgcn_sched_barrier(0);   // keep the FiLM loads of one fragment row in flight, not all
+      if (!LNPF && !LNST) __builtin_amdgcn_sched_barrier(0);   // keep the FiLM loads of one fragment row in flight, not all
     }
     __syncthreads();
   };
