@@ -231,6 +231,9 @@ struct FusedKernels {
 #define TSDP_F256_HP 2
 #define TSDP_F256_CH 256
 #endif
+#ifndef TSDP_FEW_TILES
+#define TSDP_FEW_TILES 288 /* up to this many tiles the 8-wave verify variant (one workgroup per CU) is used */
+#endif
 #ifndef TSDP_V512_HPX
 #define TSDP_V512_HPX 8    /* heads per cross-attention phase of the d = 512 verify kernel */
 #endif
@@ -455,7 +458,7 @@ void forward(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t*
   io.x_rows = x_rows; io.mod = c->mod; io.row_t = t_arr; io.t_sub = t_sub; io.T = cf.T; io.row_env = env_arr; io.d_R = d_R; io.R_cap = R_cap; io.eps_out = eps_out;
   const int stage = (&n == &c->net[0]) ? 1 : -1;          // only the base network's forward is the verify stage
   if (stage == 1) tick(c, 1, 0, s);
-  const bool few = n.fused_verify_few && (R_cap + n.verify_rpt - 1) / n.verify_rpt <= 288;
+  const bool few = n.fused_verify_few && (R_cap + n.verify_rpt - 1) / n.verify_rpt <= TSDP_FEW_TILES;
   (few ? n.fused_verify_few : n.fused_verify)(n.fnet, io, cf.A, R_cap, s);
   if (stage == 1) tick(c, 1, 1, s);
 }
