@@ -94,7 +94,8 @@ int tsdp_set_cond(tsdp_ctx* ctx, const float* d_cond, int B, void* stream);
 
 /* Drafter rollout (Section 3.2, Draft Generation Procedure).
  * in : d_x[B,H,A], d_t0[B], d_K[B] (clamped to 1..K_max, to 0..K_max with bonus_row; status bit 0 reports it),
- *      d_sigma_scale[B],
+ *      d_sigma_scale[B] (the scheduler's multiplier of sigma_t, must be > 0: it divides the mean difference in the
+ *      acceptance ratio; values are not checked on the device),
  *      d_env_id[B] global environment index used as Philox counter word (NULL = 0..B-1)
  * out: d_row_ptr[B+1], d_row_t[R_cap], d_row_env[R_cap], d_states[R_cap,H,A], d_eps_p[R_cap,H,A],
  *      d_xi[R_cap,H,A], d_y_last[B,H,A] (the latent after the last drafted step; x itself if no step
