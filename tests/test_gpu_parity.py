@@ -462,3 +462,31 @@ def test_round_replays_from_a_captured_hip_graph():
             assert torch.equal(got, want), f"replay {i} differs from the eager round"
     assert ctx.tsdp_status() == 0
     ctx.close()
+
+
+def test_round_does_not_depend_on_batch_composition():
+    # sharding invariance: with global environment ids as Philox counters, an environment's round is bit-identical
+    # whatever batch (order, neighbours, size) it is computed in
+    import torch
+    wl = ti.small_variant(ti.C3, B=12)
+    S = _setup(wl, 12, head_scale=0.3)
+    ctx = S["ctx"]
+    rng = np.random.default_rng(5)
+    t0 = rng.integers(0, 100, 12).astype(np.int32); K = rng.integers(1, 17, 12).astype(np.int32)
+    s = rng.uniform(1, 1.5, 12).astype(np.float32); env = (np.arange(12) + 500).astype(np.int32)
+
+    def run(idx):
+        ctx.tsdp_set_cond(to_dev(S["cond"][idx]))
+        x = to_dev(np.asarray(S["x"])[idx]); t = to_dev(t0[idx])
+        na = torch.zeros(len(idx), dtype=torch.int32, device="cuda"); nd = torch.zeros_like(na)
+        ctx.tsdp_round(x, t, to_dev(K[idx]), to_dev(s[idx]), to_dev(env[idx]), na, nd)
+        return x.cpu().numpy(), t.cpu().numpy(), na.cpu().numpy()
+
+    full = run(np.arange(12))
+    perm = rng.permutation(12)
+    shuffled = run(perm)
+    part = run(np.array([7, 2, 9]))
+    for got, idx in ((shuffled, perm), (part, np.array([7, 2, 9]))):
+        for a, b in zip(got, full):
+            np.testing.assert_array_equal(a, b[idx])
+    ctx.close()
