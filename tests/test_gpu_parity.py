@@ -490,3 +490,23 @@ def test_round_does_not_depend_on_batch_composition():
         for a, b in zip(got, full):
             np.testing.assert_array_equal(a, b[idx])
     ctx.close()
+    # also across the drafter's tile variants: 800 environments take the four-environment tile, 5 the single one
+    wl = ti.small_variant(ti.C5, B=800, base=ti.NetShape(1, 384, 6))
+    wb = ti.make_weights(wl, "base", head_scale=0.3); wd = ti.make_weights(wl, "draft", head_scale=0.3)
+    cond = ti.make_cond(wl, 800); x0 = np.asarray(ti.make_latents(wl, 800))
+    t0, K, s = ti.make_schedule_inputs(wl, 800)
+    env = np.arange(800, dtype=np.int32)
+    ctx = gpu_side(wl, wb, wd, cond, B_max=800)
+
+    def run5(idx):
+        ctx.tsdp_set_cond(to_dev(cond[idx]))
+        x = to_dev(x0[idx]); t = to_dev(t0[idx].astype(np.int32))
+        na = torch.zeros(len(idx), dtype=torch.int32, device="cuda")
+        ctx.tsdp_round(x, t, to_dev(K[idx].astype(np.int32)), to_dev(s[idx].astype(np.float32)), to_dev(env[idx]), na, None)
+        return x.cpu().numpy(), t.cpu().numpy(), na.cpu().numpy()
+
+    full = run5(np.arange(800))
+    idx = np.array([3, 250, 251, 600, 799])
+    for a, b in zip(run5(idx), full):
+        np.testing.assert_array_equal(a, b[idx])
+    ctx.close()
