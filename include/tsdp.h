@@ -98,7 +98,8 @@ int tsdp_set_cond(tsdp_ctx* ctx, const float* d_cond, int B, void* stream);
  *      acceptance ratio; values are not checked on the device),
  *      d_env_id[B] global environment index used as Philox counter word (NULL = 0..B-1)
  * out: d_row_ptr[B+1], d_row_t[R_cap], d_row_env[R_cap], d_states[R_cap,H,A], d_eps_p[R_cap,H,A],
- *      d_xi[R_cap,H,A], d_y_last[B,H,A] (the latent after the last drafted step; x itself if no step
+ *      d_xi[R_cap,H,A] (NULL = do not store the noise: tsdp_accept can regenerate it from the Philox counters),
+ *      d_y_last[B,H,A] (the latent after the last drafted step; x itself if no step
  *      was drafted).  R_cap = B*(K_max + bonus_row) rows must be allocated; rows beyond row_ptr[B] are not
  *      written.  Rows of environment b: K_eff = min(K, t0) drafted rows at timesteps t0, t0-1, ...; an environment
  *      at t0 = 0 has the lone row (x, t = 0) of its deterministic base step; with bonus_row every running
@@ -121,6 +122,8 @@ int tsdp_verify(tsdp_ctx* ctx, int B, int R_cap, const int32_t* d_row_ptr, const
  * per row d = (mu_p - mu_q)/(s sigma_t), log alpha = -|d|^2/2 - <d,xi>; accepted iff
  * log U_{env,t} <= log alpha; first rejection j*; the output latent is y_{K_eff} if all drafts pass,
  * else the reflection of draft j*; t_next = t0 - (steps advanced).  Arithmetic is fp64 on fp32 data.
+ * d_xi = NULL: the noise of every row is regenerated in the kernel from (seed, d_env_id, timestep), the same Philox
+ * blocks tsdp_draft drew (one third fewer bytes read; tsdp_accept_threshold has no environment ids and needs d_xi).
  * A base row (the lone row at t0 = 0; the last row of every environment with bonus_row) is not tested: when no
  * draft before it was rejected the output is mu_q(state, eps_q) + s sigma_t xi of that row, one more step.
  * out: d_x_out[B,H,A], d_t_next[B], d_n_accept[B]; optional (NULL to skip): d_n_adv[B],

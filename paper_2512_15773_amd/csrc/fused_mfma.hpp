@@ -1040,7 +1040,7 @@ __global__ __launch_bounds__(C::THREADS) void k_fused_draft(FusedNet net, DraftI
       }
       *reinterpret_cast<f32x4*>(io.states + row * DE + 4 * blk) = yv;
       *reinterpret_cast<f32x4*>(io.eps_p + row * DE + 4 * blk) = ev;
-      *reinterpret_cast<f32x4*>(io.xi + row * DE + 4 * blk) = z;
+      if (io.xi) *reinterpret_cast<f32x4*>(io.xi + row * DE + 4 * blk) = z;
       *reinterpret_cast<f32x4*>(yp) = o;
     }
     __syncthreads();

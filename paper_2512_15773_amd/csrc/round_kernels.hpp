@@ -66,7 +66,7 @@ __global__ void k_rows(const float* __restrict__ x, const int32_t* __restrict__ 
     if (t == 0) {
       states[(long long)r0 * D + e] = v;
       eps_p[(long long)r0 * D + e] = 0.0f;
-      xi[(long long)r0 * D + e] = 0.0f;
+      if (xi) xi[(long long)r0 * D + e] = 0.0f;
     }
   }
 }
@@ -104,7 +104,7 @@ __global__ void k_draft_step(int k, const float* __restrict__ eps, const int32_t
   }
   *reinterpret_cast<float4*>(states + row * D + 4 * blk) = yv;
   *reinterpret_cast<float4*>(eps_p + row * D + 4 * blk) = ev;
-  *reinterpret_cast<float4*>(xi + row * D + 4 * blk) = z;
+  if (xi) *reinterpret_cast<float4*>(xi + row * D + 4 * blk) = z;
   *reinterpret_cast<float4*>(y + (long long)b * D + 4 * blk) = make_float4(o[0], o[1], o[2], o[3]);
 }
 
@@ -127,7 +127,7 @@ __global__ void k_bonus_rows(const int32_t* __restrict__ t0, const int32_t* __re
     const float4 z = t > 0 ? xi_block(seed, env, t, blk) : make_float4(0.f, 0.f, 0.f, 0.f);
     *reinterpret_cast<float4*>(states + row * D + 4 * blk) = *reinterpret_cast<const float4*>(y + (long long)b * D + 4 * blk);
     *reinterpret_cast<float4*>(eps_p + row * D + 4 * blk) = make_float4(0.f, 0.f, 0.f, 0.f);
-    *reinterpret_cast<float4*>(xi + row * D + 4 * blk) = z;
+    if (xi) *reinterpret_cast<float4*>(xi + row * D + 4 * blk) = z;
   }
 }
 
@@ -160,7 +160,8 @@ __device__ __forceinline__ double group16_sum(double v) {
 // Acceptance: one wavefront per environment, four rows at a time (one row per group of 16 lanes).  Each
 // group streams eps_p, eps_q, xi (and the state when x0 is clamped) of its row with 16-byte loads, reduces
 // |d|^2 and <d,xi> in fp64 and tests log U <= log alpha; the wave keeps the first rejection and finally
-// writes the committed or the reflected latent.  All loads of a row are issued before the first use.
+// writes the committed or the reflected latent.  All loads of a row are issued before the first use.  xi may be
+// null: the noise of a row is then regenerated from its Philox counters (seed, environment, timestep).
 template <bool CLIP, int MAXI>
 __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __restrict__ row_ptr,
                                                 const int32_t* __restrict__ row_t, const int32_t* __restrict__ env_id,
@@ -214,11 +215,17 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
     for (int it = 0; it < MAXI; ++it) {
       const int i = gl + 16 * it;
       if (i < nb) {
-        p[it] = ep[i]; q[it] = eq[i]; z[it] = zz[i];
+        p[it] = ep[i]; q[it] = eq[i];
+        if (xi) z[it] = zz[i];
         if (CLIP) y[it] = st[i];
       }
     }
     const int t = row_t[rr];
+    if (!xi) {                                      // no stored noise: the same Philox blocks the drafter drew
+#pragma unroll
+      for (int it = 0; it < MAXI; ++it)
+        if (gl + 16 * it < nb) z[it] = xi_block(seed, env, t, gl + 16 * it);
+    }
     const double sa = tb.sqrt_abar[t], s1 = tb.sqrt_1m[t], c0 = tb.c0[t], ce = tb.ce[t], sig = s * (double)tb.sigma[t];
     // stochastic test: log U;  threshold rule p = min(1, alpha) >= lambda  <=>  log alpha >= log lambda (lambda <= 1)
     const double lu = lambda ? log((double)lambda[b]) : log((double)accept_uniform(seed, env, t));
@@ -277,7 +284,7 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
             const float4* st2 = reinterpret_cast<const float4*>(states + (long long)q2 * D);
             double dd2 = 0.0, dx2 = 0.0;
             for (int i = gl; i < nb; i += 16) {
-              const float4 a4 = ep2[i], b4 = eq2[i], c4 = zz2[i];
+              const float4 a4 = ep2[i], b4 = eq2[i], c4 = xi ? zz2[i] : xi_block(seed, env, t2, i);
               const float pp[4] = {a4.x, a4.y, a4.z, a4.w}, qq[4] = {b4.x, b4.y, b4.z, b4.w}, zv[4] = {c4.x, c4.y, c4.z, c4.w};
               float yy[4] = {0, 0, 0, 0};
               if (CLIP) { const float4 y4 = st2[i]; yy[0] = y4.x; yy[1] = y4.y; yy[2] = y4.z; yy[3] = y4.w; }
@@ -319,7 +326,7 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
     const float4* zz = reinterpret_cast<const float4*>(xi + (long long)rd * D);
     for (int i = lane; i < nb; i += 64) {
       const float4 y = st[i], e = eq[i];
-      const float4 z = t > 0 ? zz[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+      const float4 z = t > 0 ? (xi ? zz[i] : xi_block(seed, env, t, i)) : make_float4(0.f, 0.f, 0.f, 0.f);
       const float yy[4] = {y.x, y.y, y.z, y.w}, ee[4] = {e.x, e.y, e.z, e.w}, zv[4] = {z.x, z.y, z.z, z.w};
       float o[4];
 #pragma unroll
@@ -350,7 +357,7 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
     const float4* zz = reinterpret_cast<const float4*>(xi + (long long)r * D);
     const float4* st = reinterpret_cast<const float4*>(states + (long long)r * D);
     for (int i = lane; i < nb; i += 64) {
-      const float4 p = ep[i], q = eq[i], z = zz[i], y = st[i];
+      const float4 p = ep[i], q = eq[i], z = xi ? zz[i] : xi_block(seed, env, t, i), y = st[i];
       const float pp[4] = {p.x, p.y, p.z, p.w}, qq[4] = {q.x, q.y, q.z, q.w}, zv[4] = {z.x, z.y, z.z, z.w},
                   yy[4] = {y.x, y.y, y.z, y.w};
       float o[4];

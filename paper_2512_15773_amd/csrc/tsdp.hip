@@ -736,7 +736,7 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
   if (rc) return rc;
   if (B == 0) return TSDP_OK;                        // an empty batch is valid and touches nothing
   if (!d_x || !d_t0 || !d_K || !d_sigma_scale || !d_row_ptr || !d_row_t || !d_row_env || !d_states || !d_eps_p ||
-      !d_xi || !d_y_last)
+      !d_y_last)
     return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_draft");
   if (B == 0) return TSDP_OK;
   if ((rc = ensure_workspace(c))) return rc;
@@ -809,7 +809,7 @@ static int accept_impl(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32
   int rc = check_ready(c, B, false);
   if (rc) return rc;
   if (B == 0) return TSDP_OK;
-  if (!d_row_ptr || !d_row_t || !d_sigma_scale || !d_states || !d_eps_p || !d_eps_q || !d_xi || !d_y_last || !d_x_out ||
+  if (!d_row_ptr || !d_row_t || !d_sigma_scale || !d_states || !d_eps_p || !d_eps_q || !d_y_last || !d_x_out ||
       !d_t_next || !d_n_accept)
     return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_accept");
   if (B == 0) return TSDP_OK;
@@ -851,6 +851,7 @@ int tsdp_accept_threshold(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const in
                           int32_t* d_t_next, int32_t* d_n_accept, int32_t* d_n_adv, uint8_t* d_flags, float* d_logratio,
                           void* stream) {
   if (c && B > 0 && !d_lambda) return fail(c, TSDP_E_INVAL, "d_lambda is null");
+  if (c && B > 0 && !d_xi) return fail(c, TSDP_E_INVAL, "d_xi is null (no environment ids here to regenerate the noise from)");
   return accept_impl(c, B, d_row_ptr, d_row_t, nullptr, d_sigma_scale, d_lambda, d_states, d_eps_p, d_eps_q, d_xi, d_y_last,
                      d_x_out, d_t_next, d_n_accept, d_n_adv, d_flags, d_logratio, nullptr, stream);
 }

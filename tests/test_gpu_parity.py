@@ -510,3 +510,27 @@ def test_round_does_not_depend_on_batch_composition():
     for a, b in zip(run5(idx), full):
         np.testing.assert_array_equal(a, b[idx])
     ctx.close()
+
+
+def test_acceptance_with_regenerated_noise_matches_stored_noise():
+    # d_xi = NULL in tsdp_draft / tsdp_accept: the kernel redraws the Philox blocks of every row
+    wl = ti.small_variant(ti.C1, B=8)
+    t0 = np.array([9, 0, -1, 2, 5, 7, 1, 9]); K = np.array([4, 4, 4, 4, 1, 1, 3, 2])
+    s = np.array([1.0, 1.0, 1.0, 1.3, 1.0, 1.5, 1.2, 1.1]); env = np.array([5, 900, 3, 77, 1, 0, 12345678, 42])
+    for clip, bonus in ((None, False), (1.0, False), (None, True)):
+        S = _setup(wl, 8, clip=clip, bonus=bonus)
+        ctx = S["ctx"]
+        rows = _gpu_draft(S, t0, K, s, env)
+        ctx.tsdp_verify(8, rows)
+        sd, ed = to_dev(s.astype(np.float32)), to_dev(env.astype(np.int32))
+        stored = {k: v.cpu().numpy() for k, v in ctx.tsdp_accept(8, sd, ed, rows).items()}
+        rows_nx = dict(rows); rows_nx["xi"] = None
+        redrawn = {k: v.cpu().numpy() for k, v in ctx.tsdp_accept(8, sd, ed, rows_nx).items()}
+        for k in ("flags", "n_accept", "n_adv", "t_next", "logratio", "logu", "x_out"):
+            np.testing.assert_array_equal(redrawn[k], stored[k])     # the same fp32 noise, bit for bit
+        # and a rollout that never stored the noise leaves the other outputs unchanged
+        rows2 = ctx.alloc_rows(8); rows2["xi"] = None
+        ctx.tsdp_draft(to_dev(S["x"]), to_dev(t0.astype(np.int32)), to_dev(K.astype(np.int32)), sd, ed, rows2)
+        for k in ("row_ptr", "states", "eps_p", "y_last"):
+            np.testing.assert_array_equal(rows2[k].cpu().numpy(), rows[k].cpu().numpy())
+        ctx.close()
