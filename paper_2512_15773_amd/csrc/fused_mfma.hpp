@@ -1,6 +1,6 @@
-// Fused bf16 MFMA forward of the denoiser: one workgroup carries a tile of NT tokens (NT/H rows)
-// through ALL layers without leaving the compute unit.  The fp32 residual stream lives in MFMA
-// accumulator registers, bf16 activations are staged in LDS, and the weights stream from L2 straight
+// Fused MFMA forward of the denoiser (bf16 or fp32 operands, chosen by an element-type trait): one workgroup
+// carries a tile of NT tokens (NT/H rows) through ALL layers without leaving the compute unit.  The fp32 residual
+// stream lives in MFMA accumulator registers, activations are staged in LDS, and the weights stream from L2 straight
 // into registers in a fragment order prepared at load time.  Every product is computed transposed
 // (output features on the MFMA M axis, tokens on the N axis), so that an accumulator holds four
 // consecutive features of one token and can be stored to LDS as one 8-byte bf16 vector.
@@ -527,8 +527,8 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   };
 
   // Cross-attention of query fragment qf of (row, head) over the SX observation tokens of the row's environment.
-  // Keys and transposed values come from global memory already in MFMA fragment order; cross_load requests them
-  // (it needs nothing from this phase, so it runs before the query projection) and cross_attend consumes them.
+  // Keys and transposed values come from global memory already in MFMA fragment order: cross_load_k / cross_load_v
+  // request them, cross_scores and cross_pv consume them.
   constexpr int SFc = SF > 0 ? SF : 1;
   constexpr int KHc = KH > 0 ? KH : 1;
   // keys of (row r, head) as 16x16x32 A fragments, transposed values as 16x16x16 A fragments
