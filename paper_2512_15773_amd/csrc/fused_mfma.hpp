@@ -152,6 +152,9 @@ __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
 #ifndef TSDP_LN_STAGE
 #define TSDP_LN_STAGE 1      /* LayerNorm: cooperative fetch of the FiLM vectors, handed over through LDS */
 #endif
+#ifndef TSDP_XHEADMAJOR
+#define TSDP_XHEADMAJOR 1
+#endif
 #ifndef TSDP_PFMAX
 #define TSDP_PFMAX 4
 #endif
@@ -680,9 +683,20 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         GOX go;
         bf16x8 ka[KHc][SFc];
         bf16x4 va[DH / 16][SFc];
-        // task -> (row, head of the phase, query fragment)
+        // Task i of a wave -> (row, head of the phase, query fragment).  When the heads of a phase divide evenly over
+        // the waves, a wave takes whole heads: the tasks of one head (its rows and query fragments) share the keys /
+        // values as long as their rows belong to the same environment, so they are fetched once, not once per task.
+        constexpr bool HEADMAJOR = TSDP_XHEADMAJOR && (HPX % NW == 0);
+        constexpr int TPH = RPT * NKF;                  // tasks per head
+        auto task_of = [&](int i) { return HEADMAJOR ? ((wave + (i / TPH) * NW) * TPH + i % TPH) : wave + i * NW; };
         auto task_row = [&](int task) { return (task / NKF) % RPT; };
         auto task_head = [&](int task) { return task / (NKF * RPT); };
+        // does task i need operands other than those of task i-1?
+        auto task_reload = [&](int i) {
+          if (!HEADMAJOR || i % TPH == 0) return true;
+          if (i % NKF != 0) return false;               // same row, next query fragment
+          return env_of_row[task_row(task_of(i))] != env_of_row[task_row(task_of(i - 1))];
+        };
         {
           f32x4 acc[MBC][NB];
           f32x4 bias[MBC];
@@ -709,9 +723,9 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         // the first task's keys / values travel while the barrier is reached (requested only now: with the
         // projection's accumulators still live they would not fit in registers)
         __builtin_amdgcn_sched_barrier(0);
-        if (wave < NTASK) {
-          cross_load_k(task_row(wave), layer, g * HPX + task_head(wave), ka);
-          cross_load_v(task_row(wave), layer, g * HPX + task_head(wave), va);
+        if (task_of(0) < NTASK) {
+          cross_load_k(task_row(task_of(0)), layer, g * HPX + task_head(task_of(0)), ka);
+          cross_load_v(task_row(task_of(0)), layer, g * HPX + task_head(task_of(0)), va);
         }
         TSDP_TICK(3)
         __syncthreads();
@@ -719,19 +733,19 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         if (!(TSDP_ABL & 8)) {
 #pragma unroll
           for (int i = 0; i < TPW; ++i) {
-            const int task = wave + i * NW;
-            const bool more = i + 1 < TPW && task + NW < NTASK;
+            const int task = task_of(i), nxt = task_of(i + 1);
+            const bool more = i + 1 < TPW && nxt < NTASK && task_reload(i + 1);
             if (task < NTASK) {
               __bf16* qp = reinterpret_cast<__bf16*>(qbuf) + (task_row(task) * H + (task % NKF) * 16) * QXS + task_head(task) * DH;
               bf16x4 p[SFc];
               // scheduling fences: the requests must not be moved ahead of the products that free their registers
               cross_scores(qp, QXS, ka, p);
               __builtin_amdgcn_sched_barrier(0);
-              if (more) cross_load_k(task_row(task + NW), layer, g * HPX + task_head(task + NW), ka);
+              if (more) cross_load_k(task_row(nxt), layer, g * HPX + task_head(nxt), ka);
               __builtin_amdgcn_sched_barrier(0);
               cross_pv(qp, QXS, p, va);
               __builtin_amdgcn_sched_barrier(0);
-              if (more) cross_load_v(task_row(task + NW), layer, g * HPX + task_head(task + NW), va);
+              if (more) cross_load_v(task_row(nxt), layer, g * HPX + task_head(nxt), va);
               __builtin_amdgcn_sched_barrier(0);
             }
           }
