@@ -38,6 +38,11 @@ def layer_norm(h, eps=1e-5):
     return (h - mu) / np.sqrt(var + eps)
 
 
+def rms_norm(h, eps=1e-5):
+    """x / sqrt(mean(x^2) + eps), no affine parameters (the configurable alternative to layer_norm)."""
+    return h / np.sqrt((h ** 2).mean(axis=-1, keepdims=True) + eps)
+
+
 def silu(x):
     return x / (1.0 + np.exp(-x))
 
@@ -74,10 +79,11 @@ def sinusoid(t, d):
 class Denoiser:
     """eps = M(x; t, cond) for a batch of independent rows."""
 
-    def __init__(self, weights, layers, heads, cond_mode, bf16=False):
+    def __init__(self, weights, layers, heads, cond_mode, bf16=False, norm=0):
         cvt = (lambda a: round_bf16(a).astype(np.float64)) if bf16 else (lambda a: np.asarray(a, np.float64))
         self.w = {k: cvt(v) for k, v in weights.items()}
         self.layers, self.heads, self.cond_mode = layers, heads, cond_mode
+        self.norm = rms_norm if norm == 1 else layer_norm        # 0 = LayerNorm, 1 = RMSNorm
         self.d = self.w["tok_w"].shape[0]
 
     def __call__(self, x, t, cond):
@@ -93,12 +99,12 @@ class Denoiser:
         for l in range(self.layers):
             p = f"l{l}."
             g1, b1, g2, b2 = np.split(lin(sg, p + "mod"), 4, axis=-1)
-            a = layer_norm(h) * (1.0 + g1[:, None, :]) + b1[:, None, :]
+            a = self.norm(h) * (1.0 + g1[:, None, :]) + b1[:, None, :]
             q, k, v = np.split(lin(a, p + "qkv"), 3, axis=-1)
             h = h + lin(attention(q, k, v, self.heads), p + "o")
             if self.cond_mode == 1:
-                qc = lin(layer_norm(h), p + "cq")
+                qc = lin(self.norm(h), p + "cq")
                 h = h + lin(attention(qc, lin(cond, p + "ck"), lin(cond, p + "cv"), self.heads), p + "co")
-            a = layer_norm(h) * (1.0 + g2[:, None, :]) + b2[:, None, :]
+            a = self.norm(h) * (1.0 + g2[:, None, :]) + b2[:, None, :]
             h = h + lin(gelu_tanh(lin(a, p + "up")), p + "dn")
-        return lin(layer_norm(h), "head")
+        return lin(self.norm(h), "head")

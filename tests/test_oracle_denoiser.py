@@ -16,6 +16,7 @@ def test_blocks_against_torch():
     rng = np.random.default_rng(0)
     h = rng.standard_normal((3, 16, 64))
     np.testing.assert_allclose(dn.layer_norm(h), F.layer_norm(_t(h), (64,), eps=1e-5).numpy(), rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(dn.rms_norm(h), F.rms_norm(_t(h), (64,), eps=1e-5).numpy(), rtol=1e-11, atol=1e-12)
     np.testing.assert_allclose(dn.gelu_tanh(h), F.gelu(_t(h), approximate="tanh").numpy(), rtol=1e-11, atol=1e-13)
     np.testing.assert_allclose(dn.silu(h), F.silu(_t(h)).numpy(), rtol=1e-12, atol=1e-13)
     np.testing.assert_allclose(dn.softmax(h), F.softmax(_t(h), dim=-1).numpy(), rtol=1e-12)
@@ -35,13 +36,13 @@ def test_sinusoid_layout():
     np.testing.assert_allclose(e[2], np.concatenate([np.sin(37 * f), np.cos(37 * f)]), rtol=1e-12)
 
 
-def _torch_forward(w, net, cond_mode, x, t, cond):
+def _torch_forward(w, net, cond_mode, x, t, cond, norm=0):
     """The same network composed only of torch.nn.functional calls (independent composition)."""
     w = {k: _t(v) for k, v in w.items()}
     d, nh = net.d, net.heads
     x, cond = _t(x), _t(cond)
     R, H, _ = x.shape
-    LN = lambda a: F.layer_norm(a, (d,), eps=1e-5)
+    LN = (lambda a: F.rms_norm(a, (d,), eps=1e-5)) if norm == 1 else (lambda a: F.layer_norm(a, (d,), eps=1e-5))
 
     def mha(q, k, v):
         sp = lambda a: a.reshape(R, a.shape[1], nh, d // nh).transpose(1, 2)
@@ -86,6 +87,10 @@ def test_forward_against_torch_composition(wl):
     # every input matters: timestep, conditioning, latent
     assert np.abs(net(x, (t + 1) % wl.T, cond) - out).max() > 1e-3
     assert np.abs(net(x, t, cond[::-1]) - out).max() > 1e-3
+    # the RMSNorm alternative: same composition with torch's rms_norm, and a different function
+    rms = dn.Denoiser(w, wl.base.layers, wl.base.heads, wl.cond_mode, norm=1)
+    np.testing.assert_allclose(rms(x, t, cond), _torch_forward(w, wl.base, wl.cond_mode, x, t, cond, norm=1), rtol=1e-9, atol=1e-11)
+    assert np.abs(rms(x, t, cond) - out).max() > 1e-3
 
 
 def test_bf16_rounding_is_round_to_nearest_even():
