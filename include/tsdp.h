@@ -67,6 +67,8 @@ typedef struct {
                              draft (the K+1-member candidate set of Section 3.1): if all drafts pass, the base model's
                              prediction there gives an exact extra base step, so a round advances up to K_eff + 1 steps.
                              Row buffers then hold B*(K_max+1) rows and K = 0 (a plain base step) is allowed */
+  int32_t norm;           /* normalisation of both networks: 0 = LayerNorm, 1 = RMSNorm (x / sqrt(mean x^2 + 1e-5)),
+                             both without affine parameters */
 } tsdp_config;
 
 /* Builds the DDPM tables (fp64 on the host, stored fp32) and an empty context.  Synchronous. */

@@ -26,7 +26,7 @@ class TsdpConfig(C.Structure):
                 ("T", C.c_int32), ("schedule", C.c_int32), ("beta0", C.c_float), ("beta1", C.c_float),
                 ("clip_x0", C.c_int32), ("clip_val", C.c_float), ("B_max", C.c_int32), ("K_max", C.c_int32),
                 ("seed", C.c_uint64), ("sampler", C.c_int32), ("eta", C.c_float),
-                ("bonus_row", C.c_int32)]
+                ("bonus_row", C.c_int32), ("norm", C.c_int32)]
 
 
 _lib = None
@@ -90,7 +90,7 @@ class Tsdp:
     """One library context.  Methods carry the names of the C entry points."""
 
     def __init__(self, *, dtype, H, A, cond_mode, cond_dim, cond_tokens, base, draft, T, schedule,
-                 beta0=1e-4, beta1=0.02, clip=None, B_max, K_max, seed, sampler=0, eta=1.0, bonus_row=False):
+                 beta0=1e-4, beta1=0.02, clip=None, B_max, K_max, seed, sampler=0, eta=1.0, bonus_row=False, norm=0):
         """base / draft: (layers, d, heads, mlp_ratio)."""
         self.lib = load_library()
         self.cfg = TsdpConfig(dtype=dtype, H=H, A=A, cond_mode=cond_mode, cond_dim=cond_dim, cond_tokens=cond_tokens,
@@ -98,7 +98,7 @@ class Tsdp:
                               draft_layers=draft[0], draft_d=draft[1], draft_heads=draft[2], draft_mlp_ratio=draft[3],
                               T=T, schedule=schedule, beta0=beta0, beta1=beta1, clip_x0=0 if clip is None else 1,
                               clip_val=0.0 if clip is None else float(clip), B_max=B_max, K_max=K_max, seed=seed,
-                              sampler=sampler, eta=eta, bonus_row=1 if bonus_row else 0)
+                              sampler=sampler, eta=eta, bonus_row=1 if bonus_row else 0, norm=norm)
         self.ctx = C.c_void_p()
         rc = self.lib.tsdp_create(C.byref(self.cfg), C.byref(self.ctx))
         if rc != 0:
@@ -108,14 +108,14 @@ class Tsdp:
         self.rows_per_env = K_max + (1 if bonus_row else 0)
 
     @classmethod
-    def from_workload(cls, wl, *, B_max=None, K_max=None, clip=None, seed=None, sampler=0, eta=1.0, bonus_row=False):
+    def from_workload(cls, wl, *, B_max=None, K_max=None, clip=None, seed=None, sampler=0, eta=1.0, bonus_row=False, norm=0):
         return cls(dtype=0 if wl.dtype == "fp32" else 1, H=wl.H, A=wl.A, cond_mode=wl.cond_mode, cond_dim=wl.cond_dim,
                    cond_tokens=wl.cond_tokens, base=(wl.base.layers, wl.base.d, wl.base.heads, wl.base.mlp_ratio),
                    draft=(wl.draft.layers, wl.draft.d, wl.draft.heads, wl.draft.mlp_ratio), T=wl.T,
                    schedule=wl.schedule, beta0=wl.beta0 or 1e-4, beta1=wl.beta1 or 0.02, clip=clip,
                    B_max=wl.B if B_max is None else B_max, K_max=wl.K_max if K_max is None else K_max,
                    seed=wl.philox_seed if seed is None else seed, sampler=sampler, eta=eta,
-                   bonus_row=bonus_row)
+                   bonus_row=bonus_row, norm=norm)
 
     def close(self):
         if self.ctx:

@@ -48,6 +48,7 @@ struct FusedNet {
   const float* modb;           // [L*4D]
   const float* modtab;         // [T][L*4D] FiLM vectors of every timestep when they depend on nothing else
                                // (token conditioning: no conditioning vector enters them), else null
+  int rms;                     // 0 = LayerNorm, 1 = RMSNorm
   const float* temb;           // [T, D]
   const float* cemb;           // [B, D] conditioning embedding (vector conditioning) or null
   // cross-attention operands of every (env, layer, head), prepared by tsdp_set_cond:
@@ -435,7 +436,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       float s = 0.0f, q = 0.0f;
 #pragma unroll
       for (int w = 0; w < NW; ++w) { s += red1[w * NT + t]; q += red2[w * NT + t]; }
-      mean[nb] = s * (1.0f / D);
+      mean[nb] = net.rms ? 0.0f : s * (1.0f / D);     // RMSNorm: no centring, the second moment as it is
       rstd[nb] = rsqrtf(fmaxf(q * (1.0f / D) - mean[nb] * mean[nb], 0.0f) + 1e-5f);
     }
     float* fs = reinterpret_cast<float*>(lds + C::ACT_B) + wave * (CHK * 4);   // this wave's staged FiLM block

@@ -106,7 +106,7 @@ __global__ __launch_bounds__(256) void k_linear(const float* __restrict__ in, co
 // a[tok, c] = LN(h[tok, :])[c] * (1 + gamma[row, c]) + beta[row, c]; one wave per token; d <= 1024
 __global__ __launch_bounds__(256) void k_lnmod(const float* __restrict__ h, const float* __restrict__ gamma,
                                                const float* __restrict__ beta, int mod_stride, float* __restrict__ a,
-                                               int H, int d, const int32_t* d_R, int R_cap) {
+                                               int H, int d, int rms, const int32_t* d_R, int R_cap) {
   const int R = live_rows(d_R, R_cap);
   const long long tok = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (tok >= (long long)R * H) return;
@@ -119,7 +119,7 @@ __global__ __launch_bounds__(256) void k_lnmod(const float* __restrict__ h, cons
   for (int i = 0; i < 16; ++i) { const int c = lane + 64 * i; v[i] = c < d ? hr[c] : 0.0f; s += v[i]; }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
-  const float mean = s / (float)d;
+  const float mean = rms ? 0.0f : s / (float)d;        // RMSNorm: no centring
   float q = 0.0f;
 #pragma unroll
   for (int i = 0; i < 16; ++i) { const int c = lane + 64 * i; const float e = c < d ? v[i] - mean : 0.0f; q += e * e; }

@@ -364,6 +364,7 @@ int build_fused(tsdp_ctx* c, Net& n, const std::vector<float>& w, const std::vec
   f.tok_w = n.blob + n.tok_w; f.tok_b = n.blob + n.tok_b; f.pos = n.blob + n.pos;
   f.head = P(head_off); f.head_b = n.blob + n.head_b;
   f.modtab = nullptr;
+  f.rms = cf.norm;
   f.modw = P(mod_off); f.modb = n.modb; f.temb = n.temb; f.cemb = cf.cond_mode == 0 ? n.cemb : nullptr;
   if (cf.cond_mode == 1) {
     const size_t S = cf.cond_tokens, cnt = (size_t)cf.B_max * L * S * d;
@@ -413,7 +414,7 @@ void forward_f32(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int3
   for (int l = 0; l < L; ++l) {
     const LayerOff& o = n.lay[l];
     const float* mod = c->mod + (size_t)l * 4 * d;
-    hipLaunchKernelGGL(k_lnmod, lng, dim3(256), 0, s, c->h, mod, mod + d, ms, c->a, H, d, d_R, R_cap);
+    hipLaunchKernelGGL(k_lnmod, lng, dim3(256), 0, s, c->h, mod, mod + d, ms, c->a, H, d, cf.norm, d_R, R_cap);
     linear<0>(s, c->a, w + o.qkv_w, w + o.qkv_b, c->qkv, R_cap, H, 3 * d, d, d_R);
     hipLaunchKernelGGL(k_attn, dim3(R_cap, n.heads), dim3(256), H * H * sizeof(float), s, c->qkv, 3 * d, c->qkv + d,
                        c->qkv + 2 * d, 3 * d, (const int32_t*)nullptr, c->ao, d, H, H, dh, d_R, R_cap);
@@ -421,19 +422,17 @@ void forward_f32(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int3
     if (cf.cond_mode == 1) {
       const int S = cf.cond_tokens;
       const size_t per_layer = (size_t)cf.B_max * S * d;
-      hipLaunchKernelGGL(k_lnmod, lng, dim3(256), 0, s, c->h, (const float*)nullptr, (const float*)nullptr, 0, c->a, H,
-                         d, d_R, R_cap);
+      hipLaunchKernelGGL(k_lnmod, lng, dim3(256), 0, s, c->h, (const float*)nullptr, (const float*)nullptr, 0, c->a, H, d, cf.norm, d_R, R_cap);
       linear<0>(s, c->a, w + o.cq_w, w + o.cq_b, c->qkv, R_cap, H, d, d, d_R);
       hipLaunchKernelGGL(k_attn, dim3(R_cap, n.heads), dim3(256), H * S * sizeof(float), s, c->qkv, d,
                          n.kc + l * per_layer, n.vc + l * per_layer, d, env_arr, c->ao, d, H, S, dh, d_R, R_cap);
       linear<2>(s, c->ao, w + o.co_w, w + o.co_b, c->h, R_cap, H, d, d, d_R);
     }
-    hipLaunchKernelGGL(k_lnmod, lng, dim3(256), 0, s, c->h, mod + 2 * d, mod + 3 * d, ms, c->a, H, d, d_R, R_cap);
+    hipLaunchKernelGGL(k_lnmod, lng, dim3(256), 0, s, c->h, mod + 2 * d, mod + 3 * d, ms, c->a, H, d, cf.norm, d_R, R_cap);
     linear<1>(s, c->a, w + o.up_w, w + o.up_b, c->u, R_cap, H, m, d, d_R);
     linear<2>(s, c->u, w + o.dn_w, w + o.dn_b, c->h, R_cap, H, d, m, d_R);
   }
-  hipLaunchKernelGGL(k_lnmod, lng, dim3(256), 0, s, c->h, (const float*)nullptr, (const float*)nullptr, 0, c->a, H, d,
-                     d_R, R_cap);
+  hipLaunchKernelGGL(k_lnmod, lng, dim3(256), 0, s, c->h, (const float*)nullptr, (const float*)nullptr, 0, c->a, H, d, cf.norm, d_R, R_cap);
   linear<0>(s, c->a, w + n.head_w, w + n.head_b, eps_out, R_cap, H, A, d, d_R);
 }
 
@@ -546,7 +545,7 @@ int tsdp_create(const tsdp_config* cfg, tsdp_ctx** out) {
     return TSDP_E_INVAL;
   if (f.sampler < 0 || f.sampler > 1 || (f.sampler == 1 && !(f.eta > 0.0f && f.eta <= 1.0f))) return TSDP_E_INVAL;
   if (f.schedule == 0 && !(f.beta0 > 0.0f && f.beta1 >= f.beta0 && f.beta1 < 1.0f)) return TSDP_E_INVAL;
-  if (f.bonus_row < 0 || f.bonus_row > 1) return TSDP_E_INVAL;
+  if (f.bonus_row < 0 || f.bonus_row > 1 || f.norm < 0 || f.norm > 1) return TSDP_E_INVAL;
   if ((long long)f.B_max * (f.K_max + 1) > (1ll << 24)) return TSDP_E_SHAPE;
   tsdp_ctx* c = new (std::nothrow) tsdp_ctx();
   if (!c) return TSDP_E_NOMEM;

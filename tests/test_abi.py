@@ -45,10 +45,10 @@ def test_create_rejects_bad_configs_on_the_host():
     binding, lib = _lib()
     good = dict(dtype=0, H=16, A=2, cond_mode=0, cond_dim=64, cond_tokens=0, base_layers=2, base_d=64, base_heads=2,
                 base_mlp_ratio=4, draft_layers=1, draft_d=32, draft_heads=2, draft_mlp_ratio=4, T=10, schedule=0,
-                beta0=1e-4, beta1=0.02, clip_x0=0, clip_val=0.0, B_max=1, K_max=4, seed=0, sampler=0, eta=1.0, bonus_row=0)
+                beta0=1e-4, beta1=0.02, clip_x0=0, clip_val=0.0, B_max=1, K_max=4, seed=0, sampler=0, eta=1.0, bonus_row=0, norm=0)
     for bad in (dict(dtype=7), dict(H=0), dict(A=3, H=3), dict(base_heads=3), dict(T=0), dict(schedule=5),
                 dict(K_max=0), dict(cond_mode=1, cond_tokens=0), dict(clip_x0=1, clip_val=0.0), dict(beta0=-1.0),
-                dict(sampler=2), dict(bonus_row=2), dict(sampler=1, eta=0.0), dict(sampler=1, eta=1.5)):
+                dict(sampler=2), dict(bonus_row=2), dict(norm=2), dict(sampler=1, eta=0.0), dict(sampler=1, eta=1.5)):
         cfg = binding.TsdpConfig(**{**good, **bad})
         ctx = C.c_void_p()
         assert lib.tsdp_create(C.byref(cfg), C.byref(ctx)) == -1, bad

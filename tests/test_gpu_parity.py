@@ -15,14 +15,14 @@ TOL = {"fp32": 1e-5, "bf16": 2e-2}
 TIE = 1e-5          # accept flags may differ only where |log U - log alpha| is below this (fp32 nets)
 
 
-def _setup(wl, B, clip=None, K_max=None, b_std=0.02, head_scale=1.0, seed=None, sampler=0, eta=1.0, bonus=False):
+def _setup(wl, B, clip=None, K_max=None, b_std=0.02, head_scale=1.0, seed=None, sampler=0, eta=1.0, bonus=False, norm=0):
     wb = ti.make_weights(wl, "base", b_std=b_std, head_scale=head_scale)
     wd = ti.make_weights(wl, "draft", b_std=b_std, head_scale=head_scale)
     cond = ti.make_cond(wl, B)
     x = ti.make_latents(wl, B)
-    base, drafter, sched = oracle_side(wl, wb, wd, sampler=sampler, eta=eta)
+    base, drafter, sched = oracle_side(wl, wb, wd, sampler=sampler, eta=eta, norm=norm)
     ctx = gpu_side(wl, wb, wd, cond, clip=clip, B_max=B, K_max=K_max, seed=seed, sampler=sampler, eta=eta,
-                   bonus_row=bonus)
+                   bonus_row=bonus, norm=norm)
     return dict(wl=wl, B=B, cond=cond, x=x, base=base, drafter=drafter, sched=sched, ctx=ctx, clip=clip, bonus=bonus,
                 seed=wl.philox_seed if seed is None else seed)
 
@@ -87,8 +87,8 @@ def _check_accept(S, rows, o, s, env, window):
     return g, ref, env_ok
 
 
-def _stage_parity(wl, B, t0, K, s, env=None, clip=None, b_std=0.02, paths=None, sampler=0, eta=1.0, bonus=False):
-    S = _setup(wl, B, clip=clip, b_std=b_std, sampler=sampler, eta=eta, bonus=bonus)
+def _stage_parity(wl, B, t0, K, s, env=None, clip=None, b_std=0.02, paths=None, sampler=0, eta=1.0, bonus=False, norm=0):
+    S = _setup(wl, B, clip=clip, b_std=b_std, sampler=sampler, eta=eta, bonus=bonus, norm=norm)
     if paths is not None:
         assert (S["ctx"].path_name(0), S["ctx"].path_name(1)) == paths
     tol = TOL[wl.dtype]
@@ -534,3 +534,18 @@ def test_acceptance_with_regenerated_noise_matches_stored_noise():
         for k in ("row_ptr", "states", "eps_p", "y_last"):
             np.testing.assert_array_equal(rows2[k].cpu().numpy(), rows[k].cpu().numpy())
         ctx.close()
+
+
+def test_rmsnorm_networks_on_every_path():
+    # norm = 1: RMSNorm in place of LayerNorm in both networks (fused fp32, fused bf16 with either conditioning,
+    # general operator kernels)
+    wl = ti.small_variant(ti.C1, B=3)
+    _stage_parity(wl, 3, np.array([9, 5, 0]), np.array([4, 4, 4]), np.ones(3), norm=1, paths=("f32-mfma-fused", "f32-mfma-fused"))
+    wl = ti.small_variant(ti.C3, B=3)
+    t0, K, s = ti.make_schedule_inputs(wl, 3, t0=60)
+    _stage_parity(wl, 3, t0, K, s, norm=1, paths=("bf16-mfma-fused", "bf16-mfma-fused"))
+    wl = ti.small_variant(ti.C4, B=2, base=ti.NetShape(2, 512, 8))
+    t0, K, s = ti.make_schedule_inputs(wl, 2, t0=40)
+    _stage_parity(wl, 2, t0, K, s, norm=1, paths=("bf16-mfma-fused", "bf16-mfma-fused"))
+    wl = ti.small_variant(ti.C1, B=2, base=ti.NetShape(2, 96, 3), draft=ti.NetShape(1, 48, 3))
+    _stage_parity(wl, 2, np.array([9, 4]), np.array([4, 4]), np.ones(2), norm=1, paths=("f32-ops", "f32-ops"))
