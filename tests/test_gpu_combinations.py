@@ -21,7 +21,7 @@ SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("case", range(14))
+@pytest.mark.parametrize("case", range(28))
 def test_random_combination(case):
     import torch
     rng = np.random.default_rng(1000 + case)
