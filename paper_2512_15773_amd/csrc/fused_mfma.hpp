@@ -150,6 +150,12 @@ __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
 #ifndef TSDP_LN_PREFETCH
 #define TSDP_LN_PREFETCH 1   /* request the FiLM vectors before the LayerNorm statistics are reduced */
 #endif
+#ifndef TSDP_GELU_SPLIT
+#define TSDP_GELU_SPLIT 1    /* pipelined MLP: half of a chunk's GELU runs under the previous down-projection */
+#endif
+#ifndef TSDP_MLP_ROTATE
+#define TSDP_MLP_ROTATE 1
+#endif
 #ifndef TSDP_LN_STAGE
 #define TSDP_LN_STAGE 1      /* LayerNorm: cooperative fetch of the FiLM vectors, handed over through LDS */
 #endif
@@ -272,12 +278,13 @@ struct FusedCfg {
 #ifndef TSDP_UDB_OK
 #define TSDP_UDB_OK 1
 #endif
-  static constexpr bool UDB = TSDP_UDB_OK && (NW == 8) && (ACT_B + 2 * U_B + 2 * NW * NT * 4 <= 160 * 1024) && (2 * U_B >= QKV_B);
+  static constexpr bool UDB = TSDP_UDB_OK && (NW == 8) && (ACT_B + 2 * U_B + 2 * NW * NT * 4 + 4 * D * 4 <= 160 * 1024) && (2 * U_B >= QKV_B);
   static constexpr int UU_B = UDB ? 2 * U_B : U_B;
   static constexpr int SCR0_B = QKV_B > UU_B ? QKV_B : UU_B;
   static constexpr int SCR_B = SCR0_B > XT_B ? SCR0_B : XT_B;
   static constexpr int RED_B = 2 * NW * NT * 4;
-  static constexpr int LDS_B = ACT_B + SCR_B + RED_B;   // body; the drafter kernel appends its own regions
+  static constexpr int UB_B = UDB ? 4 * D * 4 : 0;      // pipelined MLP: the layer's up-projection bias (fp32)
+  static constexpr int LDS_B = ACT_B + SCR_B + RED_B + UB_B;   // body; the drafter kernel appends its own regions
   static constexpr int WG_PER_CU = LDS_B <= 80 * 1024 && NW <= 4 ? 2 : 1;
   static constexpr bool LN_STAGE = true;                // FiLM vectors come from global memory: fetch them cooperatively
   static constexpr int WAVES_PER_SIMD = (WG_PER_CU * NW + 3) / 4;
@@ -335,6 +342,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   elem* ubuf = qbuf;
   float* red1 = reinterpret_cast<float*>(lds + C::ACT_B + C::SCR_B);
   float* red2 = red1 + NW * NT;
+  float* upb = red2 + NW * NT;                          // [4D] up-projection bias of the current layer (pipelined MLP)
 
   int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index as a scalar
   __builtin_assume(wave >= 0 && wave < NW);
@@ -602,6 +610,13 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   if (XPF) gq.issue(net.layer[0].qkv, KD, wave, 0, lane, NW);
   for (int layer = 0; layer < net.L; ++layer) {
     const FusedLayer& W = net.layer[layer];
+    if constexpr (C::UDB && !XPF && (NC % 2 == 0)) {
+      // The MLP's GELU runs inside the products, where registers are scarce and a global load would have to wait
+      // for the weight requests ahead of it: its bias comes from LDS.  Every wave is past the last barrier of the
+      // previous layer's MLP, after which nothing reads the old bias.
+      for (int i = threadIdx.x * 4; i < 4 * D; i += C::THREADS * 4)
+        *reinterpret_cast<f32x4*>(upb + i) = *reinterpret_cast<const f32x4*>(W.up_b + i);
+    }
     // ================= self-attention block =================
     TSDP_TICK(11)
     write_ln(layer, 0);
@@ -763,13 +778,16 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
     }
     // ================= MLP block =================
     if constexpr (C::UDB && !XPF && (NC % 2 == 0)) {
-      // Two hidden-chunk buffers: the GELU epilogue of chunk c is spread over the k-steps of the up-projection of
-      // chunk c+1, so its vector work runs while the matrix pipeline is busy; one barrier per chunk.
+      // Two hidden-chunk buffers: the GELU epilogue of chunk c is vector work that runs in the issue slots the
+      // matrix pipeline leaves free.  Its first half is spread over the k-steps of the down-projection of chunk
+      // c-1, its second half over those of the up-projection of chunk c+1 (all of it in one product would need
+      // more vector slots than that product leaves); one barrier per chunk.
       TSDP_TICK(11)
       write_ln(layer, 2);
       TSDP_TICK(0)
       f32x4 accA[MBU][NB], accB[MBU][NB];
       constexpr int PARTS = MBU * NB;
+      constexpr int HALF = TSDP_GELU_SPLIT ? PARTS / 2 : 0;   // parts done under the previous down-projection
       auto up_gemm = [&](int c, f32x4 (&acc)[MBU][NB], auto&& side) {
         GU gu;
 #pragma unroll
@@ -780,47 +798,67 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         gu.run(act, AS, acc, lane, side);
       };
       // GELU(acc + bias) of accumulator part idx of chunk c -> hidden buffer c & 1
-      auto gelu_part = [&](int c, const f32x4 (&acc)[MBU][NB], const f32x4 (&bias)[MBU], int idx) {
+      auto gelu_part = [&](int c, const f32x4 (&acc)[MBU][NB], int idx) {
         const int mb = idx / NB, nb = idx % NB;
         const int f0 = (wave * MBU + mb) * 16 + lg * 4;
-        f32x4 v = acc[mb][nb] + bias[mb];
+        f32x4 v = acc[mb][nb] + *reinterpret_cast<const f32x4*>(upb + c * CH + f0);
 #pragma unroll
         for (int i = 0; i < 4; ++i) v[i] = (TSDP_ABL & 16) ? v[i] : gelu_fast(v[i]);
         *reinterpret_cast<vec4*>(ubuf + (c & 1) * NT * US + (nb * 16 + l16) * US + f0) = TT::cvt(v);
       };
-      auto load_bias = [&](int c, f32x4 (&bias)[MBU]) {
-#pragma unroll
-        for (int mb = 0; mb < MBU; ++mb)
-          bias[mb] = *reinterpret_cast<const f32x4*>(W.up_b + c * CH + (wave * MBU + mb) * 16 + lg * 4);
-      };
-      // chunk c: accumulator `cur` holds its pre-activations; `nxt` receives those of chunk c+1
-      auto chunk = [&](int c, f32x4 (&cur)[MBU][NB], f32x4 (&nxt)[MBU][NB]) {
+      // chunk c: accumulator `cur` holds its pre-activations, parts [0, HALF) of its GELU are already in the hidden
+      // buffer; `nxt` receives the pre-activations of chunk c+1
+      auto chunk = [&](int c, f32x4 (&cur)[MBU][NB], f32x4 (&nxt)[MBU][NB], auto HASNEXT) {
+        constexpr bool NEXT = decltype(HASNEXT)::value;
         TSDP_FENCE_IDS();
-        f32x4 bias[MBU];
-        load_bias(c, bias);
-        if (c + 1 < NC) {
+        if constexpr (NEXT) {
           up_gemm(c + 1, nxt, [&](int k) {
 #pragma unroll
-            for (int idx = k * PARTS / KD; idx < (k + 1) * PARTS / KD; ++idx) gelu_part(c, cur, bias, idx);
+            for (int idx = HALF + k * (PARTS - HALF) / KD; idx < HALF + (k + 1) * (PARTS - HALF) / KD; ++idx)
+              gelu_part(c, cur, idx);
           });
         } else {
 #pragma unroll
-          for (int idx = 0; idx < PARTS; ++idx) gelu_part(c, cur, bias, idx);
+          for (int idx = HALF; idx < PARTS; ++idx) gelu_part(c, cur, idx);
         }
         TSDP_TICK(6)
         __syncthreads();
         TSDP_TICK(7)
         GD gd;
         gd.issue(W.dn, KM, wave * MBH, c * (KC), lane);
-        gd.run(ubuf + (c & 1) * NT * US, US, h, lane);
+        if constexpr (NEXT && HALF > 0) {
+          // the buffer of chunk c+1 was last read by the down-projection of chunk c-1: every wave is past it
+          gd.run(ubuf + (c & 1) * NT * US, US, h, lane, [&](int k) {
+#pragma unroll
+            for (int idx = k * HALF / KC; idx < (k + 1) * HALF / KC; ++idx) gelu_part(c + 1, nxt, idx);
+          });
+        } else {
+          gd.run(ubuf + (c & 1) * NT * US, US, h, lane);
+        }
         TSDP_TICK(9)
       };
       up_gemm(0, accA, [](int) {});
+#pragma unroll
+      for (int idx = 0; idx < HALF; ++idx) gelu_part(0, accA, idx);
       TSDP_TICK(6)
-      for (int c = 0; c < NC; c += 2) {
-        chunk(c, accA, accB);
-        chunk(c + 1, accB, accA);
+#if TSDP_MLP_ROTATE
+      // one loop body: the pre-activations of the next chunk move into the registers of the current one
+      for (int c = 0; c + 1 < NC; ++c) {
+        chunk(c, accA, accB, std::true_type{});
+#pragma unroll
+        for (int mb = 0; mb < MBU; ++mb)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) accA[mb][nb] = accB[mb][nb];
       }
+      chunk(NC - 1, accA, accB, std::false_type{});
+#else
+      for (int c = 0; c + 2 < NC; c += 2) {
+        chunk(c, accA, accB, std::true_type{});
+        chunk(c + 1, accB, accA, std::true_type{});
+      }
+      chunk(NC - 2, accA, accB, std::true_type{});
+      chunk(NC - 1, accB, accA, std::false_type{});
+#endif
     } else {
     GU gu;
     if (XPF) gu.issue(W.up, KD, wave * MBU, 0, lane);
