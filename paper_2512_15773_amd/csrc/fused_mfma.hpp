@@ -153,8 +153,8 @@ __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
 #ifndef TSDP_GELU_SPLIT
 #define TSDP_GELU_SPLIT 1    /* pipelined MLP: half of a chunk's GELU runs under the previous down-projection */
 #endif
-#ifndef TSDP_MLP_ROTATE
-#define TSDP_MLP_ROTATE 1
+#ifndef TSDP_MLP_PRIME
+#define TSDP_MLP_PRIME 1      /* pipelined MLP: each product requests the first weights of the next in its tail */
 #endif
 #ifndef TSDP_LN_STAGE
 #define TSDP_LN_STAGE 1      /* LayerNorm: cooperative fetch of the FiLM vectors, handed over through LDS */
@@ -194,6 +194,24 @@ struct FragGemm {
     for (int mb = 0; mb < MB; ++mb) a[0][mb] = wl[(size_t)mb * kst * 64];
   }
 
+  // Priming: the first PF k-steps of this product requested stage by stage from inside the tail of the previous
+  // product (whose own ring is draining then), so the weight stream does not stop at the phase boundary.
+  // prime_begin sets the addresses, prime_stage(p) requests k-step p, run<PF>() then starts with a full ring.
+  __device__ __forceinline__ void prime_begin(const void* __restrict__ wp, int ks_total, int mf0, int ks0, int lane, int mfs = 1) {
+    wl = reinterpret_cast<const frag*>(wp) + ((size_t)mf0 * ks_total + ks0) * 64 + lane;
+    kst = ks_total * mfs;
+  }
+  __device__ __forceinline__ void prime_stage(int p) {
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) a[p][mb] = wl[((size_t)mb * kst + p) * 64];
+  }
+  // to be called as side work of k-step k of a product of PREV k-steps: requests stage k - (PREV - PF)
+  template <int PREV>
+  __device__ __forceinline__ void prime_in_tail(int k) {
+    static_assert(PREV >= PF, "the previous product is too short to hide the priming");
+    if (k >= PREV - PF) prime_stage(k - (PREV - PF));
+  }
+
   struct NoSide { __device__ __forceinline__ void operator()(int) const {} };
 
   __device__ __forceinline__ void run(const elem* act, int stride, f32x4 (&acc)[MB][NB], int lane) {
@@ -201,13 +219,15 @@ struct FragGemm {
   }
 
   // side(k) is called once per k-step after its MFMAs have been issued: independent vector work placed there
-  // (an epilogue of the previous product) executes while the matrix pipeline is busy.
-  template <class Side>
-  __device__ __forceinline__ void run(const elem* act, int stride, f32x4 (&acc)[MB][NB], int lane, Side&& side) {
+  // (an epilogue of the previous product) executes while the matrix pipeline is busy.  PRIMED = ring stages
+  // already requested (1 after issue(), PF after priming).
+  template <class Side, int PRIMED = 1>
+  __device__ __forceinline__ void run(const elem* act, int stride, f32x4 (&acc)[MB][NB], int lane, Side&& side,
+                                      std::integral_constant<int, PRIMED> = {}) {
     const elem* al = act + (lane & 15) * stride + (lane >> 4) * TT::VW;
     frag b[BD][NB];
 #pragma unroll
-    for (int p = 1; p < PF; ++p)
+    for (int p = PRIMED; p < PF; ++p)
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) a[p][mb] = wl[((size_t)mb * kst + p) * 64];
 #pragma unroll
@@ -788,14 +808,17 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       f32x4 accA[MBU][NB], accB[MBU][NB];
       constexpr int PARTS = MBU * NB;
       constexpr int HALF = TSDP_GELU_SPLIT ? PARTS / 2 : 0;   // parts done under the previous down-projection
-      auto up_gemm = [&](int c, f32x4 (&acc)[MBU][NB], auto&& side) {
-        GU gu;
+      GU gu;
+      GD gd;
+      constexpr bool PRIME = TSDP_MLP_PRIME && KD >= GD::PF && KC >= GU::PF;
+      typedef std::integral_constant<int, GU::PF> UFULL;
+      typedef std::integral_constant<int, GD::PF> DFULL;
+      typedef std::integral_constant<int, 1> ONE;
+      auto zero = [&](f32x4 (&acc)[MBU][NB]) {
 #pragma unroll
         for (int mb = 0; mb < MBU; ++mb)
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0, 0, 0, 0};
-        gu.issue(W.up, KD, c * (CH / 16) + wave * MBU, 0, lane);
-        gu.run(act, AS, acc, lane, side);
       };
       // GELU(acc + bias) of accumulator part idx of chunk c -> hidden buffer c & 1
       auto gelu_part = [&](int c, const f32x4 (&acc)[MBU][NB], int idx) {
@@ -807,58 +830,74 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         *reinterpret_cast<vec4*>(ubuf + (c & 1) * NT * US + (nb * 16 + l16) * US + f0) = TT::cvt(v);
       };
       // chunk c: accumulator `cur` holds its pre-activations, parts [0, HALF) of its GELU are already in the hidden
-      // buffer; `nxt` receives the pre-activations of chunk c+1
-      auto chunk = [&](int c, f32x4 (&cur)[MBU][NB], f32x4 (&nxt)[MBU][NB], auto HASNEXT) {
-        constexpr bool NEXT = decltype(HASNEXT)::value;
+      // buffer; `nxt` receives the pre-activations of chunk c+1.  UPRIMED: the weights of that up-projection were
+      // requested in the tail of the previous down-projection.  Each product requests the first weights of the one
+      // after it in its own tail (the down-projection those of the up-projection of chunk c+2; past the last chunk
+      // it re-requests the last chunk's, which are simply not used).
+      auto chunk = [&](int c, f32x4 (&cur)[MBU][NB], f32x4 (&nxt)[MBU][NB], auto HASNEXT, auto UPRIMED) {
+        constexpr bool NEXT = decltype(HASNEXT)::value, UP = decltype(UPRIMED)::value && PRIME;
         TSDP_FENCE_IDS();
+        if (PRIME) gd.prime_begin(W.dn, KM, wave * MBH, c * (KC), lane);
         if constexpr (NEXT) {
-          up_gemm(c + 1, nxt, [&](int k) {
+          zero(nxt);
+          if (!UP) gu.issue(W.up, KD, (c + 1) * (CH / 16) + wave * MBU, 0, lane);
+          auto side = [&](int k) {
 #pragma unroll
             for (int idx = HALF + k * (PARTS - HALF) / KD; idx < HALF + (k + 1) * (PARTS - HALF) / KD; ++idx)
               gelu_part(c, cur, idx);
-          });
+            if (PRIME) gd.template prime_in_tail<KD>(k);
+          };
+          if constexpr (UP) gu.run(act, AS, nxt, lane, side, UFULL{});
+          else gu.run(act, AS, nxt, lane, side, ONE{});
         } else {
+          if (PRIME) {
+#pragma unroll
+            for (int p = 0; p < GD::PF; ++p) gd.prime_stage(p);
+          }
 #pragma unroll
           for (int idx = HALF; idx < PARTS; ++idx) gelu_part(c, cur, idx);
         }
         TSDP_TICK(6)
         __syncthreads();
         TSDP_TICK(7)
-        GD gd;
-        gd.issue(W.dn, KM, wave * MBH, c * (KC), lane);
-        if constexpr (NEXT && HALF > 0) {
+        if (!PRIME) gd.issue(W.dn, KM, wave * MBH, c * (KC), lane);
+        if constexpr (NEXT) {
+          const int c2 = c + 2 < NC ? c + 2 : NC - 1;
+          if (PRIME) gu.prime_begin(W.up, KD, c2 * (CH / 16) + wave * MBU, 0, lane);
           // the buffer of chunk c+1 was last read by the down-projection of chunk c-1: every wave is past it
-          gd.run(ubuf + (c & 1) * NT * US, US, h, lane, [&](int k) {
+          auto side = [&](int k) {
 #pragma unroll
             for (int idx = k * HALF / KC; idx < (k + 1) * HALF / KC; ++idx) gelu_part(c + 1, nxt, idx);
-          });
+            if (PRIME) gu.template prime_in_tail<KC>(k);
+          };
+          if constexpr (PRIME) gd.run(ubuf + (c & 1) * NT * US, US, h, lane, side, DFULL{});
+          else gd.run(ubuf + (c & 1) * NT * US, US, h, lane, side, ONE{});
         } else {
-          gd.run(ubuf + (c & 1) * NT * US, US, h, lane);
+          if constexpr (PRIME) gd.run(ubuf + (c & 1) * NT * US, US, h, lane, typename GD::NoSide{}, DFULL{});
+          else gd.run(ubuf + (c & 1) * NT * US, US, h, lane);
         }
         TSDP_TICK(9)
       };
-      up_gemm(0, accA, [](int) {});
+      zero(accA);
+      gu.issue(W.up, KD, wave * MBU, 0, lane);
+      gu.run(act, AS, accA, lane);
 #pragma unroll
       for (int idx = 0; idx < HALF; ++idx) gelu_part(0, accA, idx);
       TSDP_TICK(6)
-#if TSDP_MLP_ROTATE
       // one loop body: the pre-activations of the next chunk move into the registers of the current one
-      for (int c = 0; c + 1 < NC; ++c) {
-        chunk(c, accA, accB, std::true_type{});
+      auto rotate = [&]() {
 #pragma unroll
         for (int mb = 0; mb < MBU; ++mb)
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) accA[mb][nb] = accB[mb][nb];
+      };
+      chunk(0, accA, accB, std::true_type{}, std::false_type{});
+      rotate();
+      for (int c = 1; c + 1 < NC; ++c) {
+        chunk(c, accA, accB, std::true_type{}, std::true_type{});
+        rotate();
       }
-      chunk(NC - 1, accA, accB, std::false_type{});
-#else
-      for (int c = 0; c + 2 < NC; c += 2) {
-        chunk(c, accA, accB, std::true_type{});
-        chunk(c + 1, accB, accA, std::true_type{});
-      }
-      chunk(NC - 2, accA, accB, std::true_type{});
-      chunk(NC - 1, accB, accA, std::false_type{});
-#endif
+      chunk(NC - 1, accA, accB, std::false_type{}, std::false_type{});
     } else {
     GU gu;
     if (XPF) gu.issue(W.up, KD, wave * MBU, 0, lane);
