@@ -29,7 +29,7 @@ PEAK_FP32_TFLOPS = 157.3       # MI355X fp32 vector
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # HBM bytes per launch of the fused verify forward (FETCH_SIZE + WRITE_SIZE, scaled by a 1 GiB copy), from the
 # rocprofv3 --pmc runs summarised in profiles/verify_forward_hbm_traffic_c4_c5.txt
-MEASURED_TRAFFIC_BYTES = {"C4": int((4.261 + 0.003) * 2 ** 30), "C5": int((2.161 + 0.004) * 2 ** 30)}
+MEASURED_TRAFFIC_BYTES = {"C4": int((4.261 + 0.003) * 2 ** 30), "C5": int((2.192 + 0.004) * 2 ** 30)}
 
 
 def verify_flops(wl, R):
