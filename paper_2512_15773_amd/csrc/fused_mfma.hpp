@@ -298,12 +298,12 @@ struct FusedCfg {
 #ifndef TSDP_UDB_OK
 #define TSDP_UDB_OK 1
 #endif
-  static constexpr bool UDB = TSDP_UDB_OK && (NW == 8) && (ACT_B + 2 * U_B + 2 * NW * NT * 4 + 4 * D * 4 <= 160 * 1024) && (2 * U_B >= QKV_B);
+  static constexpr bool UDB = TSDP_UDB_OK && (NW == 8) && (ACT_B + 2 * U_B + 2 * NW * NT * 4 + 7 * D * 4 <= 160 * 1024) && (2 * U_B >= QKV_B);
   static constexpr int UU_B = UDB ? 2 * U_B : U_B;
   static constexpr int SCR0_B = QKV_B > UU_B ? QKV_B : UU_B;
   static constexpr int SCR_B = SCR0_B > XT_B ? SCR0_B : XT_B;
   static constexpr int RED_B = 2 * NW * NT * 4;
-  static constexpr int UB_B = UDB ? 4 * D * 4 : 0;      // pipelined MLP: the layer's up-projection bias (fp32)
+  static constexpr int UB_B = UDB ? 7 * D * 4 : 0;      // pipelined MLP: the layer's up-projection bias and the three residual biases (fp32)
   static constexpr int LDS_B = ACT_B + SCR_B + RED_B + UB_B;   // body; the drafter kernel appends its own regions
   static constexpr int WG_PER_CU = LDS_B <= 80 * 1024 && NW <= 4 ? 2 : 1;
   static constexpr bool LN_STAGE = true;                // FiLM vectors come from global memory: fetch them cooperatively
@@ -362,7 +362,8 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   elem* ubuf = qbuf;
   float* red1 = reinterpret_cast<float*>(lds + C::ACT_B + C::SCR_B);
   float* red2 = red1 + NW * NT;
-  float* upb = red2 + NW * NT;                          // [4D] up-projection bias of the current layer (pipelined MLP)
+  float* upb = red2 + NW * NT;                          // pipelined MLP: biases of the current layer, [4D] up-projection,
+  float* resb = upb + 4 * D;                            // then [3][D] self-attention output, cross-attention output, MLP down
 
   int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave index as a scalar
   __builtin_assume(wave >= 0 && wave < NW);
@@ -617,7 +618,11 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
     }
   };
 
-  auto add_bias_h = [&](const float* bias) {
+  // residual bias `which` (0 self-attention output, 1 cross-attention output, 2 MLP down): from LDS where the layer's
+  // biases are staged (a global load here would be waited for with nothing to overlap it), else from global memory
+  constexpr bool BSTAGE = C::UDB && !XPF && (NC % 2 == 0);
+  auto add_bias_h = [&](const float* bias, int which) {
+    if (BSTAGE) bias = resb + which * D;
 #pragma unroll
     for (int mb = 0; mb < MBH; ++mb) {
       const f32x4 b = *reinterpret_cast<const f32x4*>(bias + (wave * MBH + mb) * 16 + lg * 4);
@@ -630,17 +635,24 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   if (XPF) gq.issue(net.layer[0].qkv, KD, wave, 0, lane, NW);
   for (int layer = 0; layer < net.L; ++layer) {
     const FusedLayer& W = net.layer[layer];
-    if constexpr (C::UDB && !XPF && (NC % 2 == 0)) {
-      // The MLP's GELU runs inside the products, where registers are scarce and a global load would have to wait
-      // for the weight requests ahead of it: its bias comes from LDS.  Every wave is past the last barrier of the
-      // previous layer's MLP, after which nothing reads the old bias.
-      for (int i = threadIdx.x * 4; i < 4 * D; i += C::THREADS * 4)
-        *reinterpret_cast<f32x4*>(upb + i) = *reinterpret_cast<const f32x4*>(W.up_b + i);
-    }
     // ================= self-attention block =================
     TSDP_TICK(11)
     write_ln(layer, 0);
     TSDP_TICK(0)
+    if constexpr (BSTAGE) {
+      // The layer's biases that are added outside a product's own latency shadow go to LDS: the MLP's GELU runs inside
+      // the products, where registers are scarce and a global load would queue behind the weight requests, and a
+      // residual bias is needed right after a product with nothing to overlap a global load.  Written here, after
+      // the barriers of the LayerNorm above: every wave has finished the previous layer, whose last act is to add
+      // its down-projection bias; the first use of the new values is several barriers away.
+      for (int i = threadIdx.x * 4; i < 4 * D; i += C::THREADS * 4)
+        *reinterpret_cast<f32x4*>(upb + i) = *reinterpret_cast<const f32x4*>(W.up_b + i);
+      for (int i = threadIdx.x * 4; i < D; i += C::THREADS * 4) {
+        *reinterpret_cast<f32x4*>(resb + i) = *reinterpret_cast<const f32x4*>(W.o_b + i);
+        if constexpr (CM == 1) *reinterpret_cast<f32x4*>(resb + D + i) = *reinterpret_cast<const f32x4*>(W.co_b + i);
+        *reinterpret_cast<f32x4*>(resb + 2 * D + i) = *reinterpret_cast<const f32x4*>(W.dn_b + i);
+      }
+    }
     for (int g = 0; g < NG; ++g) {
       TSDP_FENCE_IDS();
       GO go;
@@ -699,7 +711,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       }
       TSDP_TICK(5)
     }
-    add_bias_h(W.o_b);
+    add_bias_h(W.o_b, 0);
     // ================= cross-attention block (observation tokens) =================
     if constexpr (CM == 1) {
       // HPX heads per phase; the queries of a phase are one token-major LDS matrix [NT][HPX*DH], so the output
@@ -794,7 +806,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         go.run(qbuf, QXS, h, lane);
         TSDP_TICK(5)
       }
-      add_bias_h(W.co_b);
+      add_bias_h(W.co_b, 1);
     }
     // ================= MLP block =================
     if constexpr (C::UDB && !XPF && (NC % 2 == 0)) {
@@ -950,7 +962,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       TSDP_TICK(9)
     }
     }
-    add_bias_h(W.dn_b);
+    add_bias_h(W.dn_b, 2);
   }
 
   // ---- output head: eps = head_w LN(h) + head_b ---------------------------------------------------------
