@@ -132,6 +132,10 @@ __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
   return r;
 }
 
+// Tuning builds only.  TSDP_ABL is a bit mask of timing ablations that leave every address unchanged and make the
+// results meaningless: 1 weight fragments are not fetched, 2 LDS operands are not re-read, 4 no matrix instructions,
+// 8 no attention, 16 no GELU.  The product is built with 0.  The other switches below select between measured
+// alternatives and default to the faster one.
 #ifndef TSDP_ABL
 #define TSDP_ABL 0
 #endif
@@ -145,7 +149,7 @@ __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
 #define TSDP_TICK(cat)
 #endif
 #ifndef TSDP_INFLIGHT_CLK
-#define TSDP_INFLIGHT_CLK 384
+#define TSDP_INFLIGHT_CLK 384  /* cycles of matrix work between the request of a weight fragment and its use */
 #endif
 #ifndef TSDP_LN_PREFETCH
 #define TSDP_LN_PREFETCH 1   /* request the FiLM vectors before the LayerNorm statistics are reduced */
@@ -160,10 +164,10 @@ __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
 #define TSDP_LN_STAGE 1      /* LayerNorm: cooperative fetch of the FiLM vectors, handed over through LDS */
 #endif
 #ifndef TSDP_XHEADMAJOR
-#define TSDP_XHEADMAJOR 1
+#define TSDP_XHEADMAJOR 1    /* cross-attention: a wave takes whole heads where they divide evenly over the waves */
 #endif
 #ifndef TSDP_PFMAX
-#define TSDP_PFMAX 4
+#define TSDP_PFMAX 4          /* upper limit of the weight ring's depth in k-steps */
 #endif
 
 // Weight-streaming GEMM on fragments:  acc[mb][nb] += W(frag rows mf0+mb, k-steps ks0..ks0+NKS) . act^T,
