@@ -354,6 +354,10 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   constexpr int DH = C::DH, HP = C::HP, NB = C::NB, MBH = C::MBH, MBQ = C::MBQ, MBU = C::MBU, MBC = C::MBC,
                 RPT = C::RPT, NKF = C::NKF, AS = C::AS, QS = C::QS, VS = C::VS, US = C::US, SF = C::SF;
   constexpr int NG = HEADS / HP, NC = 4 * D / CH;
+  // Self-attention queries (and, over them, the attention output) of a head group: token-major [NT][HP*DH + pad], so
+  // the output projection contracts all heads of the group in one product; keys stay per head [HP][NT][DH + pad].
+  constexpr int QTS = HP * DH + C::TT::PAD;
+  static_assert(C::NT * QTS <= C::HP * C::NT * C::QS, "the token-major queries fit the per-head query region");
   typedef typename C::TT TT;
   typedef typename TT::elem elem;
   typedef typename TT::frag frag;
@@ -361,7 +365,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   constexpr int KSTEP = TT::KSTEP, VW = TT::VW;
   elem* act = reinterpret_cast<elem*>(lds);
   elem* qbuf = reinterpret_cast<elem*>(lds + C::ACT_B);
-  elem* kbuf = qbuf + HP * NT * QS;
+  elem* kbuf = qbuf + HP * NT * QS;                     // (the token-major queries need NT * QTS <= HP * NT * QS elements)
   elem* vtb = kbuf + HP * NT * QS;
   elem* ubuf = qbuf;
   float* red1 = reinterpret_cast<float*>(lds + C::ACT_B + C::SCR_B);
@@ -380,7 +384,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   constexpr bool XPF = C::XPF;
   constexpr int KD = D / KSTEP, KH = DH / KSTEP, KC = CH / KSTEP, KM = 4 * D / KSTEP;   // k-steps of D, DH, CH, 4D
   typedef FragGemm<TT, MBQ, NB, KD, BD> GQ;             // q|k|v projection of one head group
-  typedef FragGemm<TT, MBH, NB, KH, BD> GO;             // output projection, one head's slice of K
+  typedef FragGemm<TT, MBH, NB, HP * KH, BD> GO;        // output projection, the slice of K of one head group
   typedef FragGemm<TT, MBU, NB, KD, BD> GU;             // MLP up, one hidden chunk
   typedef FragGemm<TT, MBH, NB, KC, BD> GD;             // MLP down, one hidden chunk of K
   typedef FragGemm<TT, (MBC > 0 ? MBC : 1), NB, KD, BD> GC;   // cross-attention query projection
@@ -534,14 +538,14 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
 
   // softmax(q k^T) v for query fragment qf of (row, head) held in LDS; the result overwrites those q rows
   auto self_attention = [&](int r, int hh, int qf) {
-    elem* qp = qbuf + (hh * NT + r * H + qf * 16) * QS;
+    elem* qp = qbuf + (r * H + qf * 16) * QTS + hh * DH;
     const elem* kp = kbuf + (hh * NT + r * H) * QS;
     f32x4 s[NKF];                                       // [key frag]; lane: query l16, keys lg*4..
 #pragma unroll
     for (int kf = 0; kf < NKF; ++kf) s[kf] = f32x4{0, 0, 0, 0};
 #pragma unroll
     for (int ks = 0; ks < KH; ++ks) {
-      const frag qb = *reinterpret_cast<const frag*>(qp + l16 * QS + ks * KSTEP + lg * VW);
+      const frag qb = *reinterpret_cast<const frag*>(qp + l16 * QTS + ks * KSTEP + lg * VW);
 #pragma unroll
       for (int kf = 0; kf < NKF; ++kf) {
         const frag ka = *reinterpret_cast<const frag*>(kp + (kf * 16 + l16) * QS + ks * KSTEP + lg * VW);
@@ -559,7 +563,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         const vec4 va = *reinterpret_cast<const vec4*>(vp + (cf * 16 + l16) * VS + kf * 16 + lg * 4);
         TT::mma16(va, p[kf], o);
       }
-      *reinterpret_cast<vec4*>(qp + l16 * QS + cf * 16 + lg * 4) = TT::cvt(o);
+      *reinterpret_cast<vec4*>(qp + l16 * QTS + cf * 16 + lg * 4) = TT::cvt(o);
     }
   };
 
@@ -685,7 +689,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
             const f32x4 v = acc[mb][nb] + bias[mb];
             const int t = nb * 16 + l16;
             if (cls == 0) {
-              *reinterpret_cast<vec4*>(qbuf + (hh * NT + t) * QS + c0) = TT::cvt(v);
+              *reinterpret_cast<vec4*>(qbuf + t * QTS + hh * DH + c0) = TT::cvt(v);
             } else if (cls == 1) {
               *reinterpret_cast<vec4*>(kbuf + (hh * NT + t) * QS + c0) = TT::cvt(v);
             } else {
@@ -707,12 +711,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       TSDP_TICK(2)
       if (XPF && g + 1 < NG) gq.issue(W.qkv, KD, (g + 1) * (HP * 3 * DH / 16) + wave, 0, lane, NW);
       if (!XPF) go.issue(W.o, KD, wave * MBH, g * HP * KH, lane);
-      go.run(qbuf, QS, h, lane);
-#pragma unroll
-      for (int hh = 1; hh < HP; ++hh) {
-        go.issue(W.o, KD, wave * MBH, (g * HP + hh) * KH, lane);
-        go.run(qbuf + hh * NT * QS, QS, h, lane);
-      }
+      go.run(qbuf, QTS, h, lane);                        // one product over the heads of the group
       TSDP_TICK(5)
     }
     add_bias_h(W.o_b, 0);
