@@ -56,3 +56,12 @@ def test_create_rejects_bad_configs_on_the_host():
     assert lib.tsdp_create(None, None) == -1
     lib.tsdp_destroy(None)                                             # allowed
     assert lib.tsdp_last_error(None) == b"null context"
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stdout + r.stderr)
+    assert not any(line.startswith("{") for line in r.stdout.splitlines())      # no result line
