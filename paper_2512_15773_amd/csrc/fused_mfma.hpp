@@ -349,7 +349,8 @@ struct DraftCfg : Base {
 template <class C>
 __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* lds, const float* xt, int A,
                                            const float* const* mrow,
-                                           const int32_t* env_of_row, float* eo, int ntok_live) {
+                                           const int32_t* env_of_row, float* eo, int ntok_live,
+                                           const float* lbias = nullptr) {
   constexpr int D = C::D, NT = C::NT, H = C::H, HEADS = C::HEADS, CM = C::CM, CH = C::CH, NW = C::NW;
   constexpr int DH = C::DH, HP = C::HP, NB = C::NB, MBH = C::MBH, MBQ = C::MBQ, MBU = C::MBU, MBC = C::MBC,
                 RPT = C::RPT, NKF = C::NKF, AS = C::AS, QS = C::QS, VS = C::VS, US = C::US, SF = C::SF;
@@ -629,8 +630,9 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   // residual bias `which` (0 self-attention output, 1 cross-attention output, 2 MLP down): from LDS where the layer's
   // biases are staged (a global load here would be waited for with nothing to overlap it), else from global memory
   constexpr bool BSTAGE = C::UDB && !XPF && (NC % 2 == 0);
-  auto add_bias_h = [&](const float* bias, int which) {
+  auto add_bias_h = [&](const float* bias, int layer, int which) {
     if (BSTAGE) bias = resb + which * D;
+    else if (lbias) bias = lbias + (layer * 3 + which) * D;
 #pragma unroll
     for (int mb = 0; mb < MBH; ++mb) {
       const f32x4 b = *reinterpret_cast<const f32x4*>(bias + (wave * MBH + mb) * 16 + lg * 4);
@@ -714,7 +716,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       go.run(qbuf, QTS, h, lane);                        // one product over the heads of the group
       TSDP_TICK(5)
     }
-    add_bias_h(W.o_b, 0);
+    add_bias_h(W.o_b, layer, 0);
     // ================= cross-attention block (observation tokens) =================
     if constexpr (CM == 1) {
       // HPX heads per phase; the queries of a phase are one token-major LDS matrix [NT][HPX*DH], so the output
@@ -809,7 +811,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         go.run(qbuf, QXS, h, lane);
         TSDP_TICK(5)
       }
-      add_bias_h(W.co_b, 1);
+      add_bias_h(W.co_b, layer, 1);
     }
     // ================= MLP block =================
     if constexpr (C::UDB && !XPF && (NC % 2 == 0)) {
@@ -965,7 +967,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       TSDP_TICK(9)
     }
     }
-    add_bias_h(W.dn_b, 2);
+    add_bias_h(W.dn_b, layer, 2);
   }
 
   // ---- output head: eps = head_w LN(h) + head_b ---------------------------------------------------------
@@ -1053,6 +1055,9 @@ __global__ __launch_bounds__(C::THREADS) void k_fused_draft(FusedNet net, DraftI
   const int mod_cols = io.mod_cols, SPE = mod_cols / RPT;
   float* modbuf = et + NT * A;                                       // [mod_cols][L*4D] FiLM vectors
   elem* sgbuf = reinterpret_cast<elem*>(modbuf + mod_cols * mod_stride);   // [16][D+pad] SiLU(g), unused rows zero
+  // [L][3][D] residual biases (self-attention output, cross-attention output, MLP down) of all layers: they are added
+  // right after a product, where a global load has nothing to overlap it, K times per rollout
+  float* dbias = reinterpret_cast<float*>(sgbuf + 16 * SGS);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l16 = lane & 15, lg = lane >> 4;
   const int env0 = blockIdx.x * RPT;
   if (threadIdx.x == 0) s_kmax = 0;
@@ -1070,6 +1075,11 @@ __global__ __launch_bounds__(C::THREADS) void k_fused_draft(FusedNet net, DraftI
     atomicMax(&s_kmax, ke);
   }
   for (int i = threadIdx.x; i < 16 * SGS; i += TH) sgbuf[i] = (elem)0.0f;
+  for (int i = threadIdx.x; i < net.L * 3 * D; i += TH) {
+    const int l = i / (3 * D), which = (i / D) % 3, c = i % D;
+    const float* src = which == 0 ? net.layer[l].o_b : (which == 1 ? net.layer[l].co_b : net.layer[l].dn_b);
+    dbias[i] = src ? src[c] : 0.0f;
+  }
   for (int i = threadIdx.x; i < NT * A; i += TH) {
     const int b = env0 + i / DE;
     yt[i] = b < io.B ? io.y[(size_t)env0 * DE + i] : 0.0f;
@@ -1120,7 +1130,7 @@ __global__ __launch_bounds__(C::THREADS) void k_fused_draft(FusedNet net, DraftI
     }
     }
     __syncthreads();
-    fused_body<DraftCfg<C>>(net, lds, yt, A, mrow, envs, et, NT);
+    fused_body<DraftCfg<C>>(net, lds, yt, A, mrow, envs, et, NT, dbias);
     __syncthreads();
     // DDPM step of transition k for the environments that still draft
     const int nblk = DE >> 2;

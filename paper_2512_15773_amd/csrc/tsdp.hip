@@ -182,7 +182,7 @@ void launch_draft(const FusedNet& n, const DraftIO& io_in, int A, hipStream_t s)
   auto kern = k_fused_draft<C>;
   DraftIO io = io_in;
   // FiLM vectors of up to 16 / RPT steps per in-kernel product, as many as LDS has room for
-  const int fixed = C::LDS_B + 2 * C::NT * A * 4 + 16 * (C::D + C::TT::PAD) * C::ES;
+  const int fixed = C::LDS_B + 2 * C::NT * A * 4 + 16 * (C::D + C::TT::PAD) * C::ES + n.L * 3 * C::D * 4;
   const int per_col = n.L * 4 * C::D * 4;
   io.mod_cols = C::RPT;
   for (int cols = 16; cols > C::RPT; cols /= 2)
