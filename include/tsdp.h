@@ -60,7 +60,7 @@ typedef struct {
   float   clip_val;
   int32_t B_max, K_max;   /* largest batch and largest per-environment draft count */
   uint64_t seed;          /* Philox4x32-10 key */
-  int32_t sampler;        /* 0 = DDPM posterior step, 1 = DDIM(eta) step (the paper names "DDPM or DDIM scheduler") */
+  int32_t sampler;        /* 0 = DDPM posterior step, 1 = DDIM(eta) step (Section 3.2, Draft Model Training, names both schedulers) */
   float   eta;            /* DDIM only, in (0,1]: sigma_t = eta sqrt((1-abar_{t-1})/(1-abar_t)) sqrt(1-abar_t/abar_{t-1});
                              eta = 0 has no Gaussian transition to test against and is rejected */
   int32_t bonus_row;      /* 1 = every running environment gets one more verify row, the state reached by its last
@@ -97,7 +97,7 @@ int tsdp_set_cond(tsdp_ctx* ctx, const float* d_cond, int B, void* stream);
 /* Drafter rollout (Section 3.2, Draft Generation Procedure).
  * in : d_x[B,H,A], d_t0[B], d_K[B] (clamped to 1..K_max, to 0..K_max with bonus_row; status bit 0 reports it),
  *      d_sigma_scale[B] (the scheduler's multiplier of sigma_t, must be > 0: it divides the mean difference in the
- *      acceptance ratio; values are not checked on the device),
+ *      acceptance ratio; status bit 2 reports a value that is not),
  *      d_env_id[B] global environment index used as Philox counter word (NULL = 0..B-1)
  * out: d_row_ptr[B+1], d_row_t[R_cap], d_row_env[R_cap], d_states[R_cap,H,A], d_eps_p[R_cap,H,A],
  *      d_xi[R_cap,H,A] (NULL = do not store the noise: tsdp_accept can regenerate it from the Philox counters),
@@ -115,7 +115,8 @@ int tsdp_draft(tsdp_ctx* ctx, int B, const float* d_x, const int32_t* d_t0, cons
 /* Batched verification (Section 3.2, Verification of Speculative Drafts): base-network noise
  * prediction for every row of a ragged batch.  R_cap bounds the launch (<= B_max*(K_max + bonus_row)); the live row
  * count is read on the device from d_row_ptr[B].  Row r uses timestep d_row_t[r] and the conditioning
- * of environment d_row_env[r] (index into the batch given to tsdp_set_cond).
+ * of environment d_row_env[r] (index into the batch given to tsdp_set_cond); both are range-checked on the device
+ * (clamped, reported by tsdp_status).  Rows at and beyond row_ptr[B] are neither read nor written.
  * out: d_eps_q[R_cap,H,A]. */
 int tsdp_verify(tsdp_ctx* ctx, int B, int R_cap, const int32_t* d_row_ptr, const int32_t* d_row_t,
                 const int32_t* d_row_env, const float* d_states, float* d_eps_q, void* stream);
@@ -142,7 +143,7 @@ int tsdp_round(tsdp_ctx* ctx, int B, float* d_x, int32_t* d_t, const int32_t* d_
                const float* d_sigma_scale, const int32_t* d_env_id,
                int32_t* d_n_accept, int32_t* d_n_advanced, void* stream);
 
-/* Deterministic threshold rule of Section 3.2 ("accept the draft if p_i >= lambda", p_i = min{1, exp(log alpha_i)},
+/* Deterministic threshold rule of Section 3.2 (a draft passes when p_i >= lambda, p_i = min{1, exp(log alpha_i)},
  * lambda in (0,1] chosen by the scheduler): the same arithmetic as tsdp_accept / tsdp_round with the comparison
  * log alpha >= log lambda[b] in place of the uniform draw.  d_lambda[B] holds one threshold per environment.  The
  * rule is not lossless with respect to the base model; the corrected sample is still the reflection of the first
@@ -156,8 +157,8 @@ int tsdp_round_threshold(tsdp_ctx* ctx, int B, float* d_x, int32_t* d_t, const i
                          const float* d_sigma_scale, const int32_t* d_env_id, const float* d_lambda,
                          int32_t* d_n_accept, int32_t* d_n_advanced, void* stream);
 
-/* Whole denoising chain: rounds repeat until every environment has finished (t = -1), as in the paper's inference
- * loop ("this process repeats iteratively until the denoising is complete", Section 1; Sections 3.2).  Rounds are
+/* Whole denoising chain: rounds repeat until every environment has finished (t = -1), the inference loop of
+ * Section 1 and Section 3.2.  Rounds are
  * enqueued back to back; every `check_every` rounds the number of running environments is read back (this call
  * synchronises the stream at those points) and the loop stops when it is zero or after `max_rounds`.  d_x and d_t
  * are updated in place; d_lambda selects the threshold rule (NULL = the lossless stochastic test).  Optional
@@ -167,8 +168,8 @@ int tsdp_chain(tsdp_ctx* ctx, int B, float* d_x, int32_t* d_t, const int32_t* d_
                const int32_t* d_env_id, const float* d_lambda, int max_rounds, int check_every,
                int32_t* d_tot_accept, int32_t* d_tot_drafts, int32_t* d_tot_rounds, int32_t* h_rounds, void* stream);
 
-/* The same loop with the scheduler's three-stage action (Section 3.3: sigma scale, acceptance threshold and draft
- * count "for the three distinct denoising stages"): d_K3, d_sigma_scale3 and d_lambda3 (NULL = stochastic test) are
+/* The same loop with the scheduler's three-stage action (Section 3.3, action space: one sigma scale, acceptance
+ * threshold and draft count per denoising stage): d_K3, d_sigma_scale3 and d_lambda3 (NULL = stochastic test) are
  * [B,3] tables; before every round each environment takes column 0 while t >= t_hi, column 1 while t_lo <= t < t_hi,
  * column 2 below t_lo (the paper does not give the stage boundaries: they are arguments, t_hi >= t_lo >= 0). */
 int tsdp_chain_staged(tsdp_ctx* ctx, int B, float* d_x, int32_t* d_t, const int32_t* d_K3, const float* d_sigma_scale3,
@@ -184,7 +185,10 @@ int tsdp_distill_loss(tsdp_ctx* ctx, int R, const int32_t* d_row_t, const float*
                       const float* d_eps_q, float lambda1, float lambda2, double* d_loss, void* stream);
 
 /* Synchronises `stream` and returns the device status word accumulated since the last call:
- * bit 0 = some K was outside 0..K_max (clamped), bit 1 = some t0 was >= T (treated as T-1). */
+ * bit 0 = some K was outside 0..K_max (clamped), bit 1 = some t0 was >= T (treated as T-1) or a row timestep given to
+ * tsdp_verify was outside 0..T-1 (clamped), bit 2 = some running environment had sigma_scale <= 0 or NaN (not
+ * corrected: the outputs of that environment are undefined, no memory is touched out of bounds), bit 3 = a row
+ * environment index given to tsdp_verify was outside the batch of tsdp_set_cond (clamped). */
 int tsdp_status(tsdp_ctx* ctx, void* stream, int32_t* h_status);
 
 /* Measurement aid.  tsdp_kernel_timing(ctx, 1) makes the following calls record a pair of HIP events on the

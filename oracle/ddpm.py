@@ -18,8 +18,8 @@ class Schedule:
     """
 
     def __init__(self, T, schedule, beta0=1e-4, beta1=0.02, round_fp32=True, sampler=0, eta=1.0):
-        """sampler 0: DDPM posterior (above).  sampler 1: DDIM(eta), eta in (0, 1] (the paper names "DDPM or DDIM
-        scheduler" without formulas; textbook DDIM): sigma_t = eta sqrt((1-abar_{t-1})/(1-abar_t)) sqrt(1-abar_t/abar_{t-1}),
+        """sampler 0: DDPM posterior (above).  sampler 1: DDIM(eta), eta in (0, 1] (Section 3.2, Draft Model Training, names
+        both schedulers without formulas; textbook DDIM): sigma_t = eta sqrt((1-abar_{t-1})/(1-abar_t)) sqrt(1-abar_t/abar_{t-1}),
         mean = sqrt(abar_{t-1}) x0_hat + sqrt(1-abar_{t-1}-sigma_t^2) eps.  Both are written as
         mu = c0 x0_hat + cx x + ce eps  (DDPM: ce = 0; DDIM: cx = 0)."""
         i = np.arange(T, dtype=np.float64)

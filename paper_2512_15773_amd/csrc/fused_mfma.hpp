@@ -42,7 +42,7 @@ struct FusedNet {
   FusedLayer layer[FUSED_MAX_LAYERS];
   int L;
   const float* tok_w; const float* tok_b; const float* pos;   // fp32 [D,A], [D], [H,D]
-  const void* head;            // [1][D/32][64] fragments of head_w padded to 16 rows
+  const void* head;            // [ceil(A/16)][D/32][64] fragments of head_w, rows padded to a multiple of 16
   const float* head_b;         // [A]
   const void* modw;            // [L*4D/16][D/32][64] FiLM projections of all layers (drafter kernel)
   const float* modb;           // [L*4D]
@@ -54,7 +54,6 @@ struct FusedNet {
   // cross-attention operands of every (env, layer, head), prepared by tsdp_set_cond:
   const bf16x8* kc;            // [B][L][HEADS][S/16][DH/32][64]  keys as 16x16x32 A fragments
   const bf16x4* vct;           // [B][L][HEADS][DH/16][S/16][64]  values transposed as 16x16x16 A fragments
-  long long* trace;            // tuning builds only: per-wave phase cycle totals of one workgroup, else null
 };
 
 struct FusedIO {               // batched verification
@@ -132,50 +131,16 @@ __device__ __forceinline__ bf16x4 to_bf16x4(f32x4 v) {
   return r;
 }
 
-// Tuning builds only.  TSDP_ABL is a bit mask of timing ablations that leave every address unchanged and make the
-// results meaningless: 1 weight fragments are not fetched, 2 LDS operands are not re-read, 4 no matrix instructions,
-// 8 no attention, 16 no GELU.  The product is built with 0.  The other switches below select between measured
-// alternatives and default to the faster one.
-#ifndef TSDP_ABL
-#define TSDP_ABL 0
-#endif
-// Optional phase timing for tuning builds (-DTSDP_TRACE): per-wave cycle totals per phase category.
-#ifdef TSDP_TRACE
-#ifndef TSDP_TRACE_BLOCK
-#define TSDP_TRACE_BLOCK 300
-#endif
-#define TSDP_TICK(cat) { const long long now_ = clock64(); tacc_[cat] += now_ - tprev_; tprev_ = now_; }
-#else
-#define TSDP_TICK(cat)
-#endif
-#ifndef TSDP_INFLIGHT_CLK
-#define TSDP_INFLIGHT_CLK 384  /* cycles of matrix work between the request of a weight fragment and its use */
-#endif
-#ifndef TSDP_LN_PREFETCH
-#define TSDP_LN_PREFETCH 1   /* request the FiLM vectors before the LayerNorm statistics are reduced */
-#endif
-#ifndef TSDP_GELU_SPLIT
-#define TSDP_GELU_SPLIT 1    /* pipelined MLP: half of a chunk's GELU runs under the previous down-projection */
-#endif
-#ifndef TSDP_MLP_PRIME
-#define TSDP_MLP_PRIME 1      /* pipelined MLP: each product requests the first weights of the next in its tail */
-#endif
-#ifndef TSDP_LN_STAGE
-#define TSDP_LN_STAGE 1      /* LayerNorm: cooperative fetch of the FiLM vectors, handed over through LDS */
-#endif
-#ifndef TSDP_XHEADMAJOR
-#define TSDP_XHEADMAJOR 1    /* cross-attention: a wave takes whole heads where they divide evenly over the waves */
-#endif
-#ifndef TSDP_PFMAX
-#define TSDP_PFMAX 4          /* upper limit of the weight ring's depth in k-steps */
-#endif
+// Measured choices of the kernels below (each was timed against its alternative on the full-size workloads).
+constexpr int INFLIGHT_CLK = 384;   // cycles of matrix work between the request of a weight fragment and its use
+constexpr int PF_MAX = 4;           // upper limit of the weight ring's depth in k-steps
 
 // Weight-streaming GEMM on fragments:  acc[mb][nb] += W(frag rows mf0+mb, k-steps ks0..ks0+NKS) . act^T,
 // act = LDS bf16 [token][stride].  Fully unrolled with compile-time trip counts.  The weight fragments of
 // k-step k+PF are requested from L2 before the MFMAs of k-step k issue and the LDS operands of k-step k+1
 // are read while those of k-step k are multiplied; scheduling barriers keep the compiler from collapsing
 // that software pipeline, and with no branch inside, the hardware wait counters stay exact.  PF is sized so
-// that about TSDP_INFLIGHT_CLK cycles of MFMA work separate a request from its use (one L2 round trip)
+// that about INFLIGHT_CLK cycles of MFMA work separate a request from its use (one L2 round trip)
 // without flooding the small vector L1.  issue() requests k-step 0 only and may be called a whole phase
 // early (before an epilogue, a barrier or the attention of the previous phase); run() does the rest.
 template <class TT, int MB, int NB, int NKS, int BD = 2>
@@ -183,8 +148,8 @@ struct FragGemm {
   typedef typename TT::frag frag;
   typedef typename TT::elem elem;
   static constexpr int STEP_CLK = MB * NB * 16;
-  static constexpr int PFW = (TSDP_INFLIGHT_CLK + STEP_CLK - 1) / STEP_CLK;
-  static constexpr int PF0 = PFW < 1 ? 1 : (PFW > TSDP_PFMAX ? TSDP_PFMAX : PFW);
+  static constexpr int PFW = (INFLIGHT_CLK + STEP_CLK - 1) / STEP_CLK;
+  static constexpr int PF0 = PFW < 1 ? 1 : (PFW > PF_MAX ? PF_MAX : PFW);
   static constexpr int PF = PF0 > NKS ? NKS : PF0;
   frag a[PF + 1][MB];
   const frag* wl;
@@ -242,21 +207,19 @@ struct FragGemm {
       if (k + PF < NKS) {
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
-          a[(k + PF) % (PF + 1)][mb] = (TSDP_ABL & 1) ? a[0][mb] : wl[((size_t)mb * kst + k + PF) * 64];
+          a[(k + PF) % (PF + 1)][mb] = wl[((size_t)mb * kst + k + PF) * 64];
       }
       if (BD == 2 && k + 1 < NKS) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
-          b[(k + 1) & 1][nb] = (TSDP_ABL & 2) ? b[0][nb] : *reinterpret_cast<const frag*>(al + nb * 16 * stride + (k + 1) * TT::KSTEP);
+          b[(k + 1) & 1][nb] = *reinterpret_cast<const frag*>(al + nb * 16 * stride + (k + 1) * TT::KSTEP);
       }
       __builtin_amdgcn_sched_barrier(0);
-      if (!(TSDP_ABL & 4)) {
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
+      for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-          for (int nb = 0; nb < NB; ++nb)
-            TT::mma(a[k % (PF + 1)][mb], b[k % BD][nb], acc[mb][nb]);
-      }
+        for (int nb = 0; nb < NB; ++nb)
+          TT::mma(a[k % (PF + 1)][mb], b[k % BD][nb], acc[mb][nb]);
       side(k);
       if (BD == 1 && k + 1 < NKS) {
 #pragma unroll
@@ -299,10 +262,7 @@ struct FusedCfg {
   static constexpr int U_B = NT * US * ES;
   static constexpr int XT_B = NT * 64 * 4;              // fp32 latent staging of the verify kernel (A <= 64)
   // two hidden-chunk buffers (one barrier per chunk instead of two) when a single workgroup owns the CU's LDS
-#ifndef TSDP_UDB_OK
-#define TSDP_UDB_OK 1
-#endif
-  static constexpr bool UDB = TSDP_UDB_OK && (NW == 8) && (ACT_B + 2 * U_B + 2 * NW * NT * 4 + 7 * D * 4 <= 160 * 1024) && (2 * U_B >= QKV_B);
+  static constexpr bool UDB = (NW == 8) && (ACT_B + 2 * U_B + 2 * NW * NT * 4 + 7 * D * 4 <= 160 * 1024) && (2 * U_B >= QKV_B);
   static constexpr int UU_B = UDB ? 2 * U_B : U_B;
   static constexpr int SCR0_B = QKV_B > UU_B ? QKV_B : UU_B;
   static constexpr int SCR_B = SCR0_B > XT_B ? SCR0_B : XT_B;
@@ -312,16 +272,8 @@ struct FusedCfg {
   static constexpr int WG_PER_CU = LDS_B <= 80 * 1024 && NW <= 4 ? 2 : 1;
   static constexpr bool LN_STAGE = true;                // FiLM vectors come from global memory: fetch them cooperatively
   static constexpr int WAVES_PER_SIMD = (WG_PER_CU * NW + 3) / 4;
-#ifdef TSDP_FORCE_BD
-  static constexpr int BD = TSDP_FORCE_BD;
-#else
   static constexpr int BD = WAVES_PER_SIMD >= 2 ? 1 : 2; // LDS operand buffers: a second wave on the SIMD hides LDS latency
-#endif
-#ifdef TSDP_FORCE_XPF
-  static constexpr bool XPF = TSDP_FORCE_XPF;
-#else
   static constexpr bool XPF = WAVES_PER_SIMD == 1;      // request the first weight fragments of a phase one phase early
-#endif
   static_assert(D % (16 * NW) == 0 && NT % 16 == 0 && H % 16 == 0 && NT % H == 0 && DH % KSTEP == 0, "shape");
   static_assert(D % KSTEP == 0 && CH % KSTEP == 0, "shape");
   static_assert((HEADS % HP) == 0 && (HP * 3 * DH) % (16 * NW) == 0 && (CM == 0 || (HPX * DH) % (16 * NW) == 0) &&
@@ -334,12 +286,9 @@ struct FusedCfg {
 // second wave hides latency; it therefore always prefetches across phases and double-buffers the LDS operands.
 template <class Base>
 struct DraftCfg : Base {
-#ifndef TSDP_DRAFT_XPF
-#define TSDP_DRAFT_XPF 1
-#endif
-  static constexpr bool XPF = TSDP_DRAFT_XPF;
+  static constexpr bool XPF = true;
   static constexpr bool LN_STAGE = false;               // the drafter's FiLM vectors are already in LDS (or a small table)
-  static constexpr int BD = TSDP_DRAFT_XPF ? 2 : Base::BD;
+  static constexpr int BD = 2;
 };
 
 // One forward pass for the tile.  xt: LDS fp32 [NT][A] latent tokens (may alias the scratch region: it is
@@ -379,7 +328,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   int l16 = lane & 15, lg = lane >> 4;
   // Makes the lane coordinates opaque at phase boundaries: addresses derived from them are then recomputed
   // where they are used instead of being hoisted out of the layer loop and spilled to scratch.
-#define TSDP_FENCE_IDS() asm volatile("" : "+v"(lane), "+v"(l16), "+v"(lg))
+#define FENCE_LANE_IDS() asm volatile("" : "+v"(lane), "+v"(l16), "+v"(lg))
 
   constexpr int BD = C::BD;
   constexpr bool XPF = C::XPF;
@@ -390,10 +339,6 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   typedef FragGemm<TT, MBH, NB, KC, BD> GD;             // MLP down, one hidden chunk of K
   typedef FragGemm<TT, (MBC > 0 ? MBC : 1), NB, KD, BD> GC;   // cross-attention query projection
 
-#ifdef TSDP_TRACE
-  long long tacc_[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-  long long tprev_ = clock64();
-#endif
   // ---- token embedding in fp32: h = tok_w x + tok_b + pos -------------------------------------------------
   f32x4 h[MBH][NB];
 #pragma unroll
@@ -422,10 +367,10 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   // writes LN(h) (1 + g) + b as bf16 into act; which = 0 (attention) / 2 (MLP) selects the FiLM pair, -1 = none.
   // Statistics: per-wave partial sums of x and x^2 (fp32) exchanged through LDS, one barrier.
   auto write_ln = [&](int layer, int which) {
-    TSDP_FENCE_IDS();
+    FENCE_LANE_IDS();
     // FiLM vectors of the tile's rows: requested first, so they arrive while the statistics are reduced
     // (only where they fit in 64 registers; otherwise they are read fragment row by fragment row)
-    constexpr bool LNPF = TSDP_LN_PREFETCH && MBH * RPT * 2 <= 16;
+    constexpr bool LNPF = MBH * RPT * 2 <= 16;
     constexpr int FR = LNPF ? RPT : 1;
     f32x4 fg[MBH][FR], fb[MBH][FR];
     if (LNPF && which >= 0) {
@@ -441,7 +386,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
     // Otherwise the wave fetches its block [row][g|b][its features] cooperatively, 16 distinct bytes per lane and
     // request (read fragment by fragment every lane would re-read what 15 others read, in MBH dependent batches),
     // and passes it to its lanes through the scratch region, which is free between the two barriers below.
-    constexpr bool LNST = !LNPF && TSDP_LN_STAGE && C::LN_STAGE && (NW * RPT * 2 * MBH * 16 * 4 <= C::SCR_B);
+    constexpr bool LNST = !LNPF && C::LN_STAGE && (NW * RPT * 2 * MBH * 16 * 4 <= C::SCR_B);
     constexpr int CHK = RPT * 2 * MBH * 4, CPL = (CHK + 63) / 64;
     f32x4 st[LNST ? CPL : 1];
     if (LNST && which >= 0) {
@@ -646,9 +591,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   for (int layer = 0; layer < net.L; ++layer) {
     const FusedLayer& W = net.layer[layer];
     // ================= self-attention block =================
-    TSDP_TICK(11)
     write_ln(layer, 0);
-    TSDP_TICK(0)
     if constexpr (BSTAGE) {
       // The layer's biases that are added outside a product's own latency shadow go to LDS: the MLP's GELU runs inside
       // the products, where registers are scarce and a global load would queue behind the weight requests, and a
@@ -664,7 +607,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       }
     }
     for (int g = 0; g < NG; ++g) {
-      TSDP_FENCE_IDS();
+      FENCE_LANE_IDS();
       GO go;
       {
         f32x4 acc[MBQ][NB];
@@ -677,10 +620,8 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         }
         if (!XPF) gq.issue(W.qkv, KD, g * (HP * 3 * DH / 16) + wave, 0, lane, NW);
         gq.run(act, AS, acc, lane);
-        TSDP_TICK(1)
         if (XPF) go.issue(W.o, KD, wave * MBH, g * HP * KH, lane);      // needed only after the attention
         if (g > 0) __syncthreads();                     // previous group's O-projection has read qbuf
-        TSDP_TICK(2)
 #pragma unroll
         for (int mb = 0; mb < MBQ; ++mb) {
           const int lr = (mb * NW + wave) * 16;         // first logical row of this fragment inside the group (rows are
@@ -702,19 +643,13 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
           }
         }
       }
-      TSDP_TICK(3)
       __syncthreads();
-      TSDP_TICK(2)
-      if (!(TSDP_ABL & 8))
-        for (int task = wave; task < RPT * HP * NKF; task += NW)
+      for (int task = wave; task < RPT * HP * NKF; task += NW)
           self_attention((task / NKF) % RPT, task / (NKF * RPT), task % NKF);
-      TSDP_TICK(4)
       __syncthreads();
-      TSDP_TICK(2)
       if (XPF && g + 1 < NG) gq.issue(W.qkv, KD, (g + 1) * (HP * 3 * DH / 16) + wave, 0, lane, NW);
       if (!XPF) go.issue(W.o, KD, wave * MBH, g * HP * KH, lane);
       go.run(qbuf, QTS, h, lane);                        // one product over the heads of the group
-      TSDP_TICK(5)
     }
     add_bias_h(W.o_b, layer, 0);
     // ================= cross-attention block (observation tokens) =================
@@ -728,18 +663,16 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       typedef FragGemm<TT, MBH, NB, HPX * KH, BD> GOX;
       GC gc;
       if (XPF) gc.issue(W.cq, KD, wave * MBC, 0, lane);
-      TSDP_TICK(11)
       write_ln(layer, -1);                               // its barriers order the O-projection reads before qbuf writes
-      TSDP_TICK(0)
       for (int g = 0; g < NGX; ++g) {
-        TSDP_FENCE_IDS();
+        FENCE_LANE_IDS();
         GOX go;
         bf16x8 ka[KHc][SFc];
         bf16x4 va[DH / 16][SFc];
         // Task i of a wave -> (row, head of the phase, query fragment).  When the heads of a phase divide evenly over
         // the waves, a wave takes whole heads: the tasks of one head (its rows and query fragments) share the keys /
         // values as long as their rows belong to the same environment, so they are fetched once, not once per task.
-        constexpr bool HEADMAJOR = TSDP_XHEADMAJOR && (HPX % NW == 0);
+        constexpr bool HEADMAJOR = HPX % NW == 0;
         constexpr int TPH = RPT * NKF;                  // tasks per head
         auto task_of = [&](int i) { return HEADMAJOR ? ((wave + (i / TPH) * NW) * TPH + i % TPH) : wave + i * NW; };
         auto task_row = [&](int task) { return (task / NKF) % RPT; };
@@ -761,10 +694,8 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
           }
           if (!XPF) gc.issue(W.cq, KD, g * (HPX * DH / 16) + wave * MBC, 0, lane);
           gc.run(act, AS, acc, lane);
-          TSDP_TICK(1)
           if (XPF) go.issue(W.co, KD, wave * MBH, g * HPX * KH, lane);
           if (g > 0) __syncthreads();
-          TSDP_TICK(2)
 #pragma unroll
           for (int mb = 0; mb < MBC; ++mb) {
             const int c0 = (wave * MBC + mb) * 16 + lg * 4;      // column = head-of-phase * DH + feature
@@ -780,36 +711,29 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
           cross_load_k(task_row(task_of(0)), layer, g * HPX + task_head(task_of(0)), ka);
           cross_load_v(task_row(task_of(0)), layer, g * HPX + task_head(task_of(0)), va);
         }
-        TSDP_TICK(3)
         __syncthreads();
-        TSDP_TICK(2)
-        if (!(TSDP_ABL & 8)) {
 #pragma unroll
-          for (int i = 0; i < TPW; ++i) {
-            const int task = task_of(i), nxt = task_of(i + 1);
-            const bool more = i + 1 < TPW && nxt < NTASK && task_reload(i + 1);
-            if (task < NTASK) {
-              __bf16* qp = reinterpret_cast<__bf16*>(qbuf) + (task_row(task) * H + (task % NKF) * 16) * QXS + task_head(task) * DH;
-              bf16x4 p[SFc];
-              // scheduling fences: the requests must not be moved ahead of the products that free their registers
-              cross_scores(qp, QXS, ka, p);
-              __builtin_amdgcn_sched_barrier(0);
-              if (more) cross_load_k(task_row(nxt), layer, g * HPX + task_head(nxt), ka);
-              __builtin_amdgcn_sched_barrier(0);
-              cross_pv(qp, QXS, p, va);
-              __builtin_amdgcn_sched_barrier(0);
-              if (more) cross_load_v(task_row(nxt), layer, g * HPX + task_head(nxt), va);
-              __builtin_amdgcn_sched_barrier(0);
-            }
+        for (int i = 0; i < TPW; ++i) {
+          const int task = task_of(i), nxt = task_of(i + 1);
+          const bool more = i + 1 < TPW && nxt < NTASK && task_reload(i + 1);
+          if (task < NTASK) {
+            __bf16* qp = reinterpret_cast<__bf16*>(qbuf) + (task_row(task) * H + (task % NKF) * 16) * QXS + task_head(task) * DH;
+            bf16x4 p[SFc];
+            // scheduling fences: the requests must not be moved ahead of the products that free their registers
+            cross_scores(qp, QXS, ka, p);
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) cross_load_k(task_row(nxt), layer, g * HPX + task_head(nxt), ka);
+            __builtin_amdgcn_sched_barrier(0);
+            cross_pv(qp, QXS, p, va);
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) cross_load_v(task_row(nxt), layer, g * HPX + task_head(nxt), va);
+            __builtin_amdgcn_sched_barrier(0);
           }
         }
-        TSDP_TICK(10)
         __syncthreads();
-        TSDP_TICK(2)
         if (XPF && g + 1 < NGX) gc.issue(W.cq, KD, (g + 1) * (HPX * DH / 16) + wave * MBC, 0, lane);
         if (!XPF) go.issue(W.co, KD, wave * MBH, g * HPX * KH, lane);
         go.run(qbuf, QXS, h, lane);
-        TSDP_TICK(5)
       }
       add_bias_h(W.co_b, layer, 1);
     }
@@ -819,15 +743,13 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       // matrix pipeline leaves free.  Its first half is spread over the k-steps of the down-projection of chunk
       // c-1, its second half over those of the up-projection of chunk c+1 (all of it in one product would need
       // more vector slots than that product leaves); one barrier per chunk.
-      TSDP_TICK(11)
       write_ln(layer, 2);
-      TSDP_TICK(0)
       f32x4 accA[MBU][NB], accB[MBU][NB];
       constexpr int PARTS = MBU * NB;
-      constexpr int HALF = TSDP_GELU_SPLIT ? PARTS / 2 : 0;   // parts done under the previous down-projection
+      constexpr int HALF = PARTS / 2;                         // parts done under the previous down-projection
       GU gu;
       GD gd;
-      constexpr bool PRIME = TSDP_MLP_PRIME && KD >= GD::PF && KC >= GU::PF;
+      constexpr bool PRIME = KD >= GD::PF && KC >= GU::PF;
       typedef std::integral_constant<int, GU::PF> UFULL;
       typedef std::integral_constant<int, GD::PF> DFULL;
       typedef std::integral_constant<int, 1> ONE;
@@ -843,7 +765,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         const int f0 = (wave * MBU + mb) * 16 + lg * 4;
         f32x4 v = acc[mb][nb] + *reinterpret_cast<const f32x4*>(upb + c * CH + f0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = (TSDP_ABL & 16) ? v[i] : gelu_fast(v[i]);
+        for (int i = 0; i < 4; ++i) v[i] = gelu_fast(v[i]);
         *reinterpret_cast<vec4*>(ubuf + (c & 1) * NT * US + (nb * 16 + l16) * US + f0) = TT::cvt(v);
       };
       // chunk c: accumulator `cur` holds its pre-activations, parts [0, HALF) of its GELU are already in the hidden
@@ -853,7 +775,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
       // it re-requests the last chunk's, which are simply not used).
       auto chunk = [&](int c, f32x4 (&cur)[MBU][NB], f32x4 (&nxt)[MBU][NB], auto HASNEXT, auto UPRIMED) {
         constexpr bool NEXT = decltype(HASNEXT)::value, UP = decltype(UPRIMED)::value && PRIME;
-        TSDP_FENCE_IDS();
+        FENCE_LANE_IDS();
         if (PRIME) gd.prime_begin(W.dn, KM, wave * MBH, c * (KC), lane);
         if constexpr (NEXT) {
           zero(nxt);
@@ -874,9 +796,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
 #pragma unroll
           for (int idx = HALF; idx < PARTS; ++idx) gelu_part(c, cur, idx);
         }
-        TSDP_TICK(6)
         __syncthreads();
-        TSDP_TICK(7)
         if (!PRIME) gd.issue(W.dn, KM, wave * MBH, c * (KC), lane);
         if constexpr (NEXT) {
           const int c2 = c + 2 < NC ? c + 2 : NC - 1;
@@ -893,14 +813,12 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
           if constexpr (PRIME) gd.run(ubuf + (c & 1) * NT * US, US, h, lane, typename GD::NoSide{}, DFULL{});
           else gd.run(ubuf + (c & 1) * NT * US, US, h, lane);
         }
-        TSDP_TICK(9)
       };
       zero(accA);
       gu.issue(W.up, KD, wave * MBU, 0, lane);
       gu.run(act, AS, accA, lane);
 #pragma unroll
       for (int idx = 0; idx < HALF; ++idx) gelu_part(0, accA, idx);
-      TSDP_TICK(6)
       // one loop body: the pre-activations of the next chunk move into the registers of the current one
       auto rotate = [&]() {
 #pragma unroll
@@ -918,11 +836,9 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
     } else {
     GU gu;
     if (XPF) gu.issue(W.up, KD, wave * MBU, 0, lane);
-    TSDP_TICK(11)
     write_ln(layer, 2);                                  // its barriers also order the projection reads before ubuf writes
-    TSDP_TICK(0)
     for (int c = 0; c < NC; ++c) {
-      TSDP_FENCE_IDS();
+      FENCE_LANE_IDS();
       GD gd;
       {
         f32x4 acc[MBU][NB];
@@ -935,12 +851,10 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         }
         if (!XPF) gu.issue(W.up, KD, c * (CH / 16) + wave * MBU, 0, lane);
         gu.run(act, AS, acc, lane);
-        TSDP_TICK(6)
         if (XPF) gd.issue(W.dn, KM, wave * MBH, c * (KC), lane);
         // single buffer: the previous chunk's down-projection has read ubuf; double buffer: the buffer written
         // now was last read two chunks ago, and every wave has passed a barrier since
         if (c > 0 && !C::UDB) __syncthreads();
-        TSDP_TICK(7)
         elem* ub = ubuf + (C::UDB ? (c & 1) * NT * US : 0);
 #pragma unroll
         for (int mb = 0; mb < MBU; ++mb) {
@@ -949,14 +863,12 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
           for (int nb = 0; nb < NB; ++nb) {
             f32x4 v = acc[mb][nb] + bias[mb];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) v[i] = (TSDP_ABL & 16) ? v[i] : gelu_fast(v[i]);
+            for (int i = 0; i < 4; ++i) v[i] = gelu_fast(v[i]);
             *reinterpret_cast<vec4*>(ub + (nb * 16 + l16) * US + f0) = TT::cvt(v);
           }
         }
       }
-      TSDP_TICK(8)
       __syncthreads();
-      TSDP_TICK(7)
       if (XPF) {
         if (c + 1 < NC) gu.issue(W.up, KD, (c + 1) * (CH / 16) + wave * MBU, 0, lane);
         else if (layer + 1 < net.L) gq.issue(net.layer[layer + 1].qkv, KD, wave, 0, lane, NW);
@@ -964,7 +876,6 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         gd.issue(W.dn, KM, wave * MBH, c * (KC), lane);
       }
       gd.run(ubuf + (C::UDB ? (c & 1) * NT * US : 0), US, h, lane);
-      TSDP_TICK(9)
     }
     }
     add_bias_h(W.dn_b, layer, 2);
@@ -974,32 +885,30 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   write_ln(0, -1);
   {
     constexpr int NBW = (NB + NW - 1) / NW;             // token fragments per wave
-    f32x4 e[1][NBW];
-#pragma unroll
-    for (int j = 0; j < NBW; ++j) e[0][j] = f32x4{0, 0, 0, 0};
     const int nb0 = wave * NBW;
     if (nb0 < NB) {
-      FragGemm<TT, 1, NBW, KD> gh;
-      gh.issue(net.head, KD, 0, 0, lane);
-      gh.run(act + nb0 * 16 * AS, AS, e, lane);
+      // the head's A output rows are packed as ceil(A/16) fragment rows (zero rows pad the last one)
+      for (int hf = 0; hf * 16 < A; ++hf) {
+        f32x4 e[1][NBW];
 #pragma unroll
-      for (int j = 0; j < NBW; ++j) {
-        const int t = (nb0 + j) * 16 + l16;
-        if (nb0 + j < NB && t < ntok_live) {
+        for (int j = 0; j < NBW; ++j) e[0][j] = f32x4{0, 0, 0, 0};
+        FragGemm<TT, 1, NBW, KD> gh;
+        gh.issue(net.head, KD, hf, 0, lane);
+        gh.run(act + nb0 * 16 * AS, AS, e, lane);
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int a = lg * 4 + i;
-            if (a < A) eo[t * A + a] = e[0][j][i] + net.head_b[a];
+        for (int j = 0; j < NBW; ++j) {
+          const int t = (nb0 + j) * 16 + l16;
+          if (nb0 + j < NB && t < ntok_live) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const int a = hf * 16 + lg * 4 + i;
+              if (a < A) eo[t * A + a] = e[0][j][i] + net.head_b[a];
+            }
           }
         }
       }
     }
   }
-#ifdef TSDP_TRACE
-  TSDP_TICK(10)
-  if (blockIdx.x == TSDP_TRACE_BLOCK && lane == 0 && net.trace && wave < 8)
-    for (int i = 0; i < 12; ++i) net.trace[wave * 12 + i] = tacc_[i];
-#endif
 }
 
 // Batched verification: tile b of the grid takes rows b*RPT .. of the ragged batch.

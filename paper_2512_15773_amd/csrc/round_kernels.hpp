@@ -15,6 +15,7 @@ struct SchedTables {          // device pointers, fp32[T] each; posterior mean =
 // row_ptr[B+1].  K is clamped to 1..K_max (0..K_max with the bonus row, where K = 0 is a plain base step).
 // Single workgroup of 1024 threads, chunks of 1024 environments.
 __global__ __launch_bounds__(1024) void k_plan(const int32_t* __restrict__ t0, const int32_t* __restrict__ K,
+                                               const float* __restrict__ sigma_scale,
                                                int B, int K_max, int T, int bonus, int32_t* __restrict__ K_eff,
                                                int32_t* __restrict__ row_ptr, int32_t* __restrict__ status) {
   __shared__ int32_t part[1024];
@@ -29,6 +30,7 @@ __global__ __launch_bounds__(1024) void k_plan(const int32_t* __restrict__ t0, c
       const int k_min = bonus ? 0 : 1;
       if (k < k_min || k > K_max) { atomicOr(status, 1); k = k < k_min ? k_min : K_max; }
       if (t >= T) { atomicOr(status, 2); t = T - 1; }
+      if (t >= 0 && !(sigma_scale[b] > 0.0f)) atomicOr(status, 4);   // divides the mean difference: reported, not corrected
       const int ke = t < 0 ? 0 : (k < t ? k : t);
       K_eff[b] = ke;
       n = t < 0 ? 0 : (bonus ? ke + 1 : (ke > 1 ? ke : 1));
@@ -47,6 +49,21 @@ __global__ __launch_bounds__(1024) void k_plan(const int32_t* __restrict__ t0, c
     __syncthreads();
   }
   if (threadIdx.x == 0) row_ptr[B] = carry;
+}
+
+// Range check of a caller-supplied row table (tsdp_verify): copies with the timestep clamped to 0..T-1 and the
+// environment index to 0..n_env-1; status bit 1 / bit 3 report a clamp.
+__global__ void k_check_rows(const int32_t* __restrict__ d_R, int R_cap, const int32_t* __restrict__ row_t,
+                             const int32_t* __restrict__ row_env, int T, int n_env, int32_t* __restrict__ row_t_out,
+                             int32_t* __restrict__ row_env_out, int32_t* __restrict__ status) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  const int R = min(*d_R, R_cap);
+  if (r >= R) return;
+  int t = row_t[r], e = row_env[r];
+  if (t < 0 || t >= T) { atomicOr(status, 2); t = t < 0 ? 0 : T - 1; }
+  if (e < 0 || e >= n_env) { atomicOr(status, 8); e = e < 0 ? 0 : n_env - 1; }
+  row_t_out[r] = t;
+  row_env_out[r] = e;
 }
 
 // Fills row_t / row_env, copies x into y (the rollout state), and for t0 = 0 environments writes the

@@ -42,12 +42,12 @@ struct Net {
   // fused bf16 MFMA path (bf16 networks of supported shape)
   bool fused = false;
   FusedNet fnet;
-  void (*fused_verify)(const FusedNet&, const FusedIO&, int A, int R_cap, hipStream_t) = nullptr;
-  void (*fused_verify_few)(const FusedNet&, const FusedIO&, int A, int R_cap, hipStream_t) = nullptr;
+  hipError_t (*fused_verify)(const FusedNet&, const FusedIO&, int A, int R_cap, hipStream_t) = nullptr;
+  hipError_t (*fused_verify_few)(const FusedNet&, const FusedIO&, int A, int R_cap, hipStream_t) = nullptr;
   int verify_rpt = 1;
   void (*fused_mod)(const FusedNet&, const int32_t*, int, const int32_t*, int, const int32_t*, int, float*, hipStream_t) = nullptr;
-  void (*fused_draft_small)(const FusedNet&, const DraftIO&, int A, hipStream_t) = nullptr;   // few environments per workgroup
-  void (*fused_draft_big)(const FusedNet&, const DraftIO&, int A, hipStream_t) = nullptr;     // many environments per workgroup
+  hipError_t (*fused_draft_small)(const FusedNet&, const DraftIO&, int A, hipStream_t) = nullptr;   // few environments per workgroup
+  hipError_t (*fused_draft_big)(const FusedNet&, const DraftIO&, int A, hipStream_t) = nullptr;     // many environments per workgroup
   int draft_rpt_small = 0, draft_rpt_big = 0;
   uint16_t* kc_pk = nullptr;    // fragment-ordered bf16 keys / transposed values of every (env, layer, head)
   uint16_t* vct_pk = nullptr;
@@ -75,6 +75,7 @@ struct tsdp_ctx {
   bool ws_ready = false;
   float *h = nullptr, *a = nullptr, *qkv = nullptr, *ao = nullptr, *u = nullptr, *sg = nullptr, *mod = nullptr;
   float* eps_tmp = nullptr;     // [B_max, D] drafter output of the current step
+  int32_t *row_t_chk = nullptr, *row_env_chk = nullptr;   // [rows] range-checked copy of a caller's row table (tsdp_verify)
   int32_t* Bconst = nullptr;    // device ints holding B for row-count reads of dense (per-env) launches
   // round-owned ragged buffers (lazy)
   bool rb_ready = false;
@@ -166,19 +167,21 @@ void pack_frags(std::vector<uint8_t>& out, bool f32, const float* W, int K, int 
 }
 
 template <class C>
-void launch_verify(const FusedNet& n, const FusedIO& io, int A, int R_cap, hipStream_t s) {
+hipError_t launch_verify(const FusedNet& n, const FusedIO& io, int A, int R_cap, hipStream_t s) {
   auto kern = k_fused_forward<C>;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_B);
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_B);
+    if (e != hipSuccess) return e;
     attr_set = true;
   }
   const int tiles = (R_cap + C::RPT - 1) / C::RPT;
   hipLaunchKernelGGL(kern, dim3(tiles), dim3(C::THREADS), C::LDS_B, s, n, io, A);
+  return hipSuccess;
 }
 
 template <class C>
-void launch_draft(const FusedNet& n, const DraftIO& io_in, int A, hipStream_t s) {
+hipError_t launch_draft(const FusedNet& n, const DraftIO& io_in, int A, hipStream_t s) {
   auto kern = k_fused_draft<C>;
   DraftIO io = io_in;
   // FiLM vectors of up to 16 / RPT steps per in-kernel product, as many as LDS has room for
@@ -190,11 +193,13 @@ void launch_draft(const FusedNet& n, const DraftIO& io_in, int A, hipStream_t s)
   const int lds = fixed + io.mod_cols * per_col;
   static int attr_lds = 0;
   if (lds > attr_lds) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
     attr_lds = lds;
   }
   const int tiles = (io.B + C::RPT - 1) / C::RPT;
   hipLaunchKernelGGL(kern, dim3(tiles), dim3(C::THREADS), lds, s, n, io, A);
+  return hipSuccess;
 }
 
 template <int D>
@@ -210,36 +215,25 @@ void launch_mod(const FusedNet& n, const int32_t* t_arr, int t_sub, const int32_
 
 struct FusedKernels {
   // variant for batches of at most one tile per CU: one 8-wave workgroup per CU instead of two 4-wave ones
-  void (*verify_few)(const FusedNet&, const FusedIO&, int, int, hipStream_t) = nullptr;
+  hipError_t (*verify_few)(const FusedNet&, const FusedIO&, int, int, hipStream_t) = nullptr;
   int rpt_verify = 0;
   void (*mod)(const FusedNet&, const int32_t*, int, const int32_t*, int, const int32_t*, int, float*, hipStream_t) = nullptr;
-  void (*verify)(const FusedNet&, const FusedIO&, int, int, hipStream_t) = nullptr;
-  void (*draft_small)(const FusedNet&, const DraftIO&, int, hipStream_t) = nullptr;
-  void (*draft_big)(const FusedNet&, const DraftIO&, int, hipStream_t) = nullptr;
+  hipError_t (*verify)(const FusedNet&, const FusedIO&, int, int, hipStream_t) = nullptr;
+  hipError_t (*draft_small)(const FusedNet&, const DraftIO&, int, hipStream_t) = nullptr;
+  hipError_t (*draft_big)(const FusedNet&, const DraftIO&, int, hipStream_t) = nullptr;
   int rpt_small = 0, rpt_big = 0;
 };
 
-#ifndef TSDP_NWS128
-#define TSDP_NWS128 8      /* waves of the one-environment drafter tile, d = 128 */
-#endif
-#ifndef TSDP_NWS256X
-#define TSDP_NWS256X 8     /* waves and heads per phase of the one-environment drafter tile, d = 256 with cross-attention */
-#define TSDP_HPS256X 4
-#endif
-#ifndef TSDP_F256_NW
-#define TSDP_F256_NW 8     /* fp32 d = 256 verify kernel: waves, heads per phase, hidden chunk */
-#define TSDP_F256_HP 2
-#define TSDP_F256_CH 256
-#endif
-#ifndef TSDP_FEW_TILES
-#define TSDP_FEW_TILES 288 /* up to this many tiles the 8-wave verify variant (one workgroup per CU) is used */
-#endif
-#ifndef TSDP_V512_HPX
-#define TSDP_V512_HPX 8    /* heads per cross-attention phase of the d = 512 verify kernel */
-#endif
-#ifndef TSDP_V512_CH
-#define TSDP_V512_CH 256   /* hidden-chunk width of the d = 512 verify kernel */
-#endif
+// Measured tile choices of the compiled shapes.
+constexpr int NWS128 = 8;        // waves of the one-environment drafter tile, d = 128
+constexpr int NWS256X = 8;       // waves and heads per phase of the one-environment drafter tile, d = 256 with cross-attention
+constexpr int HPS256X = 4;
+constexpr int F256_NW = 8;       // fp32 d = 256 verify kernel: waves, heads per phase, hidden chunk
+constexpr int F256_HP = 2;
+constexpr int F256_CH = 256;
+constexpr int FEW_TILES = 288;   // up to this many tiles the 8-wave verify variant (one workgroup per CU) is used
+constexpr int V512_HPX = 8;      // heads per cross-attention phase of the d = 512 verify kernel
+constexpr int V512_CH = 256;     // hidden-chunk width of the d = 512 verify kernel
 // shapes with compiled fused kernels
 bool find_fused(int dtype, int D, int H, int heads, int cm, int S, int mlp_ratio, int L, FusedKernels& k) {
   if (mlp_ratio != 4 || L > FUSED_MAX_LAYERS) return false;
@@ -261,13 +255,13 @@ bool find_fused(int dtype, int D, int H, int heads, int cm, int S, int mlp_ratio
     k.verify_few = launch_verify<FusedCfg<TBF16, 384, 64, 16, 6, 0, 256, 0, 2, 8>>;
   TSDP_SHAPE(TBF16, 1, 256, 16, 4, 0, 0, 64, 128, 1, 4, 1, 16, 128, 1, 4, 64, 128, 1, 4)
   TSDP_SHAPE(TBF16, 1, 384, 16, 6, 0, 0, 64, 192, 1, 4, 1, 16, 128, 1, 4, 64, 128, 1, 4)
-  TSDP_SHAPE(TBF16, 1, 128, 16, 4, 0, 0, 128, 128, 2, 4, 2, 16, 512, 4, TSDP_NWS128, 64, 128, 2, 4)
+  TSDP_SHAPE(TBF16, 1, 128, 16, 4, 0, 0, 128, 128, 2, 4, 2, 16, 512, 4, NWS128, 64, 128, 2, 4)
   TSDP_SHAPE(TBF16, 1, 192, 16, 6, 0, 0, 128, 128, 2, 4, 2, 16, 768, 6, 4, 64, 128, 2, 4)
-  TSDP_SHAPE(TBF16, 1, 512, 32, 8, 1, 64, 64, TSDP_V512_CH, 2, 8, TSDP_V512_HPX, 32, 128, 1, 4, 64, 128, 1, 4)
-  TSDP_SHAPE(TBF16, 1, 256, 32, 8, 1, 64, 64, 256, 2, 4, 2, 32, 128, TSDP_HPS256X, TSDP_NWS256X, 64, 128, 2, 4)
+  TSDP_SHAPE(TBF16, 1, 512, 32, 8, 1, 64, 64, V512_CH, 2, 8, V512_HPX, 32, 128, 1, 4, 64, 128, 1, 4)
+  TSDP_SHAPE(TBF16, 1, 256, 32, 8, 1, 64, 64, 256, 2, 4, 2, 32, 128, HPS256X, NWS256X, 64, 128, 2, 4)
   // fp32 networks on the fp32 matrix cores: one row (16 tokens) per workgroup, weights streamed per workgroup
-  TSDP_SHAPE(TF32, 0, 256, 16, 4, 0, 0, 16, TSDP_F256_CH, TSDP_F256_HP, TSDP_F256_NW, TSDP_F256_HP, 16, 128, 1, 4, 16, 128, 1, 4)
-  TSDP_SHAPE(TF32, 0, 128, 16, 4, 0, 0, 16, 128, 2, 4, 2, 16, 512, 4, TSDP_NWS128, 16, 512, 4, 4)
+  TSDP_SHAPE(TF32, 0, 256, 16, 4, 0, 0, 16, F256_CH, F256_HP, F256_NW, F256_HP, 16, 128, 1, 4, 16, 128, 1, 4)
+  TSDP_SHAPE(TF32, 0, 128, 16, 4, 0, 0, 16, 128, 2, 4, 2, 16, 512, 4, NWS128, 16, 512, 4, 4)
   TSDP_SHAPE(TF32, 0, 64, 16, 2, 0, 0, 16, 64, 2, 4, 2, 16, 64, 2, 4, 16, 64, 2, 4)
   TSDP_SHAPE(TF32, 0, 32, 16, 2, 0, 0, 16, 32, 2, 2, 2, 16, 128, 2, 2, 16, 128, 2, 2)
 #undef TSDP_SHAPE
@@ -336,7 +330,7 @@ int build_fused(tsdp_ctx* c, Net& n, const std::vector<float>& w, const std::vec
     }
   }
   const size_t head_off = pk.size();
-  pack_frags(pk, f32, &w[n.head_w], d, 16, [&](int r) { return r < cf.A ? r : -1; });
+  pack_frags(pk, f32, &w[n.head_w], d, (cf.A + 15) / 16 * 16, [&](int r) { return r < cf.A ? r : -1; });
   const size_t mod_off = pk.size();
   pack_frags(pk, f32, modw_cat.data(), d, L * 4 * d, ident);
   uint8_t* dpk = nullptr;
@@ -373,9 +367,6 @@ int build_fused(tsdp_ctx* c, Net& n, const std::vector<float>& w, const std::vec
     f.kc = reinterpret_cast<const bf16x8*>(n.kc_pk);
     f.vct = reinterpret_cast<const bf16x4*>(n.vct_pk);
   }
-#ifdef TSDP_TRACE
-  if ((rc = dev_alloc(c, &f.trace, 8 * 12))) return rc;
-#endif
   n.fused = true;
   n.fused_verify = fk.verify;
   n.fused_verify_few = fk.verify_few;
@@ -437,11 +428,11 @@ void forward_f32(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int3
 }
 
 // eps[R,H,A] = network(x_rows; t, cond): fused bf16 MFMA kernel where the shape has one, fp32 operators otherwise.
-void forward(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t* d_R, const int32_t* t_arr,
-             int t_sub, const int32_t* env_arr, float* eps_out, hipStream_t s) {
+int forward(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t* d_R, const int32_t* t_arr,
+            int t_sub, const int32_t* env_arr, float* eps_out, hipStream_t s) {
   if (!n.fused) {
     forward_f32(c, n, x_rows, R_cap, d_R, t_arr, t_sub, env_arr, eps_out, s);
-    return;
+    return TSDP_OK;
   }
   const tsdp_config& cf = c->cfg;
   if (n.fnet.modtab) {
@@ -457,9 +448,10 @@ void forward(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t*
   io.x_rows = x_rows; io.mod = c->mod; io.row_t = t_arr; io.t_sub = t_sub; io.T = cf.T; io.row_env = env_arr; io.d_R = d_R; io.R_cap = R_cap; io.eps_out = eps_out;
   const int stage = (&n == &c->net[0]) ? 1 : -1;          // only the base network's forward is the verify stage
   if (stage == 1) tick(c, 1, 0, s);
-  const bool few = n.fused_verify_few && (R_cap + n.verify_rpt - 1) / n.verify_rpt <= TSDP_FEW_TILES;
-  (few ? n.fused_verify_few : n.fused_verify)(n.fnet, io, cf.A, R_cap, s);
+  const bool few = n.fused_verify_few && (R_cap + n.verify_rpt - 1) / n.verify_rpt <= FEW_TILES;
+  HIPCHK(c, (few ? n.fused_verify_few : n.fused_verify)(n.fnet, io, cf.A, R_cap, s));
   if (stage == 1) tick(c, 1, 1, s);
+  return TSDP_OK;
 }
 
 // dynamic LDS of the persistent drafter kernel for `rpt` environments per workgroup (mirrors launch_draft)
@@ -491,6 +483,8 @@ int ensure_workspace(tsdp_ctx* c) {
   if ((rc = dev_alloc(c, &c->sg, Rw * dmax))) return rc;
   if ((rc = dev_alloc(c, &c->mod, Rw * lmax * 4 * dmax))) return rc;
   if ((rc = dev_alloc(c, &c->eps_tmp, (size_t)cf.B_max * c->D))) return rc;
+  if ((rc = dev_alloc(c, &c->row_t_chk, Rw))) return rc;
+  if ((rc = dev_alloc(c, &c->row_env_chk, Rw))) return rc;
   c->ws_ready = true;
   return TSDP_OK;
 }
@@ -742,8 +736,8 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
   hipStream_t s = (hipStream_t)stream;
   const tsdp_config& cf = c->cfg;
   const int D = c->D;
-  hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, d_t0, d_K, B, cf.K_max, cf.T, cf.bonus_row, c->K_eff, d_row_ptr,
-                     c->status);
+  hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, d_t0, d_K, d_sigma_scale, B, cf.K_max, cf.T, cf.bonus_row, c->K_eff,
+                     d_row_ptr, c->status);
   auto bonus_rows = [&]() {
     if (cf.bonus_row)
       hipLaunchKernelGGL(k_bonus_rows, dim3(B), dim3(128), 0, s, d_t0, (const int32_t*)c->K_eff, (const int32_t*)d_row_ptr,
@@ -765,7 +759,7 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
       io.clip = cf.clip_x0; io.clip_val = cf.clip_val; io.seed = cf.seed;
       io.y = d_y_last; io.states = d_states; io.eps_p = d_eps_p; io.xi = d_xi;
       tick(c, 0, 0, s);
-      (big ? dn.fused_draft_big : dn.fused_draft_small)(dn.fnet, io, cf.A, s);
+      HIPCHK(c, (big ? dn.fused_draft_big : dn.fused_draft_small)(dn.fnet, io, cf.A, s));
       tick(c, 0, 1, s);
       bonus_rows();
       HIPCHK(c, hipGetLastError());
@@ -774,7 +768,7 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
   }
   for (int k = 1; k <= cf.K_max; ++k) {
     // every environment runs the drafter at step k; the DDPM step masks those with K_eff < k
-    forward(c, c->net[1], d_y_last, B, nullptr, d_t0, k - 1, nullptr, c->eps_tmp, s);
+    if ((rc = forward(c, c->net[1], d_y_last, B, nullptr, d_t0, k - 1, nullptr, c->eps_tmp, s))) return rc;
     hipLaunchKernelGGL(k_draft_step, grid1((long long)B * (D / 4), 256), dim3(256), 0, s, k, (const float*)c->eps_tmp,
                        d_t0, (const int32_t*)c->K_eff, (const int32_t*)d_row_ptr, d_sigma_scale, d_env_id, c->tb,
                        cf.clip_x0, cf.clip_val, cf.seed, B, D, d_y_last, d_states, d_eps_p, d_xi);
@@ -784,8 +778,8 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
   return TSDP_OK;
 }
 
-int tsdp_verify(tsdp_ctx* c, int B, int R_cap, const int32_t* d_row_ptr, const int32_t* d_row_t,
-                const int32_t* d_row_env, const float* d_states, float* d_eps_q, void* stream) {
+static int verify_impl(tsdp_ctx* c, int B, int R_cap, const int32_t* d_row_ptr, const int32_t* d_row_t,
+                       const int32_t* d_row_env, const float* d_states, float* d_eps_q, bool own_table, void* stream) {
   int rc = check_ready(c, B, true);
   if (rc) return rc;
   if (B == 0 || R_cap == 0) return TSDP_OK;
@@ -793,11 +787,24 @@ int tsdp_verify(tsdp_ctx* c, int B, int R_cap, const int32_t* d_row_ptr, const i
     return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_verify");
   if (R_cap < 0 || (size_t)R_cap > rows_max(c->cfg))
     return fail(c, TSDP_E_SHAPE, "R_cap outside 0..B_max*(K_max+bonus_row)");
-  if (B == 0 || R_cap == 0) return TSDP_OK;
   if ((rc = ensure_workspace(c))) return rc;
-  forward(c, c->net[0], d_states, R_cap, d_row_ptr + B, d_row_t, 0, d_row_env, d_eps_q, (hipStream_t)stream);
+  hipStream_t s = (hipStream_t)stream;
+  if (!own_table) {
+    // a caller's row table: timesteps and environment indices are clamped into range (the kernels index tables
+    // with them) and the status word reports it
+    hipLaunchKernelGGL(k_check_rows, grid1(R_cap, 256), dim3(256), 0, s, d_row_ptr + B, R_cap, d_row_t, d_row_env, c->cfg.T,
+                       c->cond_B, c->row_t_chk, c->row_env_chk, c->status);
+    d_row_t = c->row_t_chk;
+    d_row_env = c->row_env_chk;
+  }
+  if ((rc = forward(c, c->net[0], d_states, R_cap, d_row_ptr + B, d_row_t, 0, d_row_env, d_eps_q, s))) return rc;
   HIPCHK(c, hipGetLastError());
   return TSDP_OK;
+}
+
+int tsdp_verify(tsdp_ctx* c, int B, int R_cap, const int32_t* d_row_ptr, const int32_t* d_row_t,
+                const int32_t* d_row_env, const float* d_states, float* d_eps_q, void* stream) {
+  return verify_impl(c, B, R_cap, d_row_ptr, d_row_t, d_row_env, d_states, d_eps_q, false, stream);
 }
 
 static int accept_impl(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32_t* d_row_t, const int32_t* d_env_id,
@@ -867,7 +874,8 @@ static int round_impl(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_
   if ((rc = tsdp_draft(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, c->row_ptr, c->row_t, c->row_env, c->states,
                        c->eps_p, c->xi, c->y_last, stream)))
     return rc;
-  if ((rc = tsdp_verify(c, B, B * (c->cfg.K_max + (c->cfg.bonus_row ? 1 : 0)), c->row_ptr, c->row_t, c->row_env, c->states, c->eps_q, stream)))
+  if ((rc = verify_impl(c, B, B * (c->cfg.K_max + (c->cfg.bonus_row ? 1 : 0)), c->row_ptr, c->row_t, c->row_env, c->states,
+                        c->eps_q, true, stream)))
     return rc;
   // x and t are overwritten in place: the acceptance kernel reads only the round's own buffers
   return accept_impl(c, B, c->row_ptr, c->row_t, d_env_id, d_sigma_scale, d_lambda, c->states, c->eps_p, c->eps_q, c->xi,
@@ -955,30 +963,36 @@ int tsdp_chain_staged(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_
                     d_tot_accept, d_tot_drafts, d_tot_rounds, h_rounds, stream);
 }
 
+// partial: room for 2 * ceil(R / 16) doubles; every entry that is read is written first by the same call
+static int distill_launch(tsdp_ctx* c, int R, const int32_t* d_row_t, const float* d_states, const float* d_eps_p,
+                          const float* d_eps_q, float lambda1, float lambda2, double* partial, double* d_loss, hipStream_t s) {
+  const int parts = (R + 15) / 16;
+  if (parts > 0) {
+    if (c->cfg.clip_x0)
+      hipLaunchKernelGGL(k_distill_partial<true>, dim3(parts), dim3(256), 0, s, R, c->D, d_row_t, d_states, d_eps_p, d_eps_q,
+                         c->tb, c->cfg.clip_val, partial);
+    else
+      hipLaunchKernelGGL(k_distill_partial<false>, dim3(parts), dim3(256), 0, s, R, c->D, d_row_t, d_states, d_eps_p, d_eps_q,
+                         c->tb, c->cfg.clip_val, partial);
+  }
+  hipLaunchKernelGGL(k_distill_final, dim3(1), dim3(256), 0, s, parts, R, d_row_t, (const double*)partial, lambda1,
+                     lambda2, d_loss);
+  HIPCHK(c, hipGetLastError());
+  return TSDP_OK;
+}
+
 int tsdp_distill_loss(tsdp_ctx* c, int R, const int32_t* d_row_t, const float* d_states, const float* d_eps_p,
                       const float* d_eps_q, float lambda1, float lambda2, double* d_loss, void* stream) {
   if (!c) return TSDP_E_INVAL;
   if (R < 0 || (size_t)R > rows_max(c->cfg)) return fail(c, TSDP_E_SHAPE, "R outside 0..B_max*(K_max+bonus_row)");
   if (!d_loss || (R > 0 && (!d_row_t || !d_states || !d_eps_p || !d_eps_q)))
     return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_distill_loss");
-  hipStream_t s = (hipStream_t)stream;
-  const int parts = (R + 15) / 16;
   if (!c->loss_partial) {
     int rc = dev_alloc(c, &c->loss_partial, 2 * ((rows_max(c->cfg) + 15) / 16) + 2);
     if (rc) return rc;
   }
-  if (parts > 0) {
-    if (c->cfg.clip_x0)
-      hipLaunchKernelGGL(k_distill_partial<true>, dim3(parts), dim3(256), 0, s, R, c->D, d_row_t, d_states, d_eps_p, d_eps_q,
-                         c->tb, c->cfg.clip_val, c->loss_partial);
-    else
-      hipLaunchKernelGGL(k_distill_partial<false>, dim3(parts), dim3(256), 0, s, R, c->D, d_row_t, d_states, d_eps_p, d_eps_q,
-                         c->tb, c->cfg.clip_val, c->loss_partial);
-  }
-  hipLaunchKernelGGL(k_distill_final, dim3(1), dim3(256), 0, s, parts, R, d_row_t, (const double*)c->loss_partial, lambda1,
-                     lambda2, d_loss);
-  HIPCHK(c, hipGetLastError());
-  return TSDP_OK;
+  return distill_launch(c, R, d_row_t, d_states, d_eps_p, d_eps_q, lambda1, lambda2, c->loss_partial, d_loss,
+                        (hipStream_t)stream);
 }
 
 int tsdp_status(tsdp_ctx* c, void* stream, int32_t* h_status) {
@@ -1016,11 +1030,5 @@ const char* tsdp_path_name(const tsdp_ctx* c, int which) {
 }
 
 const char* tsdp_last_error(const tsdp_ctx* c) { return c ? c->err.c_str() : "null context"; }
-
-#ifdef TSDP_TRACE
-int tsdp_debug_trace(tsdp_ctx* c, int which, long long* h_out) {   // tuning builds only
-  return hipMemcpy(h_out, c->net[which].fnet.trace, 8 * 12 * sizeof(long long), hipMemcpyDeviceToHost) == hipSuccess ? 0 : -4;
-}
-#endif
 
 }  // extern "C"

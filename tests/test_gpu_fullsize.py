@@ -6,11 +6,12 @@ import pytest
 import bench
 import tsdp_inputs as ti
 from oracle import spec_round as sr
-from tests.helpers import gpu_side, oracle_side, scaled_err, to_dev
+from tests.helpers import assert_latents_close, drafted_rows, gpu_side, list_near_ties, oracle_side, scaled_err, to_dev
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"fp32": 1e-5, "bf16": 2e-2}            # error relative to the tensor scale, as in test_gpu_parity.py
+TOL = {"fp32": 1e-5, "bf16": 2e-2}            # noise predictions: error relative to the tensor scale; latents: elementwise
+TIE = 1e-5                                     # accept decisions may differ only inside this near-tie window
 SAMPLES = {"C2": [0], "C3": [0, 7, 31, 63], "C4": [0, 129, 255], "C5": [0, 3, 500, 777, 1023]}
 
 
@@ -47,10 +48,10 @@ def test_full_size_stages_on_sampled_environments(name):
     for j, b in enumerate(envs):
         gs = slice(row_ptr[b], row_ptr[b + 1]); os_ = slice(o["row_ptr"][j], o["row_ptr"][j + 1])
         np.testing.assert_allclose(g["xi"][gs], o["xi"][os_], rtol=1e-5, atol=2e-6)
-        for nm in ("states", "eps_p"):
-            e = scaled_err(g[nm][gs], o[nm][os_])
-            assert e < tol, (nm, int(b), e)
-        assert scaled_err(g["y_last"][b], o["y_last"][j]) < tol
+        e = scaled_err(g["eps_p"][gs], o["eps_p"][os_])
+        assert e < tol, ("eps_p", int(b), e)
+        assert_latents_close(g["states"][gs], o["states"][os_], wl.dtype, f"drafted states of env {int(b)}")
+        assert_latents_close(g["y_last"][b], o["y_last"][j], wl.dtype, f"y_last of env {int(b)}")
         # verification of the GPU's own states of that environment
         ref = sr.verify(S["base"], np.full(gs.stop - gs.start, b), g["row_t"][gs], g["states"][gs], S["cond"])
         e = scaled_err(g["eps_q"][gs], ref)
@@ -59,16 +60,17 @@ def test_full_size_stages_on_sampled_environments(name):
     # acceptance on the GPU's own tensors, every environment (the oracle's accept is cheap): indices bit-exact
     ref = sr.accept(S["sched"], row_ptr, row_t, S["s"], None, wl.philox_seed, g["states"][:R], g["eps_p"][:R],
                     g["eps_q"][:R], g["xi"][:R], g["y_last"])
-    near = np.abs(ref["logu"] - ref["logratio"]) < 1e-9
+    near = list_near_ties(name, ref["logu"], ref["logratio"], row_ptr, 1e-9, drafted_rows(row_ptr, row_t))
     assert not np.any((g["flags"][:R] != ref["flags"]) & ~near)
     ok = np.array([not np.any(near[row_ptr[b]:row_ptr[b + 1]]) for b in range(B)])
+    assert ok.sum() >= B - 2
     for k in ("n_accept", "n_adv", "t_next"):
         np.testing.assert_array_equal(g[k][ok], ref[k][ok])
-    np.testing.assert_allclose(g["x_out"][ok], ref["x_out"][ok], rtol=1e-5, atol=1e-6)
+    assert_latents_close(g["x_out"][ok], ref["x_out"][ok], "fp32", "x_out of tsdp_accept on identical tensors")
     ctx.close()
 
 
-@pytest.mark.parametrize("name", ["C3", "C5"])
+@pytest.mark.parametrize("name", ["C3", "C4", "C5"])
 def test_full_size_bf16_round_against_oracle_round(name):
     """End-to-end bf16 round: accept decisions may differ from the fp64 oracle only on rows whose margin
     |log U - log alpha| is inside the error the bf16 networks put on log alpha; environments whose first
@@ -101,12 +103,16 @@ def test_full_size_bf16_round_against_oracle_round(name):
         dl = np.abs(gl[gs][:n] - ref["logratio"][os_][:n])
         margin = np.abs(ref["logu"][os_][:n] - ref["logratio"][os_][:n])
         mism = gf[gs][:n] != ref["flags"][os_][:n]
-        assert np.all(margin[mism] <= dl[mism] + 1e-5), (int(b), margin[mism], dl[mism])
+        for k in np.nonzero(mism)[0]:
+            print(f"[{name}] env {int(b)} draft {int(k) + 1}: decision differs, margin {margin[k]:.3e}, "
+                  f"bf16 error on log alpha {dl[k]:.3e}")
+        assert np.all(margin[mism] <= dl[mism] + TIE), (int(b), margin[mism], dl[mism])
         assert dl.max() < 0.5, (int(b), dl.max())                     # bf16 error on log alpha stays a fraction of a nat
         if not mism.any():
             agree += 1
             assert int(nacc[b]) == ref["n_accept"][j] and int(t[b]) == ref["t_next"][j]
-            assert scaled_err(x[b].cpu().numpy(), ref["x_out"][j]) < TOL["bf16"]
+            w = assert_latents_close(x[b].cpu().numpy(), ref["x_out"][j], "bf16", f"final action of env {int(b)}")
+            print(f"[{name}] env {int(b)}: final action at {w:.3f} of the elementwise bound, max log-alpha error {dl.max():.3e}")
     print(f"[{name}] sampled envs with identical accept decisions: {agree}/{len(envs)}")
     assert agree >= len(envs) - 2
     ctx.close()
@@ -181,19 +187,20 @@ def test_full_size_bonus_row_with_ddim_sampler():
     for j, b in enumerate(envs):
         gs = slice(row_ptr[b], row_ptr[b + 1]); os_ = slice(o["row_ptr"][j], o["row_ptr"][j + 1])
         np.testing.assert_allclose(g["xi"][gs], o["xi"][os_], rtol=1e-5, atol=2e-6)
-        for nm in ("states", "eps_p"):
-            assert scaled_err(g[nm][gs], o[nm][os_]) < TOL["bf16"], (nm, int(b))
+        assert scaled_err(g["eps_p"][gs], o["eps_p"][os_]) < TOL["bf16"], ("eps_p", int(b))
+        assert_latents_close(g["states"][gs], o["states"][os_], "bf16", f"drafted states of env {int(b)}")
         ref = sr.verify(base, np.full(gs.stop - gs.start, b), g["row_t"][gs], g["states"][gs], cond)
         assert scaled_err(g["eps_q"][gs], ref) < TOL["bf16"], ("eps_q", int(b))
     ref = sr.accept(sched, row_ptr, row_t, s, None, wl.philox_seed, g["states"][:R], g["eps_p"][:R], g["eps_q"][:R],
                     g["xi"][:R], g["y_last"], bonus=True)
-    near = np.abs(ref["logu"] - ref["logratio"]) < 1e-5
+    near = list_near_ties("C3 bonus/DDIM", ref["logu"], ref["logratio"], row_ptr, TIE, drafted_rows(row_ptr, row_t, True))
     diff = g["flags"][:R] != ref["flags"]
     assert not np.any(diff & ~near)
     ok = np.array([not np.any(diff[row_ptr[b]:row_ptr[b + 1]]) for b in range(B)])
+    assert ok.sum() >= B - 2
     for k in ("n_accept", "n_adv", "t_next"):
         np.testing.assert_array_equal(g[k][ok], ref[k][ok])
-    np.testing.assert_allclose(g["x_out"][ok], ref["x_out"][ok], rtol=1e-5, atol=1e-6)
+    assert_latents_close(g["x_out"][ok], ref["x_out"][ok], "fp32", "x_out of tsdp_accept on identical tensors")
     # every running environment ends its round with a corrected or an exact base step
     live = t0 >= 0
     assert (ref["n_adv"][live] == ref["n_accept"][live] + 1).all() and ref["n_adv"][0] == 1
@@ -241,3 +248,79 @@ def test_speculative_chain_on_the_gpu_has_the_law_of_the_base_chain():
     sd = np.sqrt((a.var(0) + b.var(0)) / n)
     assert (np.abs(a.mean(0) - b.mean(0)) < 5 * sd).all()
     assert (np.abs(a.var(0) / b.var(0) - 1) < 6 * np.sqrt(2 / n)).all()
+
+
+def _sentinel_rows(ctx, B):
+    """Caller buffers filled with a NaN bit pattern no kernel produces."""
+    import torch
+    rows = ctx.alloc_rows(B)
+    for k in ("states", "eps_p", "eps_q", "xi"):
+        rows[k].view(torch.int32).fill_(0x7FC0BEEF)
+    for k in ("row_t", "row_env"):
+        rows[k].fill_(-777)
+    return rows
+
+
+def _check_tail_untouched(rows, R):
+    import torch
+    for k in ("states", "eps_p", "eps_q", "xi"):
+        bits = rows[k].view(torch.int32).reshape(rows[k].shape[0], -1)
+        assert bool((bits[R:] == 0x7FC0BEEF).all()), f"{k}: a row at or beyond row_ptr[B] was written"
+        assert bool(torch.isfinite(rows[k][:R]).all()), f"{k}: a live row was left unwritten"
+    for k in ("row_t", "row_env"):
+        assert bool((rows[k][R:] == -777).all()), f"{k}: an entry at or beyond row_ptr[B] was written"
+        assert bool((rows[k][:R] >= 0).all())
+
+
+def test_rows_beyond_the_live_count_are_never_written():
+    # ragged batch at the full C5 size (fused bf16 kernels, K ~ U{2..16}: about 9200 live rows of 16384), then the
+    # fused fp32 kernels and the general operator kernels on small batches: NaN sentinels behind row_ptr[B] survive
+    # tsdp_draft and tsdp_verify, every live row is written
+    wl, S = _full("C5")
+    ctx, B = S["ctx"], wl.B
+    rows = _sentinel_rows(ctx, B)
+    ctx.tsdp_draft(to_dev(S["x"]), to_dev(S["t0"]), to_dev(S["K"]), to_dev(S["s"]), None, rows)
+    ctx.tsdp_verify(B, rows)
+    R = int(rows["row_ptr"][-1].item())
+    assert 0 < R < rows["row_t"].shape[0] - 1000
+    _check_tail_untouched(rows, R)
+    ctx.close()
+    for wl in (ti.small_variant(ti.C2, B=5, base=ti.NetShape(2, 256, 4)),
+               ti.small_variant(ti.C1, B=5, base=ti.NetShape(2, 96, 3), draft=ti.NetShape(1, 48, 3)),
+               ti.small_variant(ti.C4, B=5, base=ti.NetShape(1, 512, 8))):
+        wb, wd = ti.make_weights(wl, "base", b_std=0.02), ti.make_weights(wl, "draft", b_std=0.02)
+        for bonus in (False, True):
+            ctx = gpu_side(wl, wb, wd, ti.make_cond(wl, 5), bonus_row=bonus)
+            rows = _sentinel_rows(ctx, 5)
+            t0 = np.array([wl.T - 1, 2, 0, -1, 1], np.int32); K = np.array([wl.K_max, wl.K_max, 3, 2, 1], np.int32)
+            ctx.tsdp_draft(to_dev(ti.make_latents(wl, 5)), to_dev(t0), to_dev(K), to_dev(np.ones(5, np.float32)), None, rows)
+            ctx.tsdp_verify(5, rows)
+            R = int(rows["row_ptr"][-1].item())
+            assert R == int(sr.plan_rows(t0, K, bonus)[1][-1]) and R < rows["row_t"].shape[0]
+            _check_tail_untouched(rows, R)
+            ctx.close()
+
+
+def test_verify_range_checks_a_callers_row_table():
+    # tsdp_verify indexes the timestep and conditioning tables with the caller's row table: entries out of range are
+    # clamped (no read out of bounds) and reported in the status word
+    import torch
+    wl = ti.small_variant(ti.C3, B=4, base=ti.NetShape(1, 256, 4))
+    wb, wd = ti.make_weights(wl, "base"), ti.make_weights(wl, "draft")
+    ctx = gpu_side(wl, wb, wd, ti.make_cond(wl, 4))
+    rows = ctx.alloc_rows(4)
+    t0 = np.array([50, 40, 30, 20], np.int32); K = np.full(4, 2, np.int32)
+    ctx.tsdp_draft(to_dev(ti.make_latents(wl, 4)), to_dev(t0), to_dev(K), to_dev(np.array([1.0, 0.0, 1.0, 1.0], np.float32)), None, rows)
+    assert ctx.tsdp_status() == 4                                      # sigma_scale = 0 is reported
+    ctx.tsdp_verify(4, rows)
+    assert ctx.tsdp_status() == 0
+    good = rows["eps_q"].clone()
+    rows["row_env"][1] = 9; rows["row_t"][2] = 100; rows["row_env"][7] = -3
+    ctx.tsdp_verify(4, rows)
+    assert ctx.tsdp_status() == 2 + 8
+    rows["row_env"][1] = 3; rows["row_t"][2] = 99; rows["row_env"][7] = 0   # what the clamp made of them
+    want = rows["eps_q"].clone()
+    ctx.tsdp_verify(4, rows)
+    assert ctx.tsdp_status() == 0 and torch.equal(rows["eps_q"], want)
+    assert torch.equal(want[[0, 3, 4, 5, 6]], good[[0, 3, 4, 5, 6]])
+    ctx.close()

@@ -4,15 +4,16 @@ import pytest
 
 import tsdp_inputs as ti
 from oracle import philox, spec_round as sr
-from tests.helpers import gpu_side, oracle_side, scaled_err, to_dev
+from tests.helpers import assert_latents_close, drafted_rows, gpu_side, list_near_ties, oracle_side, scaled_err, to_dev
 
 pytestmark = pytest.mark.gpu
 
-# Tolerances.  fp32 networks: the GPU accumulates dot products of length <= 4d in fp32 through L
-# residual layers, the oracle in fp64; the bound used is 1e-5 of the tensor scale plus rtol 1e-5.
-# bf16 networks: matrix-multiply inputs are rounded to bfloat16 (2^-9 relative), bound 2e-2 of scale.
+# Tolerances.  Latents (drafted states, final actions): elementwise, rtol 1e-5 for fp32 networks and 2e-2 for bf16
+# networks (tests/helpers.py: assert_latents_close).  Intermediate noise predictions: max error relative to the
+# tensor's scale below the same numbers (the GPU accumulates dot products of length <= 4d in fp32 through L residual
+# layers, the oracle in fp64; bf16 matrix-multiply inputs carry 2^-9 relative rounding).
 TOL = {"fp32": 1e-5, "bf16": 2e-2}
-TIE = 1e-5          # accept flags may differ only where |log U - log alpha| is below this (fp32 nets)
+TIE = 1e-5          # accept decisions may differ only where |log U - log alpha| is below this
 
 
 def _setup(wl, B, clip=None, K_max=None, b_std=0.02, head_scale=1.0, seed=None, sampler=0, eta=1.0, bonus=False, norm=0):
@@ -43,12 +44,12 @@ def _check_draft(S, rows, t0, K, s, env, tol):
     np.testing.assert_array_equal(rows["row_env"].cpu().numpy()[:R], o["row_env"])
     xi = rows["xi"].cpu().numpy()[:R]
     np.testing.assert_allclose(xi, o["xi"], rtol=1e-5, atol=2e-6)      # fp32 Box-Muller vs fp64
-    for name in ("states", "eps_p"):
-        e = scaled_err(rows[name].cpu().numpy()[:R], o[name])
-        print(f"[{S['wl'].name}] draft {name}: scaled err {e:.3e}")
-        assert e < tol, (name, e)
-    e = scaled_err(rows["y_last"].cpu().numpy(), o["y_last"])
-    assert e < tol, ("y_last", e)
+    e = scaled_err(rows["eps_p"].cpu().numpy()[:R], o["eps_p"])
+    print(f"[{S['wl'].name}] draft eps_p: scaled err {e:.3e}")
+    assert e < tol, ("eps_p", e)
+    w = assert_latents_close(rows["states"].cpu().numpy()[:R], o["states"], S["wl"].dtype, "drafted states")
+    w2 = assert_latents_close(rows["y_last"].cpu().numpy(), o["y_last"], S["wl"].dtype, "y_last")
+    print(f"[{S['wl'].name}] draft states / y_last: {w:.3f} / {w2:.3f} of the elementwise bound")
     return o
 
 
@@ -77,7 +78,8 @@ def _check_accept(S, rows, o, s, env, window):
                     rows["xi"].cpu().numpy()[:R], rows["y_last"].cpu().numpy(), S["clip"], bonus=S["bonus"])
     np.testing.assert_allclose(g["logu"][:R], ref["logu"], rtol=1e-6, atol=1e-7)
     np.testing.assert_allclose(g["logratio"][:R], ref["logratio"], rtol=1e-6, atol=1e-6)
-    near = np.abs(ref["logu"] - ref["logratio"]) < window
+    near = list_near_ties(S["wl"].name, ref["logu"], ref["logratio"], o["row_ptr"], window,
+                          drafted_rows(o["row_ptr"], o["row_t"], S["bonus"]))
     diff = g["flags"][:R] != ref["flags"]
     assert not np.any(diff & ~near), "accept flag differs outside the near-tie window"
     env_ok = np.array([not np.any(diff[o["row_ptr"][b]:o["row_ptr"][b + 1]]) for b in range(B)])
@@ -135,38 +137,66 @@ def test_c4_cross_attention_stages():
     _stage_parity(wl, 2, t0, K, s, paths=("bf16-mfma-fused", "bf16-mfma-fused"))
 
 
-def _round_parity(wl, B, t0, K, s, env, window, head_scale=1.0):
+def _round_parity(wl, B, t0, K, s, env, head_scale=1.0):
+    """tsdp_round against the oracle's round.  The same inputs also go through the three stages with diagnostics,
+    which gives the GPU's own log alpha of every row: the fused round must equal the stages bit for bit, accept
+    decisions must equal the oracle's outside the near-tie window (near-tie rows are printed), and the final actions
+    of every compared environment must agree elementwise.  At least one environment must be compared."""
     import torch
     S = _setup(wl, B, head_scale=head_scale)
     ctx = S["ctx"]
+    sd = to_dev(s.astype(np.float32)); ed = None if env is None else to_dev(env.astype(np.int32))
+    rows = _gpu_draft(S, t0, K, s, env)
+    ctx.tsdp_verify(B, rows)
+    st = {k: v.cpu().numpy() for k, v in ctx.tsdp_accept(B, sd, ed, rows).items()}
     x = to_dev(S["x"]); t = to_dev(t0.astype(np.int32))
     nacc = torch.zeros(B, dtype=torch.int32, device="cuda"); nadv = torch.zeros_like(nacc)
-    ctx.tsdp_round(x, t, to_dev(K.astype(np.int32)), to_dev(s.astype(np.float32)),
-                   None if env is None else to_dev(env.astype(np.int32)), nacc, nadv)
+    ctx.tsdp_round(x, t, to_dev(K.astype(np.int32)), sd, ed, nacc, nadv)
+    g = dict(x=x.cpu().numpy(), t=t.cpu().numpy(), nacc=nacc.cpu().numpy(), nadv=nadv.cpu().numpy())
+    np.testing.assert_array_equal(g["nacc"], st["n_accept"])
+    np.testing.assert_array_equal(g["nadv"], st["n_adv"])
+    np.testing.assert_array_equal(g["t"], st["t_next"])
+    np.testing.assert_array_equal(g["x"], st["x_out"])
     ref = sr.spec_round(S["base"], S["drafter"], S["sched"], S["x"], t0, K, s, env, S["seed"], S["cond"])
-    d = ref["draft"]
-    near_env = np.array([np.any(np.abs(ref["logu"][d["row_ptr"][b]:d["row_ptr"][b + 1]] -
-                                       ref["logratio"][d["row_ptr"][b]:d["row_ptr"][b + 1]]) < window) for b in range(B)])
-    ok = ~near_env
-    np.testing.assert_array_equal(nacc.cpu().numpy()[ok], ref["n_accept"][ok])
-    np.testing.assert_array_equal(nadv.cpu().numpy()[ok], ref["n_adv"][ok])
-    np.testing.assert_array_equal(t.cpu().numpy()[ok], ref["t_next"][ok])
-    e = scaled_err(x.cpu().numpy()[ok], ref["x_out"][ok])
-    assert e < TOL[wl.dtype], e
+    d = ref["draft"]; rp = d["row_ptr"]; R = int(rp[-1])
+    drafted = d["row_t"] > 0
+    near = list_near_ties(wl.name, ref["logu"], ref["logratio"], rp, TIE, drafted)
+    dl = np.abs(st["logratio"][:R] - ref["logratio"])
+    # rows up to the oracle's first rejection see the same states on both sides: there the decisions are comparable
+    seen = np.zeros(R, bool)
+    for b in range(B):
+        seen[rp[b]:rp[b] + min(int(ref["n_accept"][b]) + 1, rp[b + 1] - rp[b])] = True
+    print(f"[{wl.name}] round: max |log alpha (GPU) - log alpha (oracle)| on compared rows = {dl[seen & drafted].max(initial=0.0):.3e}")
+    mism = (st["flags"][:R] != ref["flags"]) & seen & drafted
+    # a decision may differ inside the near-tie window, or where the network's own rounding error on log alpha (the
+    # GPU's fp32 / bf16 forward against the oracle's fp64, shown here per row) reaches the margin of that row
+    margin = np.abs(ref["logu"] - ref["logratio"])
+    for r in np.nonzero(mism)[0]:
+        print(f"[{wl.name}] row {int(r)}: decision differs, margin {margin[r]:.3e}, network error on log alpha {dl[r]:.3e}")
+    bad = mism & ~near & (margin > dl + TIE)
+    assert not np.any(bad), ("accept decision differs outside the near-tie window", np.nonzero(bad)[0], margin[bad], dl[bad])
+    ok = np.array([not np.any((near | mism)[rp[b]:rp[b + 1]] & seen[rp[b]:rp[b + 1]]) for b in range(B)])
+    assert ok.any(), "every environment has a near-tie row: nothing was compared"
+    np.testing.assert_array_equal(g["nacc"][ok], ref["n_accept"][ok])
+    np.testing.assert_array_equal(g["nadv"][ok], ref["n_adv"][ok])
+    np.testing.assert_array_equal(g["t"][ok], ref["t_next"][ok])
+    w = assert_latents_close(g["x"][ok], ref["x_out"][ok], wl.dtype, "final actions of tsdp_round")
+    print(f"[{wl.name}] round: {int(ok.sum())}/{B} environments compared, final actions at {w:.3f} of the elementwise bound")
     assert ctx.tsdp_status() == 0
     ctx.close()
-    return ref, near_env
+    return ref, ~ok
 
 
 def test_c1_round():
-    ref, near = _round_parity(ti.C1, 1, np.array([9]), np.array([4]), np.array([1.0]), None, 1e-4)
+    ref, near = _round_parity(ti.C1, 1, np.array([9]), np.array([4]), np.array([1.0]), None)
     assert not near.any()
 
 
 def test_c2_round_and_chain():
     wl = ti.C2
     for t0 in (99, 50, 8, 3):
-        _round_parity(wl, 1, np.array([t0]), np.array([8]), np.array([1.0]), None, 1e-4)
+        ref, near = _round_parity(wl, 1, np.array([t0]), np.array([8]), np.array([1.0]), None)
+        assert not near.any()
 
 
 def test_round_ragged_batch_fp32():
@@ -174,7 +204,7 @@ def test_round_ragged_batch_fp32():
     rng = np.random.default_rng(3)
     t0 = rng.integers(-1, 100, 12); K = rng.integers(1, 9, 12); s = rng.uniform(1, 1.5, 12)
     t0[:3] = [0, -1, 2]
-    ref, near = _round_parity(wl, 12, t0, K, s, np.arange(12) + 1000, 1e-4, head_scale=0.5)
+    ref, near = _round_parity(wl, 12, t0, K, s, np.arange(12) + 1000, head_scale=0.5)
     assert near.sum() <= 2
     assert (ref["n_accept"] > 0).any() and (ref["n_accept"] < ref["draft"]["K_eff"]).any()
 
@@ -272,7 +302,7 @@ def test_chain_runs_rounds_until_every_environment_finishes():
         r = sr.spec_round(S["base"], S["drafter"], S["sched"], xr, tr, K, s, None, S["seed"], S["cond"])
         ran = tr >= 0
         acc += r["n_accept"]; drafts += r["draft"]["K_eff"]; nr += ran
-        near = (np.abs(r["logu"] - r["logratio"]) < 1e-4) & (r["draft"]["row_t"] > 0)
+        near = list_near_ties("C1 chain", r["logu"], r["logratio"], r["draft"]["row_ptr"], TIE, r["draft"]["row_t"] > 0)
         assert not near.any()                                             # no near-tie on this seed: decisions are comparable
         xr, tr = r["x_out"], r["t_next"]; n += 1
     assert rounds == n
@@ -280,7 +310,8 @@ def test_chain_runs_rounds_until_every_environment_finishes():
     np.testing.assert_array_equal(tot["accept"].cpu().numpy(), acc)
     np.testing.assert_array_equal(tot["drafts"].cpu().numpy(), drafts)
     np.testing.assert_array_equal(tot["rounds"].cpu().numpy(), nr)
-    assert scaled_err(x.cpu().numpy(), xr) < 1e-4                         # fp32 rounding compounded over the chain
+    # up to four rounds compound their fp32 rounding in the final action: the per-round bound, once per round
+    assert assert_latents_close(x.cpu().numpy(), xr, "fp32", "final actions of the chain") <= 1.0
     S["ctx"].close()
 
 
@@ -376,7 +407,7 @@ def test_bonus_row_stages_rounds_and_chain():
     np.testing.assert_array_equal(tot["rounds"].cpu().numpy(), ref["totals"]["rounds"])
     np.testing.assert_array_equal(tot["rounds"].cpu().numpy(), [3, 4, 1, 1])            # ceil((t0+1)/(K+1))
     np.testing.assert_array_equal(tot["accept"].cpu().numpy(), ref["totals"]["accept"])
-    assert scaled_err(x.cpu().numpy(), ref["x"]) < 1e-4
+    assert_latents_close(x.cpu().numpy(), ref["x"], "fp32", "final actions of the bonus-row chain")
     ctx.close()
 
 
@@ -394,12 +425,12 @@ def test_staged_chain_follows_the_stage_tables():
         ref = sr.chain(S["base"], S["drafter"], S["sched"], S["x"], t0, K3, s3.astype(np.float32),
                        None, S["seed"], S["cond"], lam=None if lam is None else lam.astype(np.float32), stages=(7, 3))
         for r in ref["history"]:
-            near = (np.abs(r["logu"] - r["logratio"]) < 1e-4) & (r["draft"]["row_t"] > 0)
+            near = list_near_ties("C1 staged chain", r["logu"], r["logratio"], r["draft"]["row_ptr"], TIE, r["draft"]["row_t"] > 0)
             assert not near.any()
         assert rounds == ref["rounds"] and (t.cpu().numpy() == -1).all()
         for k in ("accept", "drafts", "rounds"):
             np.testing.assert_array_equal(tot[k].cpu().numpy(), ref["totals"][k])
-        assert scaled_err(x.cpu().numpy(), ref["x"]) < 1e-4
+        assert_latents_close(x.cpu().numpy(), ref["x"], "fp32", "final actions of the staged chain")
     import pytest as _pt
     from paper_2512_15773_amd import TsdpError
     with _pt.raises(TsdpError):
@@ -549,3 +580,14 @@ def test_rmsnorm_networks_on_every_path():
     _stage_parity(wl, 2, t0, K, s, norm=1, paths=("bf16-mfma-fused", "bf16-mfma-fused"))
     wl = ti.small_variant(ti.C1, B=2, base=ti.NetShape(2, 96, 3), draft=ti.NetShape(1, 48, 3))
     _stage_parity(wl, 2, np.array([9, 4]), np.array([4, 4]), np.ones(2), norm=1, paths=("f32-ops", "f32-ops"))
+
+
+def test_action_dim_above_one_head_fragment():
+    # A = 20, 33: the output head spans two / three 16-row MFMA fragments in the fused kernels (verify and drafter)
+    wl = ti.small_variant(ti.C3, B=3, A=20, base=ti.NetShape(2, 256, 4))
+    t0, K, s = ti.make_schedule_inputs(wl, 3, t0=60)
+    _stage_parity(wl, 3, t0, K, s, paths=("bf16-mfma-fused", "bf16-mfma-fused"))
+    wl = ti.small_variant(ti.C2, B=2, H=16, A=20, base=ti.NetShape(2, 256, 4))
+    _stage_parity(wl, 2, np.array([70, 5]), np.array([8, 8]), np.array([1.0, 1.2]), paths=("f32-mfma-fused", "f32-mfma-fused"))
+    wl = ti.small_variant(ti.C1, B=2, H=16, A=32)
+    _stage_parity(wl, 2, np.array([9, 3]), np.array([4, 4]), np.ones(2), paths=("f32-mfma-fused", "f32-mfma-fused"))
