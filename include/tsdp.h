@@ -184,6 +184,18 @@ int tsdp_chain_staged(tsdp_ctx* ctx, int B, float* d_x, int32_t* d_t, const int3
 int tsdp_distill_loss(tsdp_ctx* ctx, int R, const int32_t* d_row_t, const float* d_states, const float* d_eps_p,
                       const float* d_eps_q, float lambda1, float lambda2, double* d_loss, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid it): tsdp_distill_loss with its partial sums in a file-scope device array of the library instead of
+ * context memory.  It calls no hipMalloc / hipFree or allocating library routine, on any call.  Same arguments,
+ * same kernels and bit-identical results; R is limited to 65536 rows (the array holds 2 * 65536 / 16 + 2 doubles,
+ * 64 KiB, on every GPU the library is used on, until the process ends); a larger R returns TSDP_E_SHAPE.  The
+ * context's device must be current.  All calls on one GPU share the array, which keeps the last call's partial
+ * sums (every entry a call reads it has written first, so nothing needs clearing): calls that overlap in time on
+ * one GPU, from any context or stream, race. */
+int tsdp_distill_loss_noalloc(tsdp_ctx* ctx, int R, const int32_t* d_row_t, const float* d_states,
+                              const float* d_eps_p, const float* d_eps_q, float lambda1, float lambda2,
+                              double* d_loss, void* stream);
+
 /* Synchronises `stream` and returns the device status word accumulated since the last call:
  * bit 0 = some K was outside 0..K_max (clamped), bit 1 = some t0 was >= T (treated as T-1) or a row timestep given to
  * tsdp_verify was outside 0..T-1 (clamped), bit 2 = some running environment had sigma_scale <= 0 or NaN (not

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libtsdp.so")
 
 EXPORTS = ["tsdp_create", "tsdp_destroy", "tsdp_load_weights", "tsdp_set_cond", "tsdp_draft", "tsdp_verify",
            "tsdp_accept", "tsdp_round", "tsdp_accept_threshold", "tsdp_round_threshold", "tsdp_chain", "tsdp_chain_staged",
-           "tsdp_distill_loss", "tsdp_status", "tsdp_kernel_timing", "tsdp_kernel_ms", "tsdp_path_name",
+           "tsdp_distill_loss", "tsdp_distill_loss_noalloc", "tsdp_status", "tsdp_kernel_timing", "tsdp_kernel_ms", "tsdp_path_name",
            "tsdp_last_error"]
 
 
@@ -54,6 +54,7 @@ def load_library():
     lib.tsdp_chain.argtypes = [vp, i32] + [vp] * 6 + [i32, i32] + [vp] * 3 + [C.POINTER(C.c_int32), vp]
     lib.tsdp_chain_staged.argtypes = [vp, i32] + [vp] * 5 + [i32, i32, vp, i32, i32] + [vp] * 3 + [C.POINTER(C.c_int32), vp]
     lib.tsdp_distill_loss.argtypes = [vp, i32, vp, vp, vp, vp, C.c_float, C.c_float, vp, vp]
+    lib.tsdp_distill_loss_noalloc.argtypes = lib.tsdp_distill_loss.argtypes
     lib.tsdp_status.argtypes = [vp, vp, C.POINTER(C.c_int32)]
     lib.tsdp_kernel_timing.argtypes = [vp, i32]
     lib.tsdp_kernel_ms.argtypes = [vp, i32, C.POINTER(C.c_float)]
@@ -245,6 +246,13 @@ class Tsdp:
                                              _ptr(rows["eps_p"], torch.float32), _ptr(rows["eps_q"], torch.float32),
                                              lambda1, lambda2, _ptr(loss), _stream(stream)))
         return loss
+
+    def tsdp_distill_loss_noalloc(self, R, rows, lambda1, lambda2, loss, stream=None):
+        """`loss`: caller-allocated float64[3] device tensor (this entry point allocates nothing)."""
+        self._chk(self.lib.tsdp_distill_loss_noalloc(self.ctx, R, _ptr(rows["row_t"], torch.int32),
+                                                     _ptr(rows["states"], torch.float32), _ptr(rows["eps_p"], torch.float32),
+                                                     _ptr(rows["eps_q"], torch.float32), lambda1, lambda2,
+                                                     _ptr(loss, torch.float64), _stream(stream)))
 
     def tsdp_round(self, x, t, K, sigma_scale, env_id, n_accept=None, n_advanced=None, stream=None):
         self._chk(self.lib.tsdp_round(self.ctx, x.shape[0], _ptr(x, torch.float32), _ptr(t, torch.int32),

@@ -55,8 +55,18 @@ struct Net {
 
 }  // namespace
 
+// Scratch of tsdp_distill_loss_noalloc: the per-workgroup partial sums of the loss (one pair of doubles per 16
+// rows) live in a file-scope device array instead of context memory, so that entry point allocates nothing.  Every
+// GPU holds its own copy; host code uses the address hipGetSymbolAddress returns for the current device, looked up
+// once per device in tsdp_create, never the symbol itself.
+constexpr int NOALLOC_MAX_ROWS = 65536;
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static __device__ __align__(256) double scratch[2 * (NOALLOC_MAX_ROWS / 16) + 2];
+static double* g_scratch_ptr[NOALLOC_MAX_DEVICES];   // device address of `scratch` on each device, null until looked up
+
 struct tsdp_ctx {
   tsdp_config cfg;
+  int device = -1;              // the device that was current in tsdp_create
   int D = 0;
   std::string err;
   float* tables = nullptr;      // 6 x T fp32: sqrt_abar, sqrt_1m, c0, cx, sigma, ce
@@ -584,6 +594,12 @@ int tsdp_create(const tsdp_config* cfg, tsdp_ctx** out) {
     return cleanup(TSDP_E_HIP);
   c->tb = {c->tables, c->tables + T, c->tables + 2 * T, c->tables + 3 * T, c->tables + 4 * T, c->tables + 5 * T, T};
   if (dev_alloc(c, &c->status, 1) || dev_alloc(c, &c->K_eff, (size_t)f.B_max)) return cleanup(TSDP_E_NOMEM);
+  if (hipGetDevice(&c->device) != hipSuccess || c->device < 0 || c->device >= NOALLOC_MAX_DEVICES) return cleanup(TSDP_E_HIP);
+  if (!g_scratch_ptr[c->device]) {
+    double* p = nullptr;
+    if (hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)) != hipSuccess || !p) return cleanup(TSDP_E_HIP);
+    g_scratch_ptr[c->device] = p;
+  }
   if (hipMemset(c->status, 0, sizeof(int32_t)) != hipSuccess) return cleanup(TSDP_E_HIP);
   *out = c;
   return TSDP_OK;
@@ -992,6 +1008,22 @@ int tsdp_distill_loss(tsdp_ctx* c, int R, const int32_t* d_row_t, const float* d
     if (rc) return rc;
   }
   return distill_launch(c, R, d_row_t, d_states, d_eps_p, d_eps_q, lambda1, lambda2, c->loss_partial, d_loss,
+                        (hipStream_t)stream);
+}
+
+int tsdp_distill_loss_noalloc(tsdp_ctx* c, int R, const int32_t* d_row_t, const float* d_states, const float* d_eps_p,
+                              const float* d_eps_q, float lambda1, float lambda2, double* d_loss, void* stream) {
+  if (!c) return TSDP_E_INVAL;
+  if (R < 0 || R > NOALLOC_MAX_ROWS)
+    return fail(c, TSDP_E_SHAPE, "tsdp_distill_loss_noalloc: R outside 0.." + std::to_string(NOALLOC_MAX_ROWS) +
+                                     " (the size of the static scratch)");
+  if (!d_loss || (R > 0 && (!d_row_t || !d_states || !d_eps_p || !d_eps_q)))
+    return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_distill_loss_noalloc");
+  int dev = -1;
+  HIPCHK(c, hipGetDevice(&dev));
+  if (dev != c->device || !g_scratch_ptr[dev])
+    return fail(c, TSDP_E_STATE, "tsdp_distill_loss_noalloc must run with the context's device current");
+  return distill_launch(c, R, d_row_t, d_states, d_eps_p, d_eps_q, lambda1, lambda2, g_scratch_ptr[dev], d_loss,
                         (hipStream_t)stream);
 }
 
