@@ -167,19 +167,27 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
-// sums v over the 16 lanes of a quarter wave
-__device__ __forceinline__ double group16_sum(double v) {
+// sums v over the G consecutive lanes of a lane group (G a power of two)
+template <int G>
+__device__ __forceinline__ double group_sum(double v) {
 #pragma unroll
-  for (int o = 8; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  for (int o = G / 2; o > 0; o >>= 1) v += __shfl_xor(v, o);
   return v;
 }
 
-// Acceptance: one wavefront per environment, four rows at a time (one row per group of 16 lanes).  Each
-// group streams eps_p, eps_q, xi (and the state when x0 is clamped) of its row with 16-byte loads, reduces
-// |d|^2 and <d,xi> in fp64 and tests log U <= log alpha; the wave keeps the first rejection and finally
-// writes the committed or the reflected latent.  All loads of a row are issued before the first use.  xi may be
-// null: the noise of a row is then regenerated from its Philox counters (seed, environment, timestep).
-template <bool CLIP, int MAXI>
+__device__ __forceinline__ double group16_sum(double v) { return group_sum<16>(v); }
+
+// Acceptance: one wavefront per environment, 64/G rows at a time (one row per group of G lanes; the host picks G so
+// that the D/4 16-byte vectors of a row fill the lanes: 8 lanes x 5 vectors at D = 160, 16 x 7 at D = 448).  Each
+// group streams eps_p, eps_q, xi (and the state when x0 is clamped) of its row with 16-byte loads, all of them
+// issued before the first use, reduces |d|^2 and <d,xi> in fp64 and tests log U <= log alpha; the wave keeps the
+// first rejection and finally writes the committed or the reflected latent.  Rows after the pass that holds the
+// first rejection are not read (the method discards them) unless per-row diagnostics are requested.  xi may be
+// null (REGEN): the noise of a row is then regenerated from its Philox counters (seed, environment, timestep).
+// Every load is unconditional (a slot outside its row, or a group without a row, re-reads an address inside the
+// environment's rows and its value is masked out of the sums): a load under a lane-dependent condition becomes a
+// branch with its own wait, which serialises the stream.
+template <bool CLIP, bool REGEN, int G, int MAXI>
 __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __restrict__ row_ptr,
                                                 const int32_t* __restrict__ row_t, const int32_t* __restrict__ env_id,
                                                 const float* __restrict__ sigma_scale, const float* __restrict__ states,
@@ -192,8 +200,9 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
                                                 int32_t* __restrict__ n_accept, int32_t* __restrict__ n_adv,
                                                 uint8_t* __restrict__ flags, float* __restrict__ logratio,
                                                 float* __restrict__ logu_out) {
-  // MAXI = float4 per lane and row: rows of up to 16*MAXI*4 elements
-  const int lane = threadIdx.x & 63, grp = lane >> 4, gl = lane & 15;
+  // MAXI = 16-byte vectors per lane and row: rows of up to G*MAXI*4 elements
+  constexpr int RPP = 64 / G;                       // rows per pass
+  const int lane = threadIdx.x & 63, grp = lane / G, gl = lane % G;
   const int b = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (b >= B) return;
   const int r0 = row_ptr[b], r1 = row_ptr[b + 1];
@@ -217,12 +226,13 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
   }
   const double s = (double)sigma_scale[b];
   const int env = env_id ? env_id[b] : b;
+  const bool diag = flags || logratio || logu_out;  // diagnostics cover every row: no pass is skipped
   int jstar = 0;                                    // 0 = no rejection yet; else 1-based row index
   double rej_dd = 0.0, rej_dx = 0.0;
-  for (int rb = r0; rb < rd && jstar == 0; rb += 4) {
+  for (int rb = r0; rb < rd && (jstar == 0 || diag); rb += RPP) {
     const int r = rb + grp;
-    const bool live = r < rd;
-    const int rr = live ? r : rd - 1;               // idle groups re-read the last row (in bounds), result unused
+    const bool live = r < rd;                       // a group without a row re-reads the last one; its result is unused
+    const int rr = live ? r : rd - 1;
     const float4* ep = reinterpret_cast<const float4*>(eps_p + (long long)rr * D);
     const float4* eq = reinterpret_cast<const float4*>(eps_q + (long long)rr * D);
     const float4* zz = reinterpret_cast<const float4*>(xi + (long long)rr * D);
@@ -230,18 +240,15 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
     float4 p[MAXI], q[MAXI], z[MAXI], y[MAXI];
 #pragma unroll
     for (int it = 0; it < MAXI; ++it) {
-      const int i = gl + 16 * it;
-      if (i < nb) {
-        p[it] = ep[i]; q[it] = eq[i];
-        if (xi) z[it] = zz[i];
-        if (CLIP) y[it] = st[i];
-      }
+      const int i = min(gl + G * it, nb - 1);
+      p[it] = ep[i]; q[it] = eq[i];
+      if (!REGEN) z[it] = zz[i];
+      if (CLIP) y[it] = st[i];
     }
     const int t = row_t[rr];
-    if (!xi) {                                      // no stored noise: the same Philox blocks the drafter drew
+    if (REGEN) {                                    // no stored noise: the same Philox blocks the drafter drew
 #pragma unroll
-      for (int it = 0; it < MAXI; ++it)
-        if (gl + 16 * it < nb) z[it] = xi_block(seed, env, t, gl + 16 * it);
+      for (int it = 0; it < MAXI; ++it) z[it] = xi_block(seed, env, t, min(gl + G * it, nb - 1));
     }
     const double sa = tb.sqrt_abar[t], s1 = tb.sqrt_1m[t], c0 = tb.c0[t], ce = tb.ce[t], sig = s * (double)tb.sigma[t];
     // stochastic test: log U;  threshold rule p = min(1, alpha) >= lambda  <=>  log alpha >= log lambda (lambda <= 1)
@@ -251,28 +258,29 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
     double dd = 0.0, dx = 0.0;
 #pragma unroll
     for (int it = 0; it < MAXI; ++it) {
-      if (gl + 16 * it < nb) {
-        const float pp[4] = {p[it].x, p[it].y, p[it].z, p[it].w}, qq[4] = {q[it].x, q[it].y, q[it].z, q[it].w},
-                    zv[4] = {z[it].x, z[it].y, z[it].z, z[it].w};
-        if (CLIP) {
-          const float yy[4] = {y[it].x, y[it].y, y[it].z, y[it].w};
+      const bool in = gl + G * it < nb;             // always true when the row fills the lanes exactly
+      const float pp[4] = {p[it].x, p[it].y, p[it].z, p[it].w}, qq[4] = {q[it].x, q[it].y, q[it].z, q[it].w},
+                  zv[4] = {z[it].x, z[it].y, z[it].z, z[it].w};
+      if (CLIP) {
+        const float yy[4] = {y[it].x, y[it].y, y[it].z, y[it].w};
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const double xp = fmin(fmax(((double)yy[j] - s1 * (double)pp[j]) / sa, -cv), cv);
-            const double xq = fmin(fmax(((double)yy[j] - s1 * (double)qq[j]) / sa, -cv), cv);
-            const double de = c0 * (xp - xq) + ce * ((double)pp[j] - (double)qq[j]);
-            dd = fma(de, de, dd); dx = fma(de, (double)zv[j], dx);
-          }
-        } else {
+        for (int j = 0; j < 4; ++j) {
+          const double xp = fmin(fmax(((double)yy[j] - s1 * (double)pp[j]) / sa, -cv), cv);
+          const double xq = fmin(fmax(((double)yy[j] - s1 * (double)qq[j]) / sa, -cv), cv);
+          double de = c0 * (xp - xq) + ce * ((double)pp[j] - (double)qq[j]);
+          de = in ? de : 0.0;
+          dd = fma(de, de, dd); dx = fma(de, (double)zv[j], dx);
+        }
+      } else {
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {             // x0_p - x0_q = -(s1/sa)(eps_p - eps_q)
-            const double de = (double)pp[j] - (double)qq[j];
-            dd = fma(de, de, dd); dx = fma(de, (double)zv[j], dx);
-          }
+        for (int j = 0; j < 4; ++j) {               // x0_p - x0_q = -(s1/sa)(eps_p - eps_q)
+          double de = (double)pp[j] - (double)qq[j];
+          de = in ? de : 0.0;
+          dd = fma(de, de, dd); dx = fma(de, (double)zv[j], dx);
         }
       }
     }
-    dd = group16_sum(dd); dx = group16_sum(dx);
+    dd = group_sum<G>(dd); dx = group_sum<G>(dx);
     const double kap = CLIP ? 1.0 / sig : (ce - (c0 * s1) / sa) / sig;   // d = kap * delta
     const double n2 = kap * kap * dd, ip = kap * dx;                // |d|^2, <d,xi>
     const double l = -0.5 * n2 - ip;
@@ -282,55 +290,12 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
       if (logratio) logratio[r] = (float)l;
       if (logu_out) logu_out[r] = (float)lu;
     }
-    // first rejected row among the (up to) four of this pass
+    // first rejected row among the rows of this pass
     const unsigned long long rejmask = __ballot(live && !acc);
-    if (rejmask) {
-      const int g = (__ffsll((long long)rejmask) - 1) >> 4;
+    if (rejmask && jstar == 0) {
+      const int g = (__ffsll((long long)rejmask) - 1) / G;
       jstar = rb + g - r0 + 1;
-      rej_dd = __shfl(n2, g * 16); rej_dx = __shfl(ip, g * 16);
-      if (flags || logratio || logu_out) {          // diagnostics cover every row: finish the remaining passes
-        for (int r2 = rb + 4; r2 < rd; r2 += 4) {
-          const int q2 = r2 + grp;
-          if (q2 < rd) {
-            const int t2 = row_t[q2];
-            const double sa2 = tb.sqrt_abar[t2], s12 = tb.sqrt_1m[t2], c02 = tb.c0[t2], ce2 = tb.ce[t2],
-                         sig2 = s * (double)tb.sigma[t2];
-            const float4* ep2 = reinterpret_cast<const float4*>(eps_p + (long long)q2 * D);
-            const float4* eq2 = reinterpret_cast<const float4*>(eps_q + (long long)q2 * D);
-            const float4* zz2 = reinterpret_cast<const float4*>(xi + (long long)q2 * D);
-            const float4* st2 = reinterpret_cast<const float4*>(states + (long long)q2 * D);
-            double dd2 = 0.0, dx2 = 0.0;
-            for (int i = gl; i < nb; i += 16) {
-              const float4 a4 = ep2[i], b4 = eq2[i], c4 = xi ? zz2[i] : xi_block(seed, env, t2, i);
-              const float pp[4] = {a4.x, a4.y, a4.z, a4.w}, qq[4] = {b4.x, b4.y, b4.z, b4.w}, zv[4] = {c4.x, c4.y, c4.z, c4.w};
-              float yy[4] = {0, 0, 0, 0};
-              if (CLIP) { const float4 y4 = st2[i]; yy[0] = y4.x; yy[1] = y4.y; yy[2] = y4.z; yy[3] = y4.w; }
-#pragma unroll
-              for (int j = 0; j < 4; ++j) {
-                double de;
-                if (CLIP) {
-                  const double xp = fmin(fmax(((double)yy[j] - s12 * (double)pp[j]) / sa2, -cv), cv);
-                  const double xq = fmin(fmax(((double)yy[j] - s12 * (double)qq[j]) / sa2, -cv), cv);
-                  de = c02 * (xp - xq) + ce2 * ((double)pp[j] - (double)qq[j]);
-                } else {
-                  de = (double)pp[j] - (double)qq[j];
-                }
-                dd2 = fma(de, de, dd2); dx2 = fma(de, (double)zv[j], dx2);
-              }
-            }
-            // 16-lane reductions below are executed by whole groups only (q2 depends on grp, not on gl)
-            dd2 = group16_sum(dd2); dx2 = group16_sum(dx2);
-            const double kap2 = CLIP ? 1.0 / sig2 : (ce2 - (c02 * s12) / sa2) / sig2;
-            const double l2 = -0.5 * kap2 * kap2 * dd2 - kap2 * dx2;
-            const double lu2 = lambda ? log((double)lambda[b]) : log((double)accept_uniform(seed, env, t2));
-            if (gl == 0) {
-              if (flags) flags[q2] = lu2 <= l2 ? 1 : 0;
-              if (logratio) logratio[q2] = (float)l2;
-              if (logu_out) logu_out[q2] = (float)lu2;
-            }
-          }
-        }
-      }
+      rej_dd = __shfl(n2, g * G); rej_dx = __shfl(ip, g * G);
     }
   }
   const int K_eff = rd - r0;
@@ -343,7 +308,7 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
     const float4* zz = reinterpret_cast<const float4*>(xi + (long long)rd * D);
     for (int i = lane; i < nb; i += 64) {
       const float4 y = st[i], e = eq[i];
-      const float4 z = t > 0 ? (xi ? zz[i] : xi_block(seed, env, t, i)) : make_float4(0.f, 0.f, 0.f, 0.f);
+      const float4 z = t > 0 ? (REGEN ? xi_block(seed, env, t, i) : zz[i]) : make_float4(0.f, 0.f, 0.f, 0.f);
       const float yy[4] = {y.x, y.y, y.z, y.w}, ee[4] = {e.x, e.y, e.z, e.w}, zv[4] = {z.x, z.y, z.z, z.w};
       float o[4];
 #pragma unroll
@@ -374,7 +339,7 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
     const float4* zz = reinterpret_cast<const float4*>(xi + (long long)r * D);
     const float4* st = reinterpret_cast<const float4*>(states + (long long)r * D);
     for (int i = lane; i < nb; i += 64) {
-      const float4 p = ep[i], q = eq[i], z = xi ? zz[i] : xi_block(seed, env, t, i), y = st[i];
+      const float4 p = ep[i], q = eq[i], z = REGEN ? xi_block(seed, env, t, i) : zz[i], y = st[i];
       const float pp[4] = {p.x, p.y, p.z, p.w}, qq[4] = {q.x, q.y, q.z, q.w}, zv[4] = {z.x, z.y, z.z, z.w},
                   yy[4] = {y.x, y.y, y.z, y.w};
       float o[4];

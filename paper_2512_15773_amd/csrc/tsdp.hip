@@ -840,13 +840,22 @@ static int accept_impl(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32
   const int wpb = 4;                                // environments (wavefronts) per workgroup
   const dim3 g((B + wpb - 1) / wpb), blk(64 * wpb);
   tick(c, 2, 0, s);
-  const int maxi = (c->D / 4 + 15) / 16;            // float4 per lane and row, 1..8 (H*A <= 512 is checked at create)
-#define TSDP_ACCEPT(CL, MI)                                                                                     \
-  hipLaunchKernelGGL((k_accept<CL, MI>), g, blk, 0, s, B, c->D, d_row_ptr, d_row_t, d_env_id, d_sigma_scale,   \
+  // lanes per row: the D/4 vectors of a row should fill them (8 lanes x 5 at D = 160, 16 x 7 at D = 448); at most 8 per lane
+  const int nb = c->D / 4;
+  const int maxi8 = (nb + 7) / 8, maxi16 = (nb + 15) / 16;
+  const bool g8 = maxi8 <= 8 && nb * 16 * maxi16 > nb * 8 * maxi8;   // the 8-lane mapping fits and idles fewer lanes
+  const int maxi = g8 ? maxi8 : maxi16;
+#define TSDP_ACCEPT(CL, GG, MI)                                                                                 \
+  if (d_xi) TSDP_ACCEPT_X(CL, false, GG, MI); else TSDP_ACCEPT_X(CL, true, GG, MI)
+#define TSDP_ACCEPT_X(CL, RG, GG, MI)                                                                           \
+  hipLaunchKernelGGL((k_accept<CL, RG, GG, MI>), g, blk, 0, s, B, c->D, d_row_ptr, d_row_t, d_env_id, d_sigma_scale, \
                      d_states, d_eps_p, d_eps_q, d_xi, d_y_last, c->tb, cf.clip_val, cf.seed, d_lambda, cf.bonus_row, d_x_out, d_t_next, \
                      d_n_accept, d_n_adv, d_flags, d_logratio, d_logu)
-#define TSDP_ACCEPT_MI(MI) \
-  case MI: if (cf.clip_x0) TSDP_ACCEPT(true, MI); else TSDP_ACCEPT(false, MI); break;
+#define TSDP_ACCEPT_MI(MI)                                                       \
+  case MI:                                                                       \
+    if (cf.clip_x0) { if (g8) TSDP_ACCEPT(true, 8, MI); else TSDP_ACCEPT(true, 16, MI); }    \
+    else            { if (g8) TSDP_ACCEPT(false, 8, MI); else TSDP_ACCEPT(false, 16, MI); }  \
+    break;
   switch (maxi) {
     TSDP_ACCEPT_MI(1) TSDP_ACCEPT_MI(2) TSDP_ACCEPT_MI(3) TSDP_ACCEPT_MI(4)
     TSDP_ACCEPT_MI(5) TSDP_ACCEPT_MI(6) TSDP_ACCEPT_MI(7) TSDP_ACCEPT_MI(8)
@@ -854,6 +863,7 @@ static int accept_impl(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32
   }
 #undef TSDP_ACCEPT_MI
 #undef TSDP_ACCEPT
+#undef TSDP_ACCEPT_X
   tick(c, 2, 1, s);
   HIPCHK(c, hipGetLastError());
   return TSDP_OK;
