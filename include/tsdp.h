@@ -177,6 +177,29 @@ int tsdp_chain_staged(tsdp_ctx* ctx, int B, float* d_x, int32_t* d_t, const int3
                       int check_every, int32_t* d_tot_accept, int32_t* d_tot_drafts, int32_t* d_tot_rounds,
                       int32_t* h_rounds, void* stream);
 
+/* The same chain with no host round trip (Section 1 and Section 3.2, the inference loop; Section 3.3 for the stage
+ * tables): exactly n_rounds rounds are enqueued on `stream` and the call returns; nothing is read back and nothing
+ * synchronises.  Every kernel of a round reads the round's live row count on the device and returns at once when no
+ * environment is running any more, so rounds past the end of the chain cost a few empty launches and leave latents,
+ * timesteps and totals untouched.  A round advances every running environment by at least one step, so
+ * n_rounds = (largest t) + 1 <= T always completes the chain.  Finished environments own no rows: the ragged verify
+ * batch of a round holds the running environments only, and tiles beyond its live row count exit.
+ * staged = 0: d_K[B], d_sigma_scale[B], d_lambda[B] (NULL = stochastic test) as in tsdp_chain; staged = 1: [B,3] stage
+ * tables with the bounds t_hi >= t_lo >= 0 as in tsdp_chain_staged.  Totals as in tsdp_chain (device, NULL to skip);
+ * d_rounds_run (device int32, NULL to skip) receives the number of rounds in which some environment ran.
+ * The call records kernel launches only (no memset, no copy) and allocates nothing once the context's buffers exist
+ * (after tsdp_prepare, or after any earlier round / chain call): it can be captured in a HIP graph and replayed.
+ * Results are bit-identical to tsdp_chain / tsdp_chain_staged. */
+int tsdp_chain_enqueue(tsdp_ctx* ctx, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
+                       const float* d_lambda, int staged, int t_hi, int t_lo, const int32_t* d_env_id, int n_rounds,
+                       int32_t* d_tot_accept, int32_t* d_tot_drafts, int32_t* d_tot_rounds, int32_t* d_rounds_run,
+                       void* stream);
+
+/* Allocates every buffer later calls on this context may need (network workspace, round and chain buffers) and sets
+ * the launch attributes of its kernels, so that the calls that follow allocate nothing: to be called once, after both
+ * tsdp_load_weights, before a round or chain is captured in a HIP graph.  Synchronous; enqueues no work. */
+int tsdp_prepare(tsdp_ctx* ctx);
+
 /* Forward value of the drafter's distillation objective (Section 3.2, Draft Model Training) over R rows:
  * L_pred = mean_r |eps_p[r] - eps_q[r]|^2, L_norm = mean over rows with t > 0 of |(mu_p - mu_q)/sigma_t|^2 (DDPM
  * means from the same state, unscaled sigma_t), L = lambda1 L_pred + lambda2 L_norm.  fp64 reduction in a fixed

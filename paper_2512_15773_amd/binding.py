@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libtsdp.so")
 
 EXPORTS = ["tsdp_create", "tsdp_destroy", "tsdp_load_weights", "tsdp_set_cond", "tsdp_draft", "tsdp_verify",
            "tsdp_accept", "tsdp_round", "tsdp_accept_threshold", "tsdp_round_threshold", "tsdp_chain", "tsdp_chain_staged",
+           "tsdp_chain_enqueue", "tsdp_prepare",
            "tsdp_distill_loss", "tsdp_distill_loss_noalloc", "tsdp_status", "tsdp_kernel_timing", "tsdp_kernel_ms", "tsdp_path_name",
            "tsdp_last_error"]
 
@@ -53,6 +54,8 @@ def load_library():
     lib.tsdp_round_threshold.argtypes = [vp, i32] + [vp] * 8 + [vp]
     lib.tsdp_chain.argtypes = [vp, i32] + [vp] * 6 + [i32, i32] + [vp] * 3 + [C.POINTER(C.c_int32), vp]
     lib.tsdp_chain_staged.argtypes = [vp, i32] + [vp] * 5 + [i32, i32, vp, i32, i32] + [vp] * 3 + [C.POINTER(C.c_int32), vp]
+    lib.tsdp_chain_enqueue.argtypes = [vp, i32] + [vp] * 5 + [i32, i32, i32, vp, i32] + [vp] * 4 + [vp]
+    lib.tsdp_prepare.argtypes = [vp]
     lib.tsdp_distill_loss.argtypes = [vp, i32, vp, vp, vp, vp, C.c_float, C.c_float, vp, vp]
     lib.tsdp_distill_loss_noalloc.argtypes = lib.tsdp_distill_loss.argtypes
     lib.tsdp_status.argtypes = [vp, vp, C.POINTER(C.c_int32)]
@@ -239,6 +242,23 @@ class Tsdp:
                                              _ptr(tot["drafts"]) if tot else None, _ptr(tot["rounds"]) if tot else None,
                                              C.byref(n), _stream(stream)))
         return n.value, tot
+
+    def tsdp_chain_enqueue(self, x, t, K, sigma_scale, lam, env_id, n_rounds, *, stages=None, totals=None,
+                           rounds_run=None, stream=None):
+        """Enqueues exactly n_rounds rounds with no host round trip.  stages = (t_hi, t_lo) makes K, sigma_scale and
+        lam [B,3] stage tables.  totals: dict of caller-allocated int32[B] device tensors (accept, drafts, rounds) or
+        None; rounds_run: caller-allocated int32[1] device tensor or None."""
+        tot = totals or {}
+        self._chk(self.lib.tsdp_chain_enqueue(self.ctx, x.shape[0], _ptr(x, torch.float32), _ptr(t, torch.int32),
+                                              _ptr(K, torch.int32), _ptr(sigma_scale, torch.float32),
+                                              _ptr(lam, torch.float32), 0 if stages is None else 1,
+                                              0 if stages is None else stages[0], 0 if stages is None else stages[1],
+                                              _ptr(env_id, torch.int32), n_rounds, _ptr(tot.get("accept")),
+                                              _ptr(tot.get("drafts")), _ptr(tot.get("rounds")),
+                                              _ptr(rounds_run, torch.int32), _stream(stream)))
+
+    def tsdp_prepare(self):
+        self._chk(self.lib.tsdp_prepare(self.ctx))
 
     def tsdp_distill_loss(self, R, rows, lambda1, lambda2, stream=None):
         loss = torch.zeros(3, dtype=torch.float64, device=rows["states"].device)

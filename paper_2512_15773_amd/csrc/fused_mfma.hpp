@@ -76,6 +76,7 @@ struct DraftIO {               // drafter rollout
   int mod_cols;                // columns of one in-kernel FiLM product: a multiple of RPT up to 16 (mod_cols/RPT steps at once)
   float* y;                    // [B,H,A]  in: the latents, out: the latents after the last drafted step
   float* states; float* eps_p; float* xi;   // [R,H,A] retained per drafted transition
+  const int32_t* gate;         // chain driver: live row count of the round (0 = every environment finished), or null
 };
 
 __device__ __forceinline__ float gelu_fast(float x) {
@@ -969,6 +970,7 @@ __global__ __launch_bounds__(C::THREADS) void k_fused_draft(FusedNet net, DraftI
   float* dbias = reinterpret_cast<float*>(sgbuf + 16 * SGS);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l16 = lane & 15, lg = lane >> 4;
   const int env0 = blockIdx.x * RPT;
+  if (io.gate && *io.gate == 0) return;
   if (threadIdx.x == 0) s_kmax = 0;
   __syncthreads();
   if (threadIdx.x < RPT) {

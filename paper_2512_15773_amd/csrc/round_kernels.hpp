@@ -13,11 +13,12 @@ struct SchedTables {          // device pointers, fp32[T] each; posterior mean =
 
 // K_eff = min(clamp(K), t0), rows per env = live ? (bonus ? K_eff + 1 : max(K_eff,1)) : 0, exclusive scan into
 // row_ptr[B+1].  K is clamped to 1..K_max (0..K_max with the bonus row, where K = 0 is a plain base step).
-// Single workgroup of 1024 threads, chunks of 1024 environments.
+// n_draft receives B if any environment has rows, else 0.  Single workgroup of 1024 threads, chunks of 1024 environments.
 __global__ __launch_bounds__(1024) void k_plan(const int32_t* __restrict__ t0, const int32_t* __restrict__ K,
                                                const float* __restrict__ sigma_scale,
                                                int B, int K_max, int T, int bonus, int32_t* __restrict__ K_eff,
-                                               int32_t* __restrict__ row_ptr, int32_t* __restrict__ status) {
+                                               int32_t* __restrict__ row_ptr, int32_t* __restrict__ status,
+                                               int32_t* __restrict__ n_draft) {
   __shared__ int32_t part[1024];
   __shared__ int32_t carry;
   if (threadIdx.x == 0) carry = 0;
@@ -48,7 +49,10 @@ __global__ __launch_bounds__(1024) void k_plan(const int32_t* __restrict__ t0, c
     if (threadIdx.x == 1023) carry += part[1023];
     __syncthreads();
   }
-  if (threadIdx.x == 0) row_ptr[B] = carry;
+  if (threadIdx.x == 0) {
+    row_ptr[B] = carry;
+    *n_draft = carry > 0 ? B : 0;                   // environments the drafter has to look at: none once all have finished
+  }
 }
 
 // Range check of a caller-supplied row table (tsdp_verify): copies with the timestep clamped to 0..T-1 and the
@@ -71,7 +75,8 @@ __global__ void k_check_rows(const int32_t* __restrict__ d_R, int R_cap, const i
 __global__ void k_rows(const float* __restrict__ x, const int32_t* __restrict__ t0, const int32_t* __restrict__ row_ptr,
                        int T, int D, int32_t* __restrict__ row_t, int32_t* __restrict__ row_env,
                        float* __restrict__ y, float* __restrict__ states, float* __restrict__ eps_p,
-                       float* __restrict__ xi) {
+                       float* __restrict__ xi, const int32_t* __restrict__ gate) {
+  if (gate && *gate == 0) return;                   // chain driver: no environment is running any more
   const int b = blockIdx.x;
   const int r0 = row_ptr[b], n = row_ptr[b + 1] - r0;
   int t = t0[b];
@@ -131,7 +136,7 @@ __global__ void k_bonus_rows(const int32_t* __restrict__ t0, const int32_t* __re
                              const int32_t* __restrict__ row_ptr, const int32_t* __restrict__ env_id, int T, int D,
                              uint64_t seed, const float* __restrict__ y, float* __restrict__ states,
                              float* __restrict__ eps_p, float* __restrict__ xi) {
-  const int b = blockIdx.x;
+  const int b = blockIdx.x;                          // (an environment without rows returns at once: no gate needed)
   const int r0 = row_ptr[b];
   if (row_ptr[b + 1] == r0) return;
   int t = t0[b];
@@ -199,7 +204,9 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
                                                 float* __restrict__ x_out, int32_t* __restrict__ t_next,
                                                 int32_t* __restrict__ n_accept, int32_t* __restrict__ n_adv,
                                                 uint8_t* __restrict__ flags, float* __restrict__ logratio,
-                                                float* __restrict__ logu_out) {
+                                                float* __restrict__ logu_out, const int32_t* __restrict__ gate) {
+  // chain driver: once no environment is running, latents, timesteps and counters stay as they are
+  if (gate && *gate == 0) return;
   // MAXI = 16-byte vectors per lane and row: rows of up to G*MAXI*4 elements
   constexpr int RPP = 64 / G;                       // rows per pass
   const int lane = threadIdx.x & 63, grp = lane / G, gl = lane % G;
@@ -362,7 +369,9 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
 __global__ void k_chain_accum(int B, const int32_t* __restrict__ t, const int32_t* __restrict__ K_eff,
                               const int32_t* __restrict__ n_acc, const int32_t* __restrict__ n_adv,
                               const int32_t* __restrict__ row_ptr, int32_t* __restrict__ tot_accept,
-                              int32_t* __restrict__ tot_drafts, int32_t* __restrict__ tot_rounds, int32_t* __restrict__ live) {
+                              int32_t* __restrict__ tot_drafts, int32_t* __restrict__ tot_rounds, int32_t* __restrict__ live,
+                              int32_t* __restrict__ rounds_run) {
+  if (rounds_run && blockIdx.x == 0 && threadIdx.x == 0 && row_ptr[B] > 0) *rounds_run += 1;   // a round that had rows
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B) return;
   const bool ran = row_ptr[b + 1] > row_ptr[b];      // the environment had rows in this round
@@ -371,7 +380,7 @@ __global__ void k_chain_accum(int B, const int32_t* __restrict__ t, const int32_
     if (tot_drafts) tot_drafts[b] += K_eff[b];
     if (tot_rounds) tot_rounds[b] += 1;
   }
-  if (t[b] >= 0) atomicAdd(live, 1);
+  if (live && t[b] >= 0) atomicAdd(live, 1);
 }
 
 __global__ void k_fill_i32(int32_t* p, int n, int32_t v) {

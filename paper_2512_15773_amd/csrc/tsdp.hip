@@ -81,6 +81,7 @@ struct tsdp_ctx {
   float* lam_sel = nullptr;
   double* loss_partial = nullptr;   // per-workgroup partial sums of the distillation loss
   int32_t* K_eff = nullptr;     // [B_max]
+  int32_t* n_draft = nullptr;   // B while some environment has rows in the current plan, else 0
   // network workspace (lazy)
   bool ws_ready = false;
   float *h = nullptr, *a = nullptr, *qkv = nullptr, *ao = nullptr, *u = nullptr, *sg = nullptr, *mod = nullptr;
@@ -186,7 +187,7 @@ hipError_t launch_verify(const FusedNet& n, const FusedIO& io, int A, int R_cap,
     attr_set = true;
   }
   const int tiles = (R_cap + C::RPT - 1) / C::RPT;
-  hipLaunchKernelGGL(kern, dim3(tiles), dim3(C::THREADS), C::LDS_B, s, n, io, A);
+  if (tiles > 0) hipLaunchKernelGGL(kern, dim3(tiles), dim3(C::THREADS), C::LDS_B, s, n, io, A);
   return hipSuccess;
 }
 
@@ -208,7 +209,7 @@ hipError_t launch_draft(const FusedNet& n, const DraftIO& io_in, int A, hipStrea
     attr_lds = lds;
   }
   const int tiles = (io.B + C::RPT - 1) / C::RPT;
-  hipLaunchKernelGGL(kern, dim3(tiles), dim3(C::THREADS), lds, s, n, io, A);
+  if (tiles > 0) hipLaunchKernelGGL(kern, dim3(tiles), dim3(C::THREADS), lds, s, n, io, A);
   return hipSuccess;
 }
 
@@ -593,7 +594,8 @@ int tsdp_create(const tsdp_config* cfg, tsdp_ctx** out) {
   if (hipMemcpy(c->tables, tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess)
     return cleanup(TSDP_E_HIP);
   c->tb = {c->tables, c->tables + T, c->tables + 2 * T, c->tables + 3 * T, c->tables + 4 * T, c->tables + 5 * T, T};
-  if (dev_alloc(c, &c->status, 1) || dev_alloc(c, &c->K_eff, (size_t)f.B_max)) return cleanup(TSDP_E_NOMEM);
+  if (dev_alloc(c, &c->status, 1) || dev_alloc(c, &c->K_eff, (size_t)f.B_max) || dev_alloc(c, &c->n_draft, 1))
+    return cleanup(TSDP_E_NOMEM);
   if (hipGetDevice(&c->device) != hipSuccess || c->device < 0 || c->device >= NOALLOC_MAX_DEVICES) return cleanup(TSDP_E_HIP);
   if (!g_scratch_ptr[c->device]) {
     double* p = nullptr;
@@ -738,9 +740,12 @@ int tsdp_set_cond(tsdp_ctx* c, const float* d_cond, int B, void* stream) {
   return TSDP_OK;
 }
 
-int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const int32_t* d_K,
-               const float* d_sigma_scale, const int32_t* d_env_id, int32_t* d_row_ptr, int32_t* d_row_t,
-               int32_t* d_row_env, float* d_states, float* d_eps_p, float* d_xi, float* d_y_last, void* stream) {
+// gated: chain driver -- the row-table kernel also returns at once when no environment has rows (the drafter kernels
+// always do: without rows there is nothing to draft)
+static int draft_impl(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const int32_t* d_K,
+                      const float* d_sigma_scale, const int32_t* d_env_id, int32_t* d_row_ptr, int32_t* d_row_t,
+                      int32_t* d_row_env, float* d_states, float* d_eps_p, float* d_xi, float* d_y_last, bool gated,
+                      void* stream) {
   int rc = check_ready(c, B, true);
   if (rc) return rc;
   if (B == 0) return TSDP_OK;                        // an empty batch is valid and touches nothing
@@ -753,14 +758,14 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
   const tsdp_config& cf = c->cfg;
   const int D = c->D;
   hipLaunchKernelGGL(k_plan, dim3(1), dim3(1024), 0, s, d_t0, d_K, d_sigma_scale, B, cf.K_max, cf.T, cf.bonus_row, c->K_eff,
-                     d_row_ptr, c->status);
+                     d_row_ptr, c->status, c->n_draft);
   auto bonus_rows = [&]() {
     if (cf.bonus_row)
       hipLaunchKernelGGL(k_bonus_rows, dim3(B), dim3(128), 0, s, d_t0, (const int32_t*)c->K_eff, (const int32_t*)d_row_ptr,
                          d_env_id, cf.T, D, cf.seed, (const float*)d_y_last, d_states, d_eps_p, d_xi);
   };
   hipLaunchKernelGGL(k_rows, dim3(B), dim3(128), 0, s, d_x, d_t0, (const int32_t*)d_row_ptr, cf.T, D, d_row_t,
-                     d_row_env, d_y_last, d_states, d_eps_p, d_xi);
+                     d_row_env, d_y_last, d_states, d_eps_p, d_xi, gated ? (const int32_t*)c->n_draft : nullptr);
   Net& dn = c->net[1];
   if (dn.fused) {
     // persistent drafter kernel: pick the tile (environments per workgroup) that fills the chip best
@@ -774,6 +779,7 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
       io.tb = {c->tb.sqrt_abar, c->tb.sqrt_1m, c->tb.c0, c->tb.cx, c->tb.sigma, c->tb.ce, c->tb.T};
       io.clip = cf.clip_x0; io.clip_val = cf.clip_val; io.seed = cf.seed;
       io.y = d_y_last; io.states = d_states; io.eps_p = d_eps_p; io.xi = d_xi;
+      io.gate = c->n_draft;
       tick(c, 0, 0, s);
       HIPCHK(c, (big ? dn.fused_draft_big : dn.fused_draft_small)(dn.fnet, io, cf.A, s));
       tick(c, 0, 1, s);
@@ -784,7 +790,7 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
   }
   for (int k = 1; k <= cf.K_max; ++k) {
     // every environment runs the drafter at step k; the DDPM step masks those with K_eff < k
-    if ((rc = forward(c, c->net[1], d_y_last, B, nullptr, d_t0, k - 1, nullptr, c->eps_tmp, s))) return rc;
+    if ((rc = forward(c, c->net[1], d_y_last, B, c->n_draft, d_t0, k - 1, nullptr, c->eps_tmp, s))) return rc;
     hipLaunchKernelGGL(k_draft_step, grid1((long long)B * (D / 4), 256), dim3(256), 0, s, k, (const float*)c->eps_tmp,
                        d_t0, (const int32_t*)c->K_eff, (const int32_t*)d_row_ptr, d_sigma_scale, d_env_id, c->tb,
                        cf.clip_x0, cf.clip_val, cf.seed, B, D, d_y_last, d_states, d_eps_p, d_xi);
@@ -792,6 +798,13 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
   bonus_rows();
   HIPCHK(c, hipGetLastError());
   return TSDP_OK;
+}
+
+int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const int32_t* d_K,
+               const float* d_sigma_scale, const int32_t* d_env_id, int32_t* d_row_ptr, int32_t* d_row_t,
+               int32_t* d_row_env, float* d_states, float* d_eps_p, float* d_xi, float* d_y_last, void* stream) {
+  return draft_impl(c, B, d_x, d_t0, d_K, d_sigma_scale, d_env_id, d_row_ptr, d_row_t, d_row_env, d_states, d_eps_p, d_xi,
+                    d_y_last, false, stream);
 }
 
 static int verify_impl(tsdp_ctx* c, int B, int R_cap, const int32_t* d_row_ptr, const int32_t* d_row_t,
@@ -827,7 +840,7 @@ static int accept_impl(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32
                        const float* d_sigma_scale, const float* d_lambda, const float* d_states, const float* d_eps_p,
                        const float* d_eps_q, const float* d_xi, const float* d_y_last, float* d_x_out, int32_t* d_t_next,
                        int32_t* d_n_accept, int32_t* d_n_adv, uint8_t* d_flags, float* d_logratio, float* d_logu,
-                       void* stream) {
+                       const int32_t* d_gate, void* stream) {
   int rc = check_ready(c, B, false);
   if (rc) return rc;
   if (B == 0) return TSDP_OK;
@@ -850,7 +863,7 @@ static int accept_impl(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32
 #define TSDP_ACCEPT_X(CL, RG, GG, MI)                                                                           \
   hipLaunchKernelGGL((k_accept<CL, RG, GG, MI>), g, blk, 0, s, B, c->D, d_row_ptr, d_row_t, d_env_id, d_sigma_scale, \
                      d_states, d_eps_p, d_eps_q, d_xi, d_y_last, c->tb, cf.clip_val, cf.seed, d_lambda, cf.bonus_row, d_x_out, d_t_next, \
-                     d_n_accept, d_n_adv, d_flags, d_logratio, d_logu)
+                     d_n_accept, d_n_adv, d_flags, d_logratio, d_logu, d_gate)
 #define TSDP_ACCEPT_MI(MI)                                                       \
   case MI:                                                                       \
     if (cf.clip_x0) { if (g8) TSDP_ACCEPT(true, 8, MI); else TSDP_ACCEPT(true, 16, MI); }    \
@@ -874,7 +887,7 @@ int tsdp_accept(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32_t* d_r
                 const float* d_xi, const float* d_y_last, float* d_x_out, int32_t* d_t_next, int32_t* d_n_accept,
                 int32_t* d_n_adv, uint8_t* d_flags, float* d_logratio, float* d_logu, void* stream) {
   return accept_impl(c, B, d_row_ptr, d_row_t, d_env_id, d_sigma_scale, nullptr, d_states, d_eps_p, d_eps_q, d_xi, d_y_last,
-                     d_x_out, d_t_next, d_n_accept, d_n_adv, d_flags, d_logratio, d_logu, stream);
+                     d_x_out, d_t_next, d_n_accept, d_n_adv, d_flags, d_logratio, d_logu, nullptr, stream);
 }
 
 int tsdp_accept_threshold(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32_t* d_row_t,
@@ -885,20 +898,20 @@ int tsdp_accept_threshold(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const in
   if (c && B > 0 && !d_lambda) return fail(c, TSDP_E_INVAL, "d_lambda is null");
   if (c && B > 0 && !d_xi) return fail(c, TSDP_E_INVAL, "d_xi is null (no environment ids here to regenerate the noise from)");
   return accept_impl(c, B, d_row_ptr, d_row_t, nullptr, d_sigma_scale, d_lambda, d_states, d_eps_p, d_eps_q, d_xi, d_y_last,
-                     d_x_out, d_t_next, d_n_accept, d_n_adv, d_flags, d_logratio, nullptr, stream);
+                     d_x_out, d_t_next, d_n_accept, d_n_adv, d_flags, d_logratio, nullptr, nullptr, stream);
 }
 
 static int round_impl(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
                       const int32_t* d_env_id, const float* d_lambda, int32_t* d_n_accept, int32_t* d_n_advanced,
-                      void* stream) {
+                      bool gated, void* stream) {
   int rc = check_ready(c, B, true);
   if (rc) return rc;
   if (B == 0) return TSDP_OK;
   if (!d_x || !d_t || !d_K || !d_sigma_scale) return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_round");
   if (B == 0) return TSDP_OK;
   if ((rc = ensure_round_buffers(c))) return rc;
-  if ((rc = tsdp_draft(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, c->row_ptr, c->row_t, c->row_env, c->states,
-                       c->eps_p, c->xi, c->y_last, stream)))
+  if ((rc = draft_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, c->row_ptr, c->row_t, c->row_env, c->states,
+                       c->eps_p, c->xi, c->y_last, gated, stream)))
     return rc;
   if ((rc = verify_impl(c, B, B * (c->cfg.K_max + (c->cfg.bonus_row ? 1 : 0)), c->row_ptr, c->row_t, c->row_env, c->states,
                         c->eps_q, true, stream)))
@@ -906,42 +919,52 @@ static int round_impl(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_
   // x and t are overwritten in place: the acceptance kernel reads only the round's own buffers
   return accept_impl(c, B, c->row_ptr, c->row_t, d_env_id, d_sigma_scale, d_lambda, c->states, c->eps_p, c->eps_q, c->xi,
                      c->y_last, d_x, d_t, d_n_accept ? d_n_accept : c->n_acc, d_n_advanced ? d_n_advanced : c->n_adv,
-                     nullptr, nullptr, nullptr, stream);
+                     nullptr, nullptr, nullptr, gated ? (const int32_t*)c->n_draft : nullptr, stream);
 }
 
 int tsdp_round(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
                const int32_t* d_env_id, int32_t* d_n_accept, int32_t* d_n_advanced, void* stream) {
-  return round_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, nullptr, d_n_accept, d_n_advanced, stream);
+  return round_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, nullptr, d_n_accept, d_n_advanced, false, stream);
 }
 
 int tsdp_round_threshold(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
                          const int32_t* d_env_id, const float* d_lambda, int32_t* d_n_accept, int32_t* d_n_advanced,
                          void* stream) {
   if (c && B > 0 && !d_lambda) return fail(c, TSDP_E_INVAL, "d_lambda is null");
-  return round_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, d_lambda, d_n_accept, d_n_advanced, stream);
+  return round_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, d_lambda, d_n_accept, d_n_advanced, false, stream);
 }
 
-static int chain_impl(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
-                      const int32_t* d_env_id, const float* d_lambda, bool staged, int t_hi, int t_lo, int max_rounds,
-                      int check_every, int32_t* d_tot_accept, int32_t* d_tot_drafts, int32_t* d_tot_rounds,
-                      int32_t* h_rounds, void* stream) {
-  int rc = check_ready(c, B, true);
-  if (rc) return rc;
-  if (h_rounds) *h_rounds = 0;
-  if (B == 0) return TSDP_OK;
-  if (!d_x || !d_t || !d_K || !d_sigma_scale) return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_chain");
-  if (max_rounds < 1 || check_every < 1) return fail(c, TSDP_E_INVAL, "max_rounds and check_every must be positive");
-  if (staged && !(t_hi >= t_lo && t_lo >= 0)) return fail(c, TSDP_E_INVAL, "stage bounds must satisfy t_hi >= t_lo >= 0");
+static int ensure_chain_buffers(tsdp_ctx* c) {
+  int rc;
   if ((rc = ensure_round_buffers(c))) return rc;
-  hipStream_t s = (hipStream_t)stream;
-  if (!c->live) {
-    if ((rc = dev_alloc(c, &c->live, 1))) return rc;
-  }
-  if (staged && !c->K_sel) {
+  if (!c->live && (rc = dev_alloc(c, &c->live, 1))) return rc;
+  if (!c->K_sel) {
     if ((rc = dev_alloc(c, &c->K_sel, (size_t)c->cfg.B_max))) return rc;
     if ((rc = dev_alloc(c, &c->s_sel, (size_t)c->cfg.B_max))) return rc;
     if ((rc = dev_alloc(c, &c->lam_sel, (size_t)c->cfg.B_max))) return rc;
   }
+  return TSDP_OK;
+}
+
+// host_checked: rounds are enqueued until the number of running environments, read back every check_every rounds,
+// is zero (or max_rounds is reached).  Otherwise exactly max_rounds rounds are enqueued and nothing is read back:
+// the kernels of a round return at once when the round's row table is empty (every environment has finished).
+static int chain_impl(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
+                      const int32_t* d_env_id, const float* d_lambda, bool staged, int t_hi, int t_lo, int max_rounds,
+                      int check_every, bool host_checked, int32_t* d_tot_accept, int32_t* d_tot_drafts,
+                      int32_t* d_tot_rounds, int32_t* h_rounds, int32_t* d_rounds_run, void* stream) {
+  int rc = check_ready(c, B, true);
+  if (rc) return rc;
+  if (h_rounds) *h_rounds = 0;
+  if (!host_checked && max_rounds < 0) return fail(c, TSDP_E_INVAL, "n_rounds must not be negative");
+  hipStream_t s = (hipStream_t)stream;
+  if (d_rounds_run) hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(1), 0, s, d_rounds_run, 1, 0);
+  if (B == 0) return TSDP_OK;
+  if (!d_x || !d_t || !d_K || !d_sigma_scale) return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_chain");
+  if (host_checked && (max_rounds < 1 || check_every < 1))
+    return fail(c, TSDP_E_INVAL, "max_rounds and check_every must be positive");
+  if (staged && !(t_hi >= t_lo && t_lo >= 0)) return fail(c, TSDP_E_INVAL, "stage bounds must satisfy t_hi >= t_lo >= 0");
+  if ((rc = ensure_chain_buffers(c))) return rc;
   const dim3 gb((B + 255) / 256), blk(256);
   for (int32_t* p : {d_tot_accept, d_tot_drafts, d_tot_rounds})
     if (p) hipLaunchKernelGGL(k_fill_i32, gb, blk, 0, s, p, B, 0);
@@ -952,18 +975,17 @@ static int chain_impl(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_
       hipLaunchKernelGGL(k_stage_select, gb, blk, 0, s, B, (const int32_t*)d_t, t_hi, t_lo, d_K, d_sigma_scale, d_lambda,
                          c->K_sel, c->s_sel, c->lam_sel);
       rc = round_impl(c, B, d_x, d_t, c->K_sel, c->s_sel, d_env_id, d_lambda ? c->lam_sel : nullptr, c->n_acc, c->n_adv,
-                      stream);
+                      !host_checked, stream);
     } else {
-      rc = round_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, d_lambda, c->n_acc, c->n_adv, stream);
+      rc = round_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, d_lambda, c->n_acc, c->n_adv, !host_checked, stream);
     }
     if (rc) return rc;
     ++rounds;
-    const bool check = rounds % check_every == 0 || rounds == max_rounds;
-    hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(1), 0, s, c->live, 1, 0);
+    if (host_checked) hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(1), 0, s, c->live, 1, 0);
     hipLaunchKernelGGL(k_chain_accum, gb, blk, 0, s, B, (const int32_t*)d_t, (const int32_t*)c->K_eff,
                        (const int32_t*)c->n_acc, (const int32_t*)c->n_adv, (const int32_t*)c->row_ptr, d_tot_accept,
-                       d_tot_drafts, d_tot_rounds, c->live);
-    if (check) {
+                       d_tot_drafts, d_tot_rounds, host_checked ? c->live : nullptr, d_rounds_run);
+    if (host_checked && (rounds % check_every == 0 || rounds == max_rounds)) {
       int32_t live = 0;
       HIPCHK(c, hipMemcpyAsync(&live, c->live, sizeof(int32_t), hipMemcpyDeviceToHost, s));
       HIPCHK(c, hipStreamSynchronize(s));
@@ -978,15 +1000,48 @@ static int chain_impl(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_
 int tsdp_chain(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
                const int32_t* d_env_id, const float* d_lambda, int max_rounds, int check_every, int32_t* d_tot_accept,
                int32_t* d_tot_drafts, int32_t* d_tot_rounds, int32_t* h_rounds, void* stream) {
-  return chain_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, d_lambda, false, 0, 0, max_rounds, check_every,
-                    d_tot_accept, d_tot_drafts, d_tot_rounds, h_rounds, stream);
+  return chain_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, d_lambda, false, 0, 0, max_rounds, check_every, true,
+                    d_tot_accept, d_tot_drafts, d_tot_rounds, h_rounds, nullptr, stream);
 }
 
 int tsdp_chain_staged(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K3, const float* d_sigma_scale3,
                       const float* d_lambda3, int t_hi, int t_lo, const int32_t* d_env_id, int max_rounds, int check_every,
                       int32_t* d_tot_accept, int32_t* d_tot_drafts, int32_t* d_tot_rounds, int32_t* h_rounds, void* stream) {
   return chain_impl(c, B, d_x, d_t, d_K3, d_sigma_scale3, d_env_id, d_lambda3, true, t_hi, t_lo, max_rounds, check_every,
-                    d_tot_accept, d_tot_drafts, d_tot_rounds, h_rounds, stream);
+                    true, d_tot_accept, d_tot_drafts, d_tot_rounds, h_rounds, nullptr, stream);
+}
+
+int tsdp_chain_enqueue(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_t* d_K, const float* d_sigma_scale,
+                       const float* d_lambda, int staged, int t_hi, int t_lo, const int32_t* d_env_id, int n_rounds,
+                       int32_t* d_tot_accept, int32_t* d_tot_drafts, int32_t* d_tot_rounds, int32_t* d_rounds_run,
+                       void* stream) {
+  return chain_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, d_lambda, staged != 0, t_hi, t_lo, n_rounds, 0, false,
+                    d_tot_accept, d_tot_drafts, d_tot_rounds, nullptr, d_rounds_run, stream);
+}
+
+int tsdp_prepare(tsdp_ctx* c) {
+  if (!c) return TSDP_E_INVAL;
+  if (!c->net[0].loaded || !c->net[1].loaded) return fail(c, TSDP_E_STATE, "weights of both networks must be loaded");
+  int rc;
+  if ((rc = ensure_workspace(c))) return rc;
+  if ((rc = ensure_chain_buffers(c))) return rc;
+  if (!c->loss_partial && (rc = dev_alloc(c, &c->loss_partial, 2 * ((rows_max(c->cfg) + 15) / 16) + 2))) return rc;
+  // the launch attributes of the fused kernels (dynamic LDS size): a launch over zero rows sets them and enqueues nothing
+  FusedIO io{};
+  DraftIO dio{};
+  Net& bn = c->net[0];
+  if (bn.fused) {
+    if (bn.fused_verify) HIPCHK(c, bn.fused_verify(bn.fnet, io, c->cfg.A, 0, nullptr));
+    if (bn.fused_verify_few) HIPCHK(c, bn.fused_verify_few(bn.fnet, io, c->cfg.A, 0, nullptr));
+  }
+  Net& dn = c->net[1];
+  if (dn.fused) {                                     // the tile variants tsdp_draft may pick (those that fit the LDS)
+    if (fused_draft_lds(dn, c->cfg, dn.draft_rpt_small) <= 160 * 1024)
+      HIPCHK(c, dn.fused_draft_small(dn.fnet, dio, c->cfg.A, nullptr));
+    if (fused_draft_lds(dn, c->cfg, dn.draft_rpt_big) <= 160 * 1024)
+      HIPCHK(c, dn.fused_draft_big(dn.fnet, dio, c->cfg.A, nullptr));
+  }
+  return TSDP_OK;
 }
 
 // partial: room for 2 * ceil(R / 16) doubles; every entry that is read is written first by the same call

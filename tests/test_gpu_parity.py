@@ -591,3 +591,73 @@ def test_action_dim_above_one_head_fragment():
     _stage_parity(wl, 2, np.array([70, 5]), np.array([8, 8]), np.array([1.0, 1.2]), paths=("f32-mfma-fused", "f32-mfma-fused"))
     wl = ti.small_variant(ti.C1, B=2, H=16, A=32)
     _stage_parity(wl, 2, np.array([9, 3]), np.array([4, 4]), np.ones(2), paths=("f32-mfma-fused", "f32-mfma-fused"))
+
+
+def _chain_both_ways(ctx, x0, t0, K, s, lam, env, stages, n_rounds, T):
+    """Host-checked chain and enqueue-only chain (eager, then captured in a HIP graph and replayed three times with
+    eager work between the replays) on the same inputs."""
+    import torch
+    dev = "cuda"
+    Kd, sd = to_dev(K.astype(np.int32)), to_dev(s.astype(np.float32))
+    ld = None if lam is None else to_dev(lam.astype(np.float32))
+    ed = None if env is None else to_dev(env.astype(np.int32))
+    x, t = to_dev(x0), to_dev(t0.astype(np.int32))
+    if stages is None:
+        rounds, tot = ctx.tsdp_chain(x, t, Kd, sd, ed, lam=ld, check_every=1)
+    else:
+        rounds, tot = ctx.tsdp_chain_staged(x, t, Kd, sd, ld, stages[0], stages[1], ed, check_every=1)
+    want = dict(x=x.clone(), t=t.clone(), **{k: v.clone() for k, v in tot.items()})
+    B = x.shape[0]
+    x2, t2 = to_dev(x0), to_dev(t0.astype(np.int32))
+    tot2 = {k: torch.full((B,), -5, dtype=torch.int32, device=dev) for k in ("accept", "drafts", "rounds")}
+    run = torch.full((1,), -5, dtype=torch.int32, device=dev)
+    ctx.tsdp_chain_enqueue(x2, t2, Kd, sd, ld, ed, n_rounds, stages=stages, totals=tot2, rounds_run=run)
+    torch.cuda.synchronize()
+
+    def check(tag):
+        assert int(run.item()) == rounds, (tag, int(run.item()), rounds)
+        assert torch.equal(x2, want["x"]) and torch.equal(t2, want["t"]), tag
+        for k in tot2:
+            assert torch.equal(tot2[k], want[k]), (tag, k)
+
+    check("eager")
+    # captured: kernel launches only, so the whole chain is one graph
+    ctx.tsdp_prepare()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        xw, tw = to_dev(x0), to_dev(t0.astype(np.int32))
+        ctx.tsdp_chain_enqueue(xw, tw, Kd, sd, ld, ed, 2, stages=stages)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ctx.tsdp_chain_enqueue(x2, t2, Kd, sd, ld, ed, n_rounds, stages=stages, totals=tot2, rounds_run=run)
+    for i in range(3):
+        x2.copy_(to_dev(x0)); t2.copy_(to_dev(t0.astype(np.int32)))
+        graph.replay()
+        torch.cuda.synchronize()
+        _ = (x2 * 2).sum().item()                                  # eager work and a synchronisation between replays
+        check(f"replay {i}")
+    assert rounds < n_rounds                                       # rounds past the end ran as empty launches
+    return rounds
+
+
+def test_enqueue_only_chain_is_bit_identical_to_the_host_checked_chain():
+    # C1 (fp32) and C3 (bf16) shapes; plain, bonus row, stage tables with and without the threshold rule
+    for name, B, bonus in (("C1", 6, False), ("C1", 6, True), ("C3", 12, False), ("C3", 12, True)):
+        wl = ti.small_variant(ti.WORKLOADS[name], B=B)
+        S = _setup(wl, B, head_scale=0.6 if name == "C1" else 0.2, bonus=bonus)
+        rng = np.random.default_rng(17)
+        t0 = rng.integers(-1, wl.T, B); t0[0] = wl.T - 1; t0[1] = 0
+        K = rng.integers(0 if bonus else 1, wl.K_max + 1, B); s = rng.uniform(1.0, 1.3, B)
+        env = rng.integers(0, 10 ** 6, B)
+        n = _chain_both_ways(S["ctx"], S["x"], t0, K, s, None, env, None, wl.T + 3, wl.T)
+        assert n >= 1
+        K3 = rng.integers(0 if bonus else 1, wl.K_max + 1, (B, 3)); s3 = rng.uniform(1.0, 1.3, (B, 3))
+        l3 = rng.uniform(0.2, 0.9, (B, 3))
+        stages = (7 * wl.T // 10, 3 * wl.T // 10)
+        _chain_both_ways(S["ctx"], S["x"], t0, K3, s3, None, None, stages, wl.T + 3, wl.T)
+        _chain_both_ways(S["ctx"], S["x"], t0, K3, s3, l3, env, stages, wl.T + 3, wl.T)
+        assert S["ctx"].tsdp_status() == 0
+        S["ctx"].close()
