@@ -366,7 +366,7 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
   __syncthreads();
 
   // writes LN(h) (1 + g) + b as bf16 into act; which = 0 (attention) / 2 (MLP) selects the FiLM pair, -1 = none.
-  // Statistics: per-wave partial sums of x and x^2 (fp32) exchanged through LDS, one barrier.
+  // Statistics: per-wave partial results (fp32) exchanged through LDS, one barrier.
   auto write_ln = [&](int layer, int which) {
     FENCE_LANE_IDS();
     // FiLM vectors of the tile's rows: requested first, so they arrive while the statistics are reduced
@@ -401,15 +401,36 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
         }
       }
     }
+    // Statistics.  fp32 networks (results are held to 1e-5): without cancellation -- every wave reduces the sum of
+    // its D/NW features of a token and then their squared deviations from its own mean (registers only); the NW
+    // (sum, M2) pairs are combined after one barrier, M2 = sum_w M2_w + n_w (mean_w - mean)^2; the roundings are
+    // pinned (no contraction), so every tile variant gives the same bits.  bf16 networks: one pass over x and x^2
+    // (its fp32 cancellation error, 2^-24 mean^2 / var, is far below the bf16 rounding of the operands).
+    // RMSNorm takes the plain second moment either way.
+    constexpr bool CENTRED = std::is_same<TT, TF32>::value;
+    constexpr float NWF = (float)(D / NW);              // features per wave
     float mean[NB], rstd[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       float s = 0.0f, q = 0.0f;
+      if (CENTRED && !net.rms) {
 #pragma unroll
-      for (int mb = 0; mb < MBH; ++mb)
+        for (int mb = 0; mb < MBH; ++mb)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { s += h[mb][nb][i]; q = fmaf(h[mb][nb][i], h[mb][nb][i], q); }
-      s += __shfl_xor(s, 16); s += __shfl_xor(s, 32);
+          for (int i = 0; i < 4; ++i) s += h[mb][nb][i];
+        s += __shfl_xor(s, 16); s += __shfl_xor(s, 32);
+        const float mw = __fmul_rn(s, 1.0f / NWF);
+#pragma unroll
+        for (int mb = 0; mb < MBH; ++mb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { const float dv = __fsub_rn(h[mb][nb][i], mw); q = fmaf(dv, dv, q); }
+      } else {
+#pragma unroll
+        for (int mb = 0; mb < MBH; ++mb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) { s += h[mb][nb][i]; q = fmaf(h[mb][nb][i], h[mb][nb][i], q); }
+        s += __shfl_xor(s, 16); s += __shfl_xor(s, 32);
+      }
       q += __shfl_xor(q, 16); q += __shfl_xor(q, 32);
       if (lane < 16) { red1[wave * NT + nb * 16 + lane] = s; red2[wave * NT + nb * 16 + lane] = q; }
     }
@@ -417,11 +438,22 @@ __device__ __forceinline__ void fused_body(const FusedNet& net, unsigned char* l
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       const int t = nb * 16 + l16;
-      float s = 0.0f, q = 0.0f;
+      float sw[NW], s = 0.0f, q = 0.0f;
 #pragma unroll
-      for (int w = 0; w < NW; ++w) { s += red1[w * NT + t]; q += red2[w * NT + t]; }
+      for (int w = 0; w < NW; ++w) { sw[w] = red1[w * NT + t]; s += sw[w]; q += red2[w * NT + t]; }
       mean[nb] = net.rms ? 0.0f : s * (1.0f / D);     // RMSNorm: no centring, the second moment as it is
-      rstd[nb] = rsqrtf(fmaxf(q * (1.0f / D) - mean[nb] * mean[nb], 0.0f) + 1e-5f);
+      if (CENTRED) {
+        if (!net.rms) {
+#pragma unroll
+          for (int w = 0; w < NW; ++w) {
+            const float dm = __fsub_rn(__fmul_rn(sw[w], 1.0f / NWF), mean[nb]);
+            q = fmaf(__fmul_rn(NWF, dm), dm, q);
+          }
+        }
+        rstd[nb] = rsqrtf(q * (1.0f / D) + 1e-5f);
+      } else {
+        rstd[nb] = rsqrtf(fmaxf(q * (1.0f / D) - mean[nb] * mean[nb], 0.0f) + 1e-5f);
+      }
     }
     float* fs = reinterpret_cast<float*>(lds + C::ACT_B) + wave * (CHK * 4);   // this wave's staged FiLM block
     if (LNST && which >= 0) {

@@ -661,3 +661,25 @@ def test_enqueue_only_chain_is_bit_identical_to_the_host_checked_chain():
         _chain_both_ways(S["ctx"], S["x"], t0, K3, s3, l3, env, stages, wl.T + 3, wl.T)
         assert S["ctx"].tsdp_status() == 0
         S["ctx"].close()
+
+
+def test_layernorm_statistics_survive_a_large_mean_in_fp32():
+    # a residual stream whose mean is 12x its spread (token-embedding bias 0.5 on features of spread 0.04): the
+    # one-pass variance E[x^2] - mean^2 loses 2^-24 mean^2 / var = 1e-5 of the variance in fp32, at the fp32
+    # tolerance; the fused fp32 kernels centre their statistics
+    for wl in (ti.small_variant(ti.C1, B=3), ti.small_variant(ti.C2, B=2, base=ti.NetShape(2, 256, 4))):
+        wb = ti.make_weights(wl, "base", b_std=0.02); wd = ti.make_weights(wl, "draft", b_std=0.02)
+        for w in (wb, wd):
+            w["tok_b"] = (w["tok_b"] + np.float32(0.5)).astype(np.float32)
+        B = wl.B
+        cond, x = ti.make_cond(wl, B), ti.make_latents(wl, B)
+        base, drafter, sched = oracle_side(wl, wb, wd)
+        ctx = gpu_side(wl, wb, wd, cond)
+        assert ctx.path_name(0) == "f32-mfma-fused" and ctx.path_name(1) == "f32-mfma-fused"
+        t0 = np.full(B, wl.T - 2); K = np.full(B, wl.K_max); s = np.ones(B)
+        S = dict(wl=wl, B=B, cond=cond, x=x, base=base, drafter=drafter, sched=sched, ctx=ctx, clip=None, bonus=False,
+                 seed=wl.philox_seed)
+        rows = _gpu_draft(S, t0, K, s, None)
+        o = _check_draft(S, rows, t0, K, s, None, TOL["fp32"])
+        _check_verify(S, rows, o, TOL["fp32"])
+        ctx.close()
