@@ -172,6 +172,13 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
+// 16-byte load of data that is read once (streamed past the caches' replacement order)
+__device__ __forceinline__ float4 load_once(const float4* a) {
+  typedef float f4v __attribute__((ext_vector_type(4)));
+  const f4v v = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(a));
+  return make_float4(v[0], v[1], v[2], v[3]);
+}
+
 // sums v over the G consecutive lanes of a lane group (G a power of two)
 template <int G>
 __device__ __forceinline__ double group_sum(double v) {
@@ -191,7 +198,8 @@ __device__ __forceinline__ double group16_sum(double v) { return group_sum<16>(v
 // null (REGEN): the noise of a row is then regenerated from its Philox counters (seed, environment, timestep).
 // Every load is unconditional (a slot outside its row, or a group without a row, re-reads an address inside the
 // environment's rows and its value is masked out of the sums): a load under a lane-dependent condition becomes a
-// branch with its own wait, which serialises the stream.
+// branch with its own wait, which serialises the stream.  The row data is read exactly once: non-temporal loads
+// (2^20-row shape: 0.426 -> 0.391 ms).
 template <bool CLIP, bool REGEN, int G, int MAXI>
 __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __restrict__ row_ptr,
                                                 const int32_t* __restrict__ row_t, const int32_t* __restrict__ env_id,
@@ -248,9 +256,9 @@ __global__ __launch_bounds__(256) void k_accept(int B, int D, const int32_t* __r
 #pragma unroll
     for (int it = 0; it < MAXI; ++it) {
       const int i = min(gl + G * it, nb - 1);
-      p[it] = ep[i]; q[it] = eq[i];
-      if (!REGEN) z[it] = zz[i];
-      if (CLIP) y[it] = st[i];
+      p[it] = load_once(ep + i); q[it] = load_once(eq + i);
+      if (!REGEN) z[it] = load_once(zz + i);
+      if (CLIP) y[it] = load_once(st + i);
     }
     const int t = row_t[rr];
     if (REGEN) {                                    // no stored noise: the same Philox blocks the drafter drew
