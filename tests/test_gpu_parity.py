@@ -683,3 +683,50 @@ def test_layernorm_statistics_survive_a_large_mean_in_fp32():
         o = _check_draft(S, rows, t0, K, s, None, TOL["fp32"])
         _check_verify(S, rows, o, TOL["fp32"])
         ctx.close()
+
+
+def test_prepare_makes_a_fresh_context_capturable_and_short_chains_stop_where_asked():
+    # tsdp_prepare on a context that has never run: the very first round is recorded into a HIP graph (an allocation
+    # or a launch-attribute call during capture would fail it) and its replay equals the eager round of a second
+    # context; an enqueue-only chain of 2 rounds equals the host-checked chain cut at max_rounds = 2
+    import torch
+    wl = ti.small_variant(ti.C3, B=9)
+    wb = ti.make_weights(wl, "base", head_scale=0.2); wd = ti.make_weights(wl, "draft", head_scale=0.2)
+    cond, x0 = ti.make_cond(wl, 9), ti.make_latents(wl, 9)
+    t0 = np.array([99, 80, 60, 40, 20, 10, 3, 0, -1], np.int32); K = np.full(9, 16, np.int32); s = np.ones(9, np.float32)
+    Kd, sd = to_dev(K), to_dev(s)
+    ref_ctx = gpu_side(wl, wb, wd, cond)
+    xr, tr = to_dev(x0), to_dev(t0)
+    na_r = torch.zeros(9, dtype=torch.int32, device="cuda"); nd_r = torch.zeros_like(na_r)
+    ref_ctx.tsdp_round(xr, tr, Kd, sd, None, na_r, nd_r)
+    torch.cuda.synchronize()
+    ctx = gpu_side(wl, wb, wd, cond)
+    ctx.tsdp_prepare()
+    x, t = to_dev(x0), to_dev(t0)
+    na = torch.zeros(9, dtype=torch.int32, device="cuda"); nd = torch.zeros_like(na)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ctx.tsdp_round(x, t, Kd, sd, None, na, nd)
+    for i in range(2):
+        x.copy_(to_dev(x0)); t.copy_(to_dev(t0))
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in ((x, xr), (t, tr), (na, na_r), (nd, nd_r)):
+            assert torch.equal(got, want), f"replay {i}"
+    # a chain cut short
+    xa, ta = to_dev(x0), to_dev(t0)
+    rounds, tot = ref_ctx.tsdp_chain(xa, ta, Kd, sd, None, max_rounds=2, check_every=1)
+    assert rounds == 2 and (ta.cpu().numpy()[:5] >= 0).all()
+    xb, tb = to_dev(x0), to_dev(t0)
+    totb = {k: torch.zeros(9, dtype=torch.int32, device="cuda") for k in ("accept", "drafts", "rounds")}
+    run = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ctx.tsdp_chain_enqueue(xb, tb, Kd, sd, None, None, 2, totals=totb, rounds_run=run)
+    torch.cuda.synchronize()
+    assert int(run.item()) == 2 and torch.equal(xa, xb) and torch.equal(ta, tb)
+    for k in totb:
+        assert torch.equal(totb[k], tot[k])
+    ctx.tsdp_chain_enqueue(xb, tb, Kd, sd, None, None, 0, rounds_run=run)     # zero rounds: nothing but the counter
+    torch.cuda.synchronize()
+    assert int(run.item()) == 0 and torch.equal(xa, xb)
+    ref_ctx.close(); ctx.close()
