@@ -208,8 +208,10 @@ def test_full_size_bonus_row_with_ddim_sampler():
     ctx.close()
 
 
-def test_speculative_chain_on_the_gpu_has_the_law_of_the_base_chain():
-    # Losslessness end to end on the device: final actions of whole chains driven by an imperfect drafter against
+@pytest.mark.parametrize("variant", ["plain", "bonus_row_ddim_enqueue"])
+def test_speculative_chain_on_the_gpu_has_the_law_of_the_base_chain(variant):
+    # Losslessness end to end on the device (second variant: the K+1 candidate set with the DDIM(0.7) transition, driven
+    # by the enqueue-only chain): final actions of whole chains driven by an imperfect drafter against
     # final actions of the plain base chain (drafter = base, every draft accepted, which the identity test above
     # ties to plain DDPM steps).  Same conditioning for all environments, independent noise seeds and initial
     # latents for the two runs; per-dimension two-sample Kolmogorov-Smirnov tests with a Bonferroni bound.
@@ -222,11 +224,17 @@ def test_speculative_chain_on_the_gpu_has_the_law_of_the_base_chain():
     K = to_dev(np.full(n, 4, np.int32)); s = to_dev(np.ones(n, np.float32))
     finals = []
     rates = []
+    import torch
+    extra = dict(sampler=1, eta=0.7, bonus_row=True) if variant != "plain" else {}
     for run, (wl_run, w_draft, seed) in enumerate(((wl, wd, 11), (ti.small_variant(wl, draft=wl.base), wb, 12))):
-        ctx = gpu_side(wl_run, wb, w_draft, cond, B_max=n, seed=seed)
+        ctx = gpu_side(wl_run, wb, w_draft, cond, B_max=n, seed=seed, **extra)
         x = to_dev(np.random.default_rng(100 + run).standard_normal((n, wl.H, wl.A)).astype(np.float32))
         t = to_dev(np.full(n, wl.T - 1, np.int32))
-        rounds, tot = ctx.tsdp_chain(x, t, K, s, None, check_every=2)
+        if variant == "plain":
+            rounds, tot = ctx.tsdp_chain(x, t, K, s, None, check_every=2)
+        else:
+            tot = {k: torch.zeros(n, dtype=torch.int32, device="cuda") for k in ("accept", "drafts", "rounds")}
+            ctx.tsdp_chain_enqueue(x, t, K, s, None, None, wl.T, totals=tot)
         assert (t.cpu().numpy() == -1).all()
         finals.append(x.cpu().numpy().reshape(n, -1))
         rates.append(tot["accept"].sum().item() / tot["drafts"].sum().item())
@@ -234,7 +242,7 @@ def test_speculative_chain_on_the_gpu_has_the_law_of_the_base_chain():
     assert 0.2 < rates[0] < 0.98 and rates[1] == 1.0                   # rejections happen in the speculative run
     # power of the detector: the drafter's own chain (threshold rule with a vanishing threshold accepts every
     # draft) has a visibly different law
-    ctx = gpu_side(wl, wb, wd, cond, B_max=n, seed=13)
+    ctx = gpu_side(wl, wb, wd, cond, B_max=n, seed=13, **extra)
     x = to_dev(np.random.default_rng(102).standard_normal((n, wl.H, wl.A)).astype(np.float32))
     t = to_dev(np.full(n, wl.T - 1, np.int32))
     ctx.tsdp_chain(x, t, K, s, None, lam=to_dev(np.full(n, 1e-30, np.float32)), check_every=2)

@@ -253,6 +253,16 @@ def test_error_paths_return_codes():
                        torch.ones(2, device="cuda"), None)
     assert e.value.code == -2                                          # B > B_max
     ctx.tsdp_round(x, i, i, f, None)
+    # the enqueue-only chain: negative round count, bad stage bounds, null latents
+    with pytest.raises(TsdpError) as e:
+        ctx.tsdp_chain_enqueue(x, i, i, f, None, None, -1)
+    assert e.value.code == -1
+    with pytest.raises(TsdpError) as e:
+        ctx.tsdp_chain_enqueue(x, i, torch.zeros(1, 3, dtype=torch.int32, device="cuda"), torch.ones(1, 3, device="cuda"),
+                               None, None, 2, stages=(2, 3))
+    assert e.value.code == -1
+    assert ctx.lib.tsdp_chain_enqueue(ctx.ctx, 1, None, None, None, None, None, 0, 0, 0, None, 1, None, None, None, None, None) == -1
+    assert ctx.lib.tsdp_prepare(None) == -1
     ctx.close()
 
 
