@@ -238,7 +238,7 @@ struct FusedKernels {
 // Measured tile choices of the compiled shapes.
 constexpr int NWS128 = 8;        // waves of the one-environment drafter tile, d = 128
 constexpr int NWS256X = 8;       // waves and heads per phase of the one-environment drafter tile, d = 256 with cross-attention
-constexpr int HPS256X = 4;
+constexpr int HPS256X = 8;
 constexpr int F256_NW = 8;       // fp32 d = 256 verify kernel: waves, heads per phase, hidden chunk
 constexpr int F256_HP = 2;
 constexpr int F256_CH = 256;
