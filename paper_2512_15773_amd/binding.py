@@ -280,7 +280,8 @@ class Tsdp:
                                       _ptr(n_accept, torch.int32), _ptr(n_advanced, torch.int32), _stream(stream)))
 
     def tsdp_kernel_timing(self, enable):
-        self._chk(self.lib.tsdp_kernel_timing(self.ctx, 1 if enable else 0))
+        """False / 0 = off, True / 1 = all stages, 2 * mask = chosen stages (mask bit 0 drafter, 1 verify, 2 accept)."""
+        self._chk(self.lib.tsdp_kernel_timing(self.ctx, int(enable)))
 
     def tsdp_kernel_ms(self, stage):
         ms = C.c_float(0)

@@ -1112,15 +1112,16 @@ __global__ __launch_bounds__(C::THREADS) void k_fused_draft(FusedNet net, DraftI
 }
 
 // FiLM vectors of a ragged batch with the matrix cores: mod[r, :] = W_mod SiLU(temb[t_r] + cemb[env_r]) + b_mod
-// for all layers at once.  Tile: 128 rows x 256 outputs per workgroup; the SiLU input rows are built in LDS as
-// bf16 and the weights stream as fragments (FusedNet::modw).
-template <int D>
+// for all layers at once.  Tile: NR rows x 256 outputs per workgroup pass; the SiLU input rows are built in LDS as
+// bf16 and the weights stream as fragments (FusedNet::modw).  NR = 64 keeps the tile under a third of the LDS at
+// d <= 384, so three workgroups share a CU (the kernel is bound by its output stream, R x L*4D fp32).
+template <int D, int NR>
 __global__ __launch_bounds__(256) void k_mod_gemm(const void* __restrict__ modw, const float* __restrict__ modb,
                                                   const float* __restrict__ temb, const float* __restrict__ cemb,
                                                   const int32_t* __restrict__ t_arr, int t_sub,
                                                   const int32_t* __restrict__ env_arr, int T, int Nm,
                                                   const int32_t* d_R, int R_cap, float* __restrict__ mod) {
-  constexpr int NR = 128, NB = NR / 16, MB = 4, AS = D + 8;
+  constexpr int NB = NR / 16, MB = 4, AS = D + 8;
   __shared__ __attribute__((aligned(16))) __bf16 sg[NR * AS];
   const int R = d_R ? min(*d_R, R_cap) : R_cap;
   const int row0 = blockIdx.y * NR;

@@ -93,8 +93,13 @@ struct tsdp_ctx {
   int32_t *row_ptr = nullptr, *row_t = nullptr, *row_env = nullptr, *t_next = nullptr, *n_acc = nullptr, *n_adv = nullptr;
   float *states = nullptr, *eps_p = nullptr, *eps_q = nullptr, *xi = nullptr, *y_last = nullptr;
   std::vector<void*> owned;
+  // A round computes the base network's per-row FiLM vectors (k_mod_gemm, bound by its output stream) on a second
+  // stream of the same priority while the drafter rolls out: forked after the row table, joined before the verify.
+  hipStream_t aux = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   // optional kernel timing: events recorded around the dominant kernel of each stage
   bool timing = false;
+  int timing_mask = 7;          // stages whose kernels are bracketed by events while timing is on (bit = stage)
   hipEvent_t ev[3][2] = {{nullptr, nullptr}, {nullptr, nullptr}, {nullptr, nullptr}};   // draft, verify, accept
   bool ev_used[3] = {false, false, false};
 };
@@ -107,7 +112,7 @@ int fail(tsdp_ctx* c, int code, const std::string& msg) {
 }
 
 inline void tick(tsdp_ctx* c, int stage, int edge, hipStream_t s) {
-  if (c->timing) {
+  if (c->timing && ((c->timing_mask >> stage) & 1)) {
     (void)hipEventRecord(c->ev[stage][edge], s);
     c->ev_used[stage] = true;
   }
@@ -217,10 +222,13 @@ template <int D>
 void launch_mod(const FusedNet& n, const int32_t* t_arr, int t_sub, const int32_t* env_arr, int T, const int32_t* d_R,
                 int R_cap, float* mod, hipStream_t s) {
   const int Nm = n.L * 4 * D;                           // a multiple of 256 because D is a multiple of 64
-  const int row_tiles = (R_cap + 127) / 128;
-  const int fx = std::max(1, std::min(Nm / 256, (768 + row_tiles - 1) / row_tiles));   // about three workgroups per CU
+  constexpr int NR = 64;                                // rows per workgroup
+  const int row_tiles = (R_cap + NR - 1) / NR;
+  // output tiles of 256 features are dealt over blockIdx.x; enough workgroups for about twelve per CU at the row bound
+  // (a ragged batch leaves the tiles beyond its live rows empty)
+  const int fx = std::max(1, std::min(Nm / 256, (3072 + row_tiles - 1) / row_tiles));
   dim3 g(fx, row_tiles);
-  hipLaunchKernelGGL(k_mod_gemm<D>, g, dim3(256), 0, s, n.modw, n.modb, n.temb, n.cemb, t_arr, t_sub, env_arr, T, Nm, d_R,
+  hipLaunchKernelGGL((k_mod_gemm<D, NR>), g, dim3(256), 0, s, n.modw, n.modb, n.temb, n.cemb, t_arr, t_sub, env_arr, T, Nm, d_R,
                      R_cap, mod);
 }
 
@@ -441,14 +449,16 @@ void forward_f32(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int3
 }
 
 // eps[R,H,A] = network(x_rows; t, cond): fused bf16 MFMA kernel where the shape has one, fp32 operators otherwise.
+// mod_ready: the FiLM vectors of these rows are already in c->mod (computed on the auxiliary stream; the caller has
+// made `s` wait for them)
 int forward(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t* d_R, const int32_t* t_arr,
-            int t_sub, const int32_t* env_arr, float* eps_out, hipStream_t s) {
+            int t_sub, const int32_t* env_arr, float* eps_out, hipStream_t s, bool mod_ready = false) {
   if (!n.fused) {
     forward_f32(c, n, x_rows, R_cap, d_R, t_arr, t_sub, env_arr, eps_out, s);
     return TSDP_OK;
   }
   const tsdp_config& cf = c->cfg;
-  if (n.fnet.modtab) {
+  if (n.fnet.modtab || mod_ready) {
     // token conditioning: the FiLM vectors are a function of the timestep only and were tabulated at load time
   } else if (n.fused_mod) {
     n.fused_mod(n.fnet, t_arr, t_sub, env_arr, cf.T, d_R, R_cap, c->mod, s);
@@ -605,6 +615,10 @@ int tsdp_create(const tsdp_config* cfg, tsdp_ctx** out) {
     g_scratch_ptr[c->device] = p;
   }
   if (hipMemset(c->status, 0, sizeof(int32_t)) != hipSuccess) return cleanup(TSDP_E_HIP);
+  if (hipStreamCreateWithFlags(&c->aux, hipStreamNonBlocking) != hipSuccess ||
+      hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess)
+    return cleanup(TSDP_E_HIP);
   *out = c;
   return TSDP_OK;
 }
@@ -615,6 +629,9 @@ void tsdp_destroy(tsdp_ctx* c) {
   for (auto& st : c->ev)
     for (auto& e : st)
       if (e) (void)hipEventDestroy(e);
+  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+  if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+  if (c->aux) (void)hipStreamDestroy(c->aux);
   for (void* p : c->owned) (void)hipFree(p);
   delete c;
 }
@@ -747,7 +764,9 @@ int tsdp_set_cond(tsdp_ctx* c, const float* d_cond, int B, void* stream) {
 static int draft_impl(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const int32_t* d_K,
                       const float* d_sigma_scale, const int32_t* d_env_id, int32_t* d_row_ptr, int32_t* d_row_t,
                       int32_t* d_row_env, float* d_states, float* d_eps_p, float* d_xi, float* d_y_last, bool gated,
-                      void* stream) {
+                      void* stream, int base_mod_rows = 0, bool* base_mod_started = nullptr) {
+  // base_mod_rows > 0 (whole rounds): once the row table exists, the base network's per-row FiLM vectors of up to that
+  // many rows are computed on the auxiliary stream, beside the rollout; *base_mod_started tells the caller to join
   int rc = check_ready(c, B, true);
   if (rc) return rc;
   if (B == 0) return TSDP_OK;                        // an empty batch is valid and touches nothing
@@ -775,6 +794,15 @@ static int draft_impl(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0,
     const int rpt = big ? dn.draft_rpt_big : dn.draft_rpt_small;
     const size_t lds = fused_draft_lds(dn, cf, rpt);
     if (lds <= 160 * 1024) {
+      Net& bn = c->net[0];
+      if (base_mod_rows > 0 && bn.fused && bn.fused_mod && !bn.fnet.modtab) {
+        // fork: the fused rollout keeps its FiLM vectors in LDS, so the shared buffer is free for the base network's
+        HIPCHK(c, hipEventRecord(c->ev_fork, s));
+        HIPCHK(c, hipStreamWaitEvent(c->aux, c->ev_fork, 0));
+        bn.fused_mod(bn.fnet, d_row_t, 0, d_row_env, cf.T, d_row_ptr + B, base_mod_rows, c->mod, c->aux);
+        HIPCHK(c, hipEventRecord(c->ev_join, c->aux));
+        if (base_mod_started) *base_mod_started = true;
+      }
       DraftIO io;
       io.B = B; io.t0 = d_t0; io.K_eff = c->K_eff; io.row_ptr = d_row_ptr; io.sigma_scale = d_sigma_scale;
       io.env_id = d_env_id;
@@ -810,7 +838,8 @@ int tsdp_draft(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0, const 
 }
 
 static int verify_impl(tsdp_ctx* c, int B, int R_cap, const int32_t* d_row_ptr, const int32_t* d_row_t,
-                       const int32_t* d_row_env, const float* d_states, float* d_eps_q, bool own_table, void* stream) {
+                       const int32_t* d_row_env, const float* d_states, float* d_eps_q, bool own_table, void* stream,
+                       bool mod_ready = false) {
   int rc = check_ready(c, B, true);
   if (rc) return rc;
   if (B == 0 || R_cap == 0) return TSDP_OK;
@@ -828,7 +857,8 @@ static int verify_impl(tsdp_ctx* c, int B, int R_cap, const int32_t* d_row_ptr, 
     d_row_t = c->row_t_chk;
     d_row_env = c->row_env_chk;
   }
-  if ((rc = forward(c, c->net[0], d_states, R_cap, d_row_ptr + B, d_row_t, 0, d_row_env, d_eps_q, s))) return rc;
+  if (mod_ready) HIPCHK(c, hipStreamWaitEvent(s, c->ev_join, 0));   // join: the FiLM vectors computed beside the rollout
+  if ((rc = forward(c, c->net[0], d_states, R_cap, d_row_ptr + B, d_row_t, 0, d_row_env, d_eps_q, s, mod_ready))) return rc;
   HIPCHK(c, hipGetLastError());
   return TSDP_OK;
 }
@@ -912,11 +942,12 @@ static int round_impl(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_
   if (!d_x || !d_t || !d_K || !d_sigma_scale) return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_round");
   if (B == 0) return TSDP_OK;
   if ((rc = ensure_round_buffers(c))) return rc;
+  const int R_cap = B * (c->cfg.K_max + (c->cfg.bonus_row ? 1 : 0));
+  bool mod_started = false;
   if ((rc = draft_impl(c, B, d_x, d_t, d_K, d_sigma_scale, d_env_id, c->row_ptr, c->row_t, c->row_env, c->states,
-                       c->eps_p, c->xi, c->y_last, gated, stream)))
+                       c->eps_p, c->xi, c->y_last, gated, stream, R_cap, &mod_started)))
     return rc;
-  if ((rc = verify_impl(c, B, B * (c->cfg.K_max + (c->cfg.bonus_row ? 1 : 0)), c->row_ptr, c->row_t, c->row_env, c->states,
-                        c->eps_q, true, stream)))
+  if ((rc = verify_impl(c, B, R_cap, c->row_ptr, c->row_t, c->row_env, c->states, c->eps_q, true, stream, mod_started)))
     return rc;
   // x and t are overwritten in place: the acceptance kernel reads only the round's own buffers
   return accept_impl(c, B, c->row_ptr, c->row_t, d_env_id, d_sigma_scale, d_lambda, c->states, c->eps_p, c->eps_q, c->xi,
@@ -1111,6 +1142,7 @@ int tsdp_kernel_timing(tsdp_ctx* c, int enable) {
       for (auto& e : st) HIPCHK(c, hipEventCreate(&e));
   }
   c->timing = enable != 0;
+  c->timing_mask = enable <= 1 ? 7 : (enable >> 1) & 7;
   for (bool& u : c->ev_used) u = false;
   return TSDP_OK;
 }
