@@ -90,8 +90,10 @@ def make_problem(wl, point):
     return wb, wd, cond, x, t0, K, s
 
 
-def time_events(fn, iters, torch):
+def time_events(fn, iters, torch, warm=0):
     """Durations (mean, p50, p95 in ms) of fn() on torch's current stream (the stream the library launches on)."""
+    for _ in range(warm):
+        fn()
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
     for a, b in ev:
         a.record(); fn(); b.record()
@@ -402,12 +404,13 @@ def measure_workload(wl, point, steps, warmup, torch, Tsdp, dev, full):
     ctx.tsdp_draft(x0d, t0d, Kd, sd, None, rows)
     ctx.tsdp_verify(wl.B, rows)
     out = ctx.tsdp_accept(wl.B, sd, None, rows, diagnostics=False)
-    n_it = max(10, min(100, steps))
-    t_draft = time_events(lambda: ctx.tsdp_draft(x0d, t0d, Kd, sd, None, rows), n_it, torch)
-    t_verify = time_events(lambda: ctx.tsdp_verify(wl.B, rows), n_it, torch)
-    t_accept = time_events(lambda: ctx.tsdp_accept_into(wl.B, sd, None, rows, out), n_it, torch)
-    t_round = time_events(step, n_it, torch)
-    lat = {"round": dict(zip(("mean", "p50", "p95"), t_round)), "draft": dict(zip(("mean", "p50", "p95"), t_draft)),
+    # the headline workload: 200 launches after 20 warm-ups each; the other workloads a shorter loop
+    n_it, n_warm = (200, 20) if full else (max(10, min(100, steps)), 3)
+    t_draft = time_events(lambda: ctx.tsdp_draft(x0d, t0d, Kd, sd, None, rows), n_it, torch, n_warm)
+    t_verify = time_events(lambda: ctx.tsdp_verify(wl.B, rows), n_it, torch, n_warm)
+    t_accept = time_events(lambda: ctx.tsdp_accept_into(wl.B, sd, None, rows, out), n_it, torch, n_warm)
+    t_round = time_events(step, n_it, torch, n_warm)
+    lat = {"launches_timed": n_it, "warmup_launches": n_warm, "round": dict(zip(("mean", "p50", "p95"), t_round)), "draft": dict(zip(("mean", "p50", "p95"), t_draft)),
            "verify": dict(zip(("mean", "p50", "p95"), t_verify)), "accept": dict(zip(("mean", "p50", "p95"), t_accept))}
     if full:
         # the same step replayed from a captured HIP graph (a round is a fixed launch sequence: no allocation, no host

@@ -16,7 +16,11 @@
  *    neither frees nor keeps caller pointers beyond the work it enqueues (exception: tsdp_set_cond
  *    caches derived tensors in context-owned memory, not the pointer).
  *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).  All work is enqueued on it and
- *    no call synchronises, except tsdp_create / tsdp_load_weights / tsdp_destroy / tsdp_status.
+ *    no call synchronises, except tsdp_create / tsdp_load_weights / tsdp_destroy / tsdp_status.  (Whole rounds --
+ *    tsdp_round, tsdp_round_threshold, the chain drivers -- may run one kernel on a second stream that the context
+ *    owns, of the same priority, forked from `stream` and joined back into it by events inside the call: work
+ *    enqueued on `stream` after the call still runs after all of the call's work, and the fork / join is recorded
+ *    like any other work when `stream` is being captured into a HIP graph.)
  *  - Latents, noise predictions, noises and means are fp32 in every configuration; only the network
  *    internals follow tsdp_config.dtype.  All tensors are dense row-major.
  *  - Timesteps run t = T-1 .. 0; a latent "at t" is x_t; t = -1 marks a finished environment.
