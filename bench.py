@@ -298,10 +298,11 @@ def operating_points(ctx, wl, torch, dev, round_ms):
     return out
 
 
-def chain_section(ctx, wl, torch, dev, x0d, Kd, sd, s):
+def chain_section(ctx, wl, torch, dev, x0d, Kd, sd, s, brief=False):
     """Whole action prediction: every environment from t = T-1 down to the clean action.  The chain is enqueued with
     no host round trip (tsdp_chain_enqueue, T rounds: a round advances every running environment by at least one
-    step) and replayed from one captured HIP graph; the host-checked loop (tsdp_chain) is timed beside it."""
+    step) and replayed from one captured HIP graph; the host-checked loop (tsdp_chain) is timed beside it.
+    brief: the graph-replayed chain only (no host-checked loop, no staged draft counts)."""
     B, T = wl.B, wl.T
     tT = torch.full((B,), T - 1, dtype=torch.int32, device=dev)
     tot = {k: torch.zeros(B, dtype=torch.int32, device=dev) for k in ("accept", "drafts", "rounds")}
@@ -330,14 +331,17 @@ def chain_section(ctx, wl, torch, dev, x0d, Kd, sd, s):
         assert bool((tc == -1).all())
         a, d, r = (float(tot[k].float().mean().item()) for k in ("accept", "drafts", "rounds"))
         # host-checked loop on the same inputs
-        xh, th = x0d.clone(), tT.clone()
-        torch.cuda.synchronize(); tic = time.perf_counter()
-        if stages is None:
-            n_host, _ = ctx.tsdp_chain(xh, th, Kt, st, None, check_every=4, totals=False)
-        else:
-            n_host, _ = ctx.tsdp_chain_staged(xh, th, Kt, st, None, stages[0], stages[1], None, check_every=4, totals=False)
-        torch.cuda.synchronize(); el_host = time.perf_counter() - tic
-        assert torch.equal(xh, xc)
+        n_host = el_host = None
+        if not brief:
+            xh, th = x0d.clone(), tT.clone()
+            torch.cuda.synchronize(); tic = time.perf_counter()
+            if stages is None:
+                n_host, _ = ctx.tsdp_chain(xh, th, Kt, st, None, check_every=4, totals=False)
+            else:
+                n_host, _ = ctx.tsdp_chain_staged(xh, th, Kt, st, None, stages[0], stages[1], None, check_every=4,
+                                                  totals=False)
+            torch.cuda.synchronize(); el_host = time.perf_counter() - tic
+            assert torch.equal(xh, xc)
         out[name] = {"driver": "tsdp_chain_enqueue, one HIP graph of T rounds, no host round trip",
                      "denoising_steps": T, "rounds_enqueued": T, "rounds_run": int(run.item()), "seconds": best,
                      "action_predictions_per_s": B / best, "denoising_steps_per_s": B * T / best,
@@ -352,6 +356,9 @@ def chain_section(ctx, wl, torch, dev, x0d, Kd, sd, s):
             out[name]["stage_bounds"] = list(stages)
 
     measure("chain", None, Kd, sd)
+    if brief:
+        del out["chain"]["host_checked_loop"]
+        return out
     # the same chain with a three-stage draft count (the scheduler's hook): one draft per round while the noise is
     # high and acceptance is nil, the full count in the middle, half of it for the last steps
     K3 = np.tile(np.array([1, wl.K_max, max(1, wl.K_max // 2)], dtype=np.int32), (B, 1))
@@ -360,6 +367,54 @@ def chain_section(ctx, wl, torch, dev, x0d, Kd, sd, s):
     measure("chain_staged", (9 * T // 10, min(wl.K_max, T // 4)), K3d, s3d)
     out["chain_staged"]["K_by_stage"] = [1, wl.K_max, max(1, wl.K_max // 2)]
     return out
+
+
+def plain_chain(wl, point, torch, Tsdp, dev):
+    """The chain without speculation, on the same kernels: T rounds with a draft count of zero, each one base-model
+    evaluation and one sampler step per environment (a context with the bonus row: its only verify row is the current
+    state).  What the paper's speed-up columns divide by (Tables 1-3: vanilla Diffusion Policy)."""
+    wb, wd, cond, x, _, _, s = make_problem(wl, point)
+    ctx = Tsdp.from_workload(wl, bonus_row=True)
+    ctx.tsdp_load_weights(0, ti.pack_blob(wb)); ctx.tsdp_load_weights(1, ti.pack_blob(wd))
+    ctx.tsdp_set_cond(torch.from_numpy(cond).to(dev))
+    B, T = wl.B, wl.T
+    x0d, sd = torch.from_numpy(x).to(dev), torch.from_numpy(s).to(dev)
+    K0 = torch.zeros(B, dtype=torch.int32, device=dev)
+    tT = torch.full((B,), T - 1, dtype=torch.int32, device=dev)
+    xc, tc = x0d.clone(), tT.clone()
+    ctx.tsdp_prepare()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ctx.tsdp_chain_enqueue(xc, tc, K0, sd, None, None, 2)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        ctx.tsdp_chain_enqueue(xc, tc, K0, sd, None, None, T)
+    best = None
+    for _ in range(2):
+        xc.copy_(x0d); tc.copy_(tT)
+        torch.cuda.synchronize(); tic = time.perf_counter()
+        graph.replay()
+        torch.cuda.synchronize(); el = time.perf_counter() - tic
+        best = el if best is None else min(best, el)
+    assert bool((tc == -1).all())
+    del graph
+    ctx.close()
+    return best
+
+
+def action_prediction(chain, plain_s, wl):
+    """Latency of one whole action prediction with and without speculation (the paper's Table 5 quantity)."""
+    return {"tsdp_chain_ms": 1e3 * chain["seconds"], "plain_chain_ms": 1e3 * plain_s,
+            "speedup_over_plain_chain": plain_s / chain["seconds"],
+            "predictions_per_s": wl.B / chain["seconds"], "plain_predictions_per_s": wl.B / plain_s,
+            "mean_rounds_per_env": chain["mean_rounds_per_env"],
+            "nfe_fraction_of_plain_chain": chain["nfe_fraction_of_plain_chain"],
+            "acceptance_of_all_drafts": chain["acceptance_of_all_drafts"],
+            "note": "same kernels, same GPU, both replayed from one HIP graph; the plain chain is T rounds of one base "
+                    "evaluation per environment"}
 
 
 def measure_workload(wl, point, steps, warmup, torch, Tsdp, dev, full):
@@ -593,6 +648,7 @@ def main():
                **{k: v for k, v in res.items() if k not in ("metric", "value", "unit", "ms_per_step", "dtype")})
     if not args.no_chain:
         res.update(chain_section(ctx, wl, torch, dev, st["x0d"], st["Kd"], st["sd"], st["problem"][6]))
+        res["action_prediction"] = action_prediction(res["chain"], plain_chain(wl, args.point, torch, Tsdp, dev), wl)
     if not args.no_points and args.point == "calibrated":
         res["operating_points"] = operating_points(ctx, wl, torch, dev, st["t_round"][0])
     ctx.close()
@@ -607,16 +663,22 @@ def main():
             if name == wl.name:
                 r = res
             else:
-                r, s2 = measure_workload(ti.WORKLOADS[name], args.point, max(10, min(30, args.steps)), 3, torch, Tsdp,
-                                         dev, full=False)
+                w2 = ti.WORKLOADS[name]
+                r, s2 = measure_workload(w2, args.point, max(10, min(30, args.steps)), 3, torch, Tsdp, dev, full=False)
+                if not args.no_chain:
+                    ch = chain_section(s2["ctx"], w2, torch, dev, s2["x0d"], s2["Kd"], s2["sd"], s2["problem"][6],
+                                       brief=True)["chain"]
                 s2["ctx"].close()
                 del s2
+                if not args.no_chain:
+                    r["action_prediction"] = action_prediction(ch, plain_chain(w2, args.point, torch, Tsdp, dev), w2)
             table[name] = {"accepted_steps_per_s": r["value"], "round_ms": r["latency_ms"]["round"]["mean"],
                            "draft_ms": r["latency_ms"]["draft"]["mean"], "verify_ms": r["latency_ms"]["verify"]["mean"],
                            "accept_ms": r["latency_ms"]["accept"]["mean"], "verify_rows": r["config"]["verify_rows"],
                            "steps_advanced_per_round": r["round"]["steps_advanced_per_round"],
                            "acceptance_of_all_drafts": r["round"]["acceptance_of_all_drafts"],
-                           "paths": r["config"]["paths"], "roofline": r["roofline"], "drafter": r.get("drafter")}
+                           "paths": r["config"]["paths"], "roofline": r["roofline"], "drafter": r.get("drafter"),
+                           "action_prediction": r.get("action_prediction")}
         res["workloads"] = table
     print(json.dumps(res))
     if args.pmc_copy:

@@ -13,7 +13,8 @@ struct SchedTables {          // device pointers, fp32[T] each; posterior mean =
 
 // K_eff = min(clamp(K), t0), rows per env = live ? (bonus ? K_eff + 1 : max(K_eff,1)) : 0, exclusive scan into
 // row_ptr[B+1].  K is clamped to 1..K_max (0..K_max with the bonus row, where K = 0 is a plain base step).
-// n_draft receives B if any environment has rows, else 0.  Single workgroup of 1024 threads, chunks of 1024 environments.
+// n_draft[0] receives B if any environment has rows, else 0; n_draft[1] receives B if any environment drafts
+// (K_eff > 0), else 0.  Single workgroup of 1024 threads, chunks of 1024 environments.
 __global__ __launch_bounds__(1024) void k_plan(const int32_t* __restrict__ t0, const int32_t* __restrict__ K,
                                                const float* __restrict__ sigma_scale,
                                                int B, int K_max, int T, int bonus, int32_t* __restrict__ K_eff,
@@ -23,9 +24,10 @@ __global__ __launch_bounds__(1024) void k_plan(const int32_t* __restrict__ t0, c
   __shared__ int32_t carry;
   if (threadIdx.x == 0) carry = 0;
   __syncthreads();
+  int any_draft = 0;
   for (int base = 0; base < B; base += 1024) {
     const int b = base + threadIdx.x;
-    int n = 0;
+    int n = 0, drafts = 0;
     if (b < B) {
       int k = K[b], t = t0[b];
       const int k_min = bonus ? 0 : 1;
@@ -34,10 +36,11 @@ __global__ __launch_bounds__(1024) void k_plan(const int32_t* __restrict__ t0, c
       if (t >= 0 && !(sigma_scale[b] > 0.0f)) atomicOr(status, 4);   // divides the mean difference: reported, not corrected
       const int ke = t < 0 ? 0 : (k < t ? k : t);
       K_eff[b] = ke;
+      drafts = ke;
       n = t < 0 ? 0 : (bonus ? ke + 1 : (ke > 1 ? ke : 1));
     }
     part[threadIdx.x] = n;
-    __syncthreads();
+    any_draft |= __syncthreads_or(drafts > 0);
     for (int o = 1; o < 1024; o <<= 1) {            // inclusive Hillis-Steele scan
       const int v = threadIdx.x >= o ? part[threadIdx.x - o] : 0;
       __syncthreads();
@@ -51,7 +54,8 @@ __global__ __launch_bounds__(1024) void k_plan(const int32_t* __restrict__ t0, c
   }
   if (threadIdx.x == 0) {
     row_ptr[B] = carry;
-    *n_draft = carry > 0 ? B : 0;                   // environments the drafter has to look at: none once all have finished
+    n_draft[0] = carry > 0 ? B : 0;                 // environments with rows: none once all have finished
+    n_draft[1] = any_draft ? B : 0;                 // environments the drafter has to look at: none in a round of plain base steps
   }
 }
 

@@ -81,7 +81,7 @@ struct tsdp_ctx {
   float* lam_sel = nullptr;
   double* loss_partial = nullptr;   // per-workgroup partial sums of the distillation loss
   int32_t* K_eff = nullptr;     // [B_max]
-  int32_t* n_draft = nullptr;   // B while some environment has rows in the current plan, else 0
+  int32_t* n_draft = nullptr;   // [0] B while some environment has rows in the current plan, [1] B while one drafts; else 0
   // network workspace (lazy)
   bool ws_ready = false;
   float *h = nullptr, *a = nullptr, *qkv = nullptr, *ao = nullptr, *u = nullptr, *sg = nullptr, *mod = nullptr;
@@ -606,7 +606,7 @@ int tsdp_create(const tsdp_config* cfg, tsdp_ctx** out) {
   if (hipMemcpy(c->tables, tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice) != hipSuccess)
     return cleanup(TSDP_E_HIP);
   c->tb = {c->tables, c->tables + T, c->tables + 2 * T, c->tables + 3 * T, c->tables + 4 * T, c->tables + 5 * T, T};
-  if (dev_alloc(c, &c->status, 1) || dev_alloc(c, &c->K_eff, (size_t)f.B_max) || dev_alloc(c, &c->n_draft, 1))
+  if (dev_alloc(c, &c->status, 1) || dev_alloc(c, &c->K_eff, (size_t)f.B_max) || dev_alloc(c, &c->n_draft, 2))
     return cleanup(TSDP_E_NOMEM);
   if (hipGetDevice(&c->device) != hipSuccess || c->device < 0 || c->device >= NOALLOC_MAX_DEVICES) return cleanup(TSDP_E_HIP);
   if (!g_scratch_ptr[c->device]) {
@@ -809,7 +809,7 @@ static int draft_impl(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0,
       io.tb = {c->tb.sqrt_abar, c->tb.sqrt_1m, c->tb.c0, c->tb.cx, c->tb.sigma, c->tb.ce, c->tb.T};
       io.clip = cf.clip_x0; io.clip_val = cf.clip_val; io.seed = cf.seed;
       io.y = d_y_last; io.states = d_states; io.eps_p = d_eps_p; io.xi = d_xi;
-      io.gate = c->n_draft;
+      io.gate = c->n_draft + 1;
       tick(c, 0, 0, s);
       HIPCHK(c, (big ? dn.fused_draft_big : dn.fused_draft_small)(dn.fnet, io, cf.A, s));
       tick(c, 0, 1, s);
@@ -820,7 +820,7 @@ static int draft_impl(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0,
   }
   for (int k = 1; k <= cf.K_max; ++k) {
     // every environment runs the drafter at step k; the DDPM step masks those with K_eff < k
-    if ((rc = forward(c, c->net[1], d_y_last, B, c->n_draft, d_t0, k - 1, nullptr, c->eps_tmp, s))) return rc;
+    if ((rc = forward(c, c->net[1], d_y_last, B, c->n_draft + 1, d_t0, k - 1, nullptr, c->eps_tmp, s))) return rc;
     hipLaunchKernelGGL(k_draft_step, grid1((long long)B * (D / 4), 256), dim3(256), 0, s, k, (const float*)c->eps_tmp,
                        d_t0, (const int32_t*)c->K_eff, (const int32_t*)d_row_ptr, d_sigma_scale, d_env_id, c->tb,
                        cf.clip_x0, cf.clip_val, cf.seed, B, D, d_y_last, d_states, d_eps_p, d_xi);
