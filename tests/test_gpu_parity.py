@@ -421,6 +421,33 @@ def test_bonus_row_stages_rounds_and_chain():
     ctx.close()
 
 
+def test_draft_count_zero_is_the_plain_base_chain():
+    # bonus-row context, K = 0 everywhere: every round is one base evaluation and one sampler step per environment
+    # (no drafter work at all), so the chain is the base model's own reverse process with the round's noise stream
+    for wl, B, dtype, paths in ((ti.small_variant(ti.C1, B=3), 3, "fp32", None),
+                                (ti.small_variant(ti.C3, B=5), 5, "bf16", ("bf16-mfma-fused", "bf16-mfma-fused"))):
+        S = _setup(wl, B, bonus=True)
+        if paths is not None:
+            assert (S["ctx"].path_name(0), S["ctx"].path_name(1)) == paths
+        t0 = np.full(B, min(wl.T - 1, 9)); t0[-1] = 3           # a short chain: bf16 rounding adds up over the steps
+        s = np.linspace(1.0, 1.4, B)
+        x = to_dev(S["x"]); t = to_dev(t0.astype(np.int32))
+        K0 = to_dev(np.zeros(B, dtype=np.int32))
+        rounds, tot = S["ctx"].tsdp_chain(x, t, K0, to_dev(s.astype(np.float32)), None, check_every=1)
+        assert rounds == t0.max() + 1 and (t.cpu().numpy() == -1).all()
+        np.testing.assert_array_equal(tot["rounds"].cpu().numpy(), t0 + 1)
+        np.testing.assert_array_equal(tot["drafts"].cpu().numpy(), 0)
+        ref = S["x"].astype(np.float64); tt = t0.copy()
+        while (tt >= 0).any():
+            live = tt >= 0
+            step = sr.base_chain_step(S["base"], S["sched"], ref[live], tt[live], s[live], np.arange(B)[live], S["seed"],
+                                      S["cond"][live])
+            ref[live] = step
+            tt[live] -= 1
+        assert_latents_close(x.cpu().numpy(), ref, dtype, "final actions of the plain chain")
+        S["ctx"].close()
+
+
 def test_staged_chain_follows_the_stage_tables():
     wl = ti.small_variant(ti.C1, B=6)
     S = _setup(wl, 6, head_scale=0.6)
