@@ -421,6 +421,29 @@ def test_bonus_row_stages_rounds_and_chain():
     ctx.close()
 
 
+@pytest.mark.parametrize("bonus", [False, True])
+def test_row_table_of_a_batch_of_several_thousand_environments(bonus):
+    # the plan kernel scans environments in chunks of 1024: a batch over several chunks with a ragged tail, finished
+    # environments, t0 = 0 and (bonus row) K = 0 against the oracle's row table; the base rows' states are the inputs
+    B = 2500
+    wl = ti.small_variant(ti.C1, B=B)
+    rng = np.random.default_rng(77)
+    t0 = rng.integers(-1, wl.T, B); K = rng.integers(0 if bonus else 1, wl.K_max + 1, B)
+    t0[1023:1026] = [0, -1, wl.T - 1]; K[1023:1026] = [wl.K_max, 1, 0 if bonus else 1]
+    S = _setup(wl, B, bonus=bonus)
+    rows = _gpu_draft(S, t0, K, np.ones(B), None)
+    K_eff, row_ptr, row_env, row_t = sr.plan_rows(t0, K, bonus)
+    R = int(row_ptr[-1])
+    np.testing.assert_array_equal(rows["row_ptr"].cpu().numpy(), row_ptr)
+    np.testing.assert_array_equal(rows["row_t"].cpu().numpy()[:R], row_t)
+    np.testing.assert_array_equal(rows["row_env"].cpu().numpy()[:R], row_env)
+    first = row_ptr[:-1][np.diff(row_ptr) > 0]                       # every running environment's first row holds x
+    live = np.flatnonzero(np.diff(row_ptr) > 0)
+    np.testing.assert_array_equal(rows["states"].cpu().numpy()[first], S["x"][live])
+    assert S["ctx"].tsdp_status() == 0
+    S["ctx"].close()
+
+
 def test_draft_count_zero_is_the_plain_base_chain():
     # bonus-row context, K = 0 everywhere: every round is one base evaluation and one sampler step per environment
     # (no drafter work at all), so the chain is the base model's own reverse process with the round's noise stream
