@@ -773,7 +773,6 @@ static int draft_impl(tsdp_ctx* c, int B, const float* d_x, const int32_t* d_t0,
   if (!d_x || !d_t0 || !d_K || !d_sigma_scale || !d_row_ptr || !d_row_t || !d_row_env || !d_states || !d_eps_p ||
       !d_y_last)
     return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_draft");
-  if (B == 0) return TSDP_OK;
   if ((rc = ensure_workspace(c))) return rc;
   hipStream_t s = (hipStream_t)stream;
   const tsdp_config& cf = c->cfg;
@@ -879,7 +878,6 @@ static int accept_impl(tsdp_ctx* c, int B, const int32_t* d_row_ptr, const int32
   if (!d_row_ptr || !d_row_t || !d_sigma_scale || !d_states || !d_eps_p || !d_eps_q || !d_y_last || !d_x_out ||
       !d_t_next || !d_n_accept)
     return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_accept");
-  if (B == 0) return TSDP_OK;
   hipStream_t s = (hipStream_t)stream;
   const tsdp_config& cf = c->cfg;
   const int wpb = 4;                                // environments (wavefronts) per workgroup
@@ -940,7 +938,6 @@ static int round_impl(tsdp_ctx* c, int B, float* d_x, int32_t* d_t, const int32_
   if (rc) return rc;
   if (B == 0) return TSDP_OK;
   if (!d_x || !d_t || !d_K || !d_sigma_scale) return fail(c, TSDP_E_INVAL, "null pointer passed to tsdp_round");
-  if (B == 0) return TSDP_OK;
   if ((rc = ensure_round_buffers(c))) return rc;
   const int R_cap = B * (c->cfg.K_max + (c->cfg.bonus_row ? 1 : 0));
   bool mod_started = false;
