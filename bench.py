@@ -102,6 +102,63 @@ def time_events(fn, iters, torch, warm=0):
     return float(np.mean(ts)), ts[len(ts) // 2], ts[min(len(ts) - 1, int(0.95 * len(ts)))]
 
 
+def engine_clock_while(fn, iters, torch):
+    """Engine clock (MHz) and board power (W) read from the driver's sysfs files while `iters` launches of fn() run back
+    to back (medians of the samples taken after the first 150 ms; None where the files cannot be read).  The published
+    peaks assume the 2.4 GHz peak engine clock; under matrix-core load the board holds its power limit instead."""
+    import glob
+    dpm = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
+    pw = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") +
+                glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average"))
+    if not dpm:
+        return None
+    done = torch.cuda.Event()
+    tic = time.perf_counter()
+    for _ in range(iters):
+        fn()
+    done.record()
+    clk, watts = [], []
+    while not done.query():
+        time.sleep(0.05)
+        if time.perf_counter() - tic < 0.15:
+            continue
+        try:
+            m = re.search(r"(\d+)\s*Mhz\s*\*", open(dpm[0]).read())
+            if m:
+                clk.append(int(m.group(1)))
+            if pw:
+                watts.append(int(open(pw[0]).read()) * 1e-6)
+        except (OSError, ValueError):
+            break
+    torch.cuda.synchronize()
+    if not clk:
+        return None
+    return {"sclk_mhz": float(np.median(clk)), "board_power_w": float(np.median(watts)) if watts else None,
+            "samples": len(clk)}
+
+
+def library_gemm_reference(wl, rows, torch):
+    """What the matrix cores deliver on this machine to the vendor library's plain bf16 GEMM (torch.matmul), as context for
+    the roofline fraction: a large cube, and the three weight products of one layer of the workload's base network at
+    the verify batch's token count (no LayerNorm, attention, GELU or residual around them)."""
+    tokens, d = rows * wl.H, wl.base.d
+    out = {}
+    for name, (M, N, K) in (("cube_8192", (8192, 8192, 8192)), ("qkv_projection", (tokens, 3 * d, d)),
+                            ("mlp_up_projection", (tokens, 4 * d, d)), ("mlp_down_projection", (tokens, d, 4 * d))):
+        a = torch.randn(M, K, device="cuda", dtype=torch.bfloat16)
+        b = torch.randn(K, N, device="cuda", dtype=torch.bfloat16)
+        c = torch.empty(M, N, device="cuda", dtype=torch.bfloat16)
+        fl = 2.0 * M * N * K
+        n = max(20, int(3e14 / fl))
+        ms = time_events(lambda: torch.matmul(a, b, out=c), n, torch, warm=5)[0]
+        clock = engine_clock_while(lambda: torch.matmul(a, b, out=c), 5 * n, torch)
+        out[name] = {"m_n_k": [M, N, K], "ms": ms, "tflops": fl / ms / 1e9, "frac_of_peak": fl / ms / 1e9 / PEAK_BF16_TFLOPS,
+                     "sclk_mhz": clock["sclk_mhz"] if clock else None,
+                     "board_power_w": clock["board_power_w"] if clock else None}
+        del a, b, c
+    return out
+
+
 def time_kernel(ctx, fn, stage, iters):
     """Mean duration (ms) of the dominant kernel of a stage, from the library's own HIP events."""
     ctx.tsdp_kernel_timing(True)
@@ -504,12 +561,22 @@ def measure_workload(wl, point, steps, warmup, torch, Tsdp, dev, full):
            "latency_ms": lat}
     if bf16 and fused:
         achieved = flops / (k_ms * 1e-3) / 1e12
+        clock = engine_clock_while(lambda: ctx.tsdp_verify(wl.B, rows), max(50, int(600 / max(k_ms, 0.05))), torch) \
+            if full else None
         traffic = profile_value("verify_forward_hbm_traffic_c4_c5.txt", f"traffic_bytes_per_launch_{wl.name}")
         res["roofline"] = {"kernel": kname, "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                            "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                            "traffic_source": "profiles/verify_forward_hbm_traffic_c4_c5.txt" if traffic else None,
                            "kernel_ms": k_ms, "kernel_ms_median": k_med,
                            "kernel_ms_last_timed_step": last_verify_kernel_ms, "algorithmic_flops_per_launch": flops}
+        if clock is not None:
+            # context, not the roofline fraction: the clock the board sustains under this kernel (power-limited) and the
+            # matrix peak scaled to it
+            res["roofline"]["engine_clock_under_kernel"] = dict(
+                clock, nominal_mhz=2400, peak_at_this_clock=PEAK_BF16_TFLOPS * clock["sclk_mhz"] / 2400.0,
+                frac_of_peak_at_this_clock=achieved / (PEAK_BF16_TFLOPS * clock["sclk_mhz"] / 2400.0))
+        if full:
+            res["roofline"]["library_gemm_on_this_box"] = library_gemm_reference(wl, R, torch)
     else:
         # fp32 networks at batch 1: a handful of workgroups, each streaming all weights; bound by latency, no
         # roofline fraction is claimed (the achieved rate is reported against the fp32 vector peak for scale only)
