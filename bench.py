@@ -108,10 +108,17 @@ def engine_clock_while(fn, iters, torch):
     peaks assume the 2.4 GHz peak engine clock; under matrix-core load the board holds its power limit instead."""
     import glob
     dpm = sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"))
-    pw = sorted(glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input") +
-                glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_average"))
+    if len(dpm) > 1:
+        # several cards in the host: the one whose PCI bus number is that of torch's current device
+        bus = getattr(torch.cuda.get_device_properties(torch.cuda.current_device()), "pci_bus_id", None)
+        match = [p for p in dpm
+                 if re.search(r":([0-9a-f]{2}):[0-9a-f]{2}\.[0-9]$", os.path.realpath(os.path.dirname(p))) and
+                 int(re.search(r":([0-9a-f]{2}):[0-9a-f]{2}\.[0-9]$", os.path.realpath(os.path.dirname(p))).group(1), 16) == bus]
+        dpm = match[:1]
     if not dpm:
         return None
+    dev_dir = os.path.dirname(dpm[0])
+    pw = sorted(glob.glob(dev_dir + "/hwmon/hwmon*/power1_input") + glob.glob(dev_dir + "/hwmon/hwmon*/power1_average"))
     done = torch.cuda.Event()
     tic = time.perf_counter()
     for _ in range(iters):
@@ -131,7 +138,7 @@ def engine_clock_while(fn, iters, torch):
         except (OSError, ValueError):
             break
     torch.cuda.synchronize()
-    if not clk:
+    if not clk or np.median(clk) < 600:          # an idle reading: not the card the kernels run on
         return None
     return {"sclk_mhz": float(np.median(clk)), "board_power_w": float(np.median(watts)) if watts else None,
             "samples": len(clk)}
