@@ -592,6 +592,16 @@ def measure_workload(wl, point, steps, warmup, torch, Tsdp, dev, full):
                            "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_TFLOPS, "traffic": None, "kernel_ms": k_ms,
                            "kernel_ms_median": k_med, "algorithmic_flops_per_launch": flops,
                            "note": "latency-bound at this size: reported for scale, no fraction claimed"}
+    if bf16 and fused and wl.cond_mode == 0:
+        # vector conditioning: the per-row FiLM vectors are their own launch before the forward kernel (in a whole round
+        # it runs beside the rollout); bound by its fp32 output stream
+        fm_ms, _ = time_kernel(ctx, lambda: ctx.tsdp_verify(wl.B, rows), 3, n_it)
+        out_bytes = R * wl.base.layers * 4 * wl.base.d * 4
+        res["film_gemm"] = {"kernel": "k_mod_gemm (per-row FiLM vectors of all layers, bf16 MFMA, fp32 out)",
+                            "kernel_ms": fm_ms, "bound": "hbm", "algorithmic_bytes_written": out_bytes,
+                            "achieved": out_bytes / (fm_ms * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                            "frac": out_bytes / (fm_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                            "flops": 2.0 * R * wl.base.d * wl.base.layers * 4 * wl.base.d}
     if kd_ms is not None:
         # drafter rollout: one workgroup per tile of environments re-reads the drafter's weights from the L2 at every
         # one of its K sequential steps
@@ -752,7 +762,7 @@ def main():
                            "steps_advanced_per_round": r["round"]["steps_advanced_per_round"],
                            "acceptance_of_all_drafts": r["round"]["acceptance_of_all_drafts"],
                            "paths": r["config"]["paths"], "roofline": r["roofline"], "drafter": r.get("drafter"),
-                           "action_prediction": r.get("action_prediction")}
+                           "film_gemm": r.get("film_gemm"), "action_prediction": r.get("action_prediction")}
         res["workloads"] = table
     print(json.dumps(res))
     if args.pmc_copy:

@@ -232,11 +232,12 @@ int tsdp_status(tsdp_ctx* ctx, void* stream, int32_t* h_status);
 
 /* Measurement aid.  tsdp_kernel_timing(ctx, 1) makes the following calls record a pair of HIP events on the
  * caller's stream around the dominant kernel of each stage (0 = drafter rollout kernel, 1 = verify forward
- * kernel, 2 = acceptance kernel); tsdp_kernel_ms waits for the last such pair of a stage and returns its
+ * kernel, 2 = acceptance kernel, 3 = the FiLM-vector product that tsdp_verify runs before the forward kernel of a
+ * bf16 network with vector conditioning); tsdp_kernel_ms waits for the last such pair of a stage and returns its
  * elapsed time in milliseconds.  enable = 0 switches it off; enable = 2 * mask (mask: bit 0 drafter, bit 1 verify,
- * bit 2 acceptance) brackets the chosen stages only -- timing events on the launch stream around the drafter take
- * away part of the overlap a whole round has between the rollout and the FiLM vectors of the base network.
- * Stages that run as a sequence of operator kernels are not timed. */
+ * bit 2 acceptance, bit 3 FiLM product) brackets the chosen stages only -- timing events on the launch stream around
+ * the drafter take away part of the overlap a whole round has between the rollout and the FiLM vectors of the base
+ * network.  Stages that run as a sequence of operator kernels are not timed. */
 int tsdp_kernel_timing(tsdp_ctx* ctx, int enable);
 int tsdp_kernel_ms(tsdp_ctx* ctx, int stage, float* h_ms);
 

@@ -99,9 +99,9 @@ struct tsdp_ctx {
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   // optional kernel timing: events recorded around the dominant kernel of each stage
   bool timing = false;
-  int timing_mask = 7;          // stages whose kernels are bracketed by events while timing is on (bit = stage)
-  hipEvent_t ev[3][2] = {{nullptr, nullptr}, {nullptr, nullptr}, {nullptr, nullptr}};   // draft, verify, accept
-  bool ev_used[3] = {false, false, false};
+  int timing_mask = 15;         // stages whose kernels are bracketed by events while timing is on (bit = stage)
+  hipEvent_t ev[4][2] = {{nullptr, nullptr}, {nullptr, nullptr}, {nullptr, nullptr}, {nullptr, nullptr}};   // draft, verify, accept, FiLM GEMM
+  bool ev_used[4] = {false, false, false, false};
 };
 
 namespace {
@@ -461,7 +461,10 @@ int forward(tsdp_ctx* c, Net& n, const float* x_rows, int R_cap, const int32_t* 
   if (n.fnet.modtab || mod_ready) {
     // token conditioning: the FiLM vectors are a function of the timestep only and were tabulated at load time
   } else if (n.fused_mod) {
+    const bool base = &n == &c->net[0];
+    if (base) tick(c, 3, 0, s);
     n.fused_mod(n.fnet, t_arr, t_sub, env_arr, cf.T, d_R, R_cap, c->mod, s);
+    if (base) tick(c, 3, 1, s);
   } else {                                            // fp32 networks: exact fp32 FiLM vectors from the operator kernels
     hipLaunchKernelGGL(k_gvec, grid1((long long)R_cap * n.d, 256), dim3(256), 0, s, t_arr, t_sub, env_arr, n.temb,
                        cf.cond_mode == 0 ? n.cemb : nullptr, c->sg, n.d, cf.T, d_R, R_cap);
@@ -1139,13 +1142,13 @@ int tsdp_kernel_timing(tsdp_ctx* c, int enable) {
       for (auto& e : st) HIPCHK(c, hipEventCreate(&e));
   }
   c->timing = enable != 0;
-  c->timing_mask = enable <= 1 ? 7 : (enable >> 1) & 7;
+  c->timing_mask = enable <= 1 ? 15 : (enable >> 1) & 15;
   for (bool& u : c->ev_used) u = false;
   return TSDP_OK;
 }
 
 int tsdp_kernel_ms(tsdp_ctx* c, int stage, float* h_ms) {
-  if (!c || !h_ms || stage < 0 || stage > 2) return TSDP_E_INVAL;
+  if (!c || !h_ms || stage < 0 || stage > 3) return TSDP_E_INVAL;
   if (!c->ev[0][0] || !c->ev_used[stage]) return fail(c, TSDP_E_STATE, "no timed launch of that stage since timing was enabled");
   HIPCHK(c, hipEventSynchronize(c->ev[stage][1]));
   HIPCHK(c, hipEventElapsedTime(h_ms, c->ev[stage][0], c->ev[stage][1]));
