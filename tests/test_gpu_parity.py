@@ -444,6 +444,42 @@ def test_row_table_of_a_batch_of_several_thousand_environments(bonus):
     S["ctx"].close()
 
 
+def test_kernel_timing_brackets_the_chosen_stages():
+    # measurement aid: event pairs around the stage kernels; a stage without a timed launch is an error, not a number
+    from paper_2512_15773_amd import TsdpError
+    wl = ti.small_variant(ti.C3, B=6)
+    S = _setup(wl, 6)
+    ctx = S["ctx"]
+    t0, K, s = ti.make_schedule_inputs(wl, 6, t0=40)
+    rows = _gpu_draft(S, t0, K, s, None)
+    ctx.tsdp_verify(6, rows)
+    before = {k: v.clone() for k, v in rows.items()}
+    ctx.tsdp_kernel_timing(True)                               # all stages
+    with pytest.raises(TsdpError):
+        ctx.tsdp_kernel_ms(1)                                  # nothing launched since timing was switched on
+    ctx.tsdp_draft(to_dev(S["x"]), to_dev(t0.astype(np.int32)), to_dev(K.astype(np.int32)), to_dev(s.astype(np.float32)),
+                   None, rows)
+    ctx.tsdp_verify(6, rows)
+    ctx.tsdp_accept(6, to_dev(s.astype(np.float32)), None, rows)
+    ms = [ctx.tsdp_kernel_ms(st) for st in range(4)]           # rollout, verify forward, acceptance, FiLM product
+    assert all(0.0 < m < 50.0 for m in ms), ms
+    for k in ("states", "eps_p", "eps_q", "xi", "row_t"):      # timing changes no result
+        assert torch_equal(rows[k], before[k]), k
+    ctx.tsdp_kernel_timing(2 * 0b0010)                         # the verify forward only
+    ctx.tsdp_verify(6, rows)
+    assert ctx.tsdp_kernel_ms(1) > 0.0
+    for st in (0, 2, 3):
+        with pytest.raises(TsdpError):
+            ctx.tsdp_kernel_ms(st)
+    ctx.tsdp_kernel_timing(False)
+    ctx.close()
+
+
+def torch_equal(a, b):
+    import torch
+    return bool(torch.equal(a, b))
+
+
 def test_draft_count_zero_is_the_plain_base_chain():
     # bonus-row context, K = 0 everywhere: every round is one base evaluation and one sampler step per environment
     # (no drafter work at all), so the chain is the base model's own reverse process with the round's noise stream
