@@ -1128,16 +1128,37 @@ __global__ __launch_bounds__(256) void k_mod_gemm(const void* __restrict__ modw,
   if (row0 >= R) return;
   int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  for (int i = threadIdx.x; i < NR * (D / 4); i += 256) {
-    const int r = i / (D / 4), c = (i % (D / 4)) * 4;
-    const int row = min(row0 + r, R - 1);
-    int t = t_arr[row] - t_sub;
-    t = t < 0 ? 0 : (t >= T ? T - 1 : t);
-    f32x4 g = *reinterpret_cast<const f32x4*>(temb + (size_t)t * D + c);
-    if (cemb) g += *reinterpret_cast<const f32x4*>(cemb + (size_t)(env_arr ? env_arr[row] : row) * D + c);
+  // the SiLU rows: batches of independent gathers (row indices first, then the two embedding vectors of every slot of
+  // the batch), so that a batch costs two memory round trips instead of two per slot
+  constexpr int SLOTS = NR * (D / 4), BATCH = 8;
+  for (int i0 = threadIdx.x; i0 < SLOTS; i0 += 256 * BATCH) {
+    int tt[BATCH], ee[BATCH];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) g[j] = silu_fast(g[j]);
-    *reinterpret_cast<bf16x4*>(sg + r * AS + c) = TBF16::cvt(g);
+    for (int j = 0; j < BATCH; ++j) {
+      const int i = min(i0 + 256 * j, SLOTS - 1);
+      const int row = min(row0 + i / (D / 4), R - 1);
+      tt[j] = t_arr[row] - t_sub;
+      ee[j] = cemb ? (env_arr ? env_arr[row] : row) : 0;
+    }
+    f32x4 g[BATCH];
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j) {
+      const int i = min(i0 + 256 * j, SLOTS - 1);
+      const int c = (i % (D / 4)) * 4;
+      const int t = tt[j] < 0 ? 0 : (tt[j] >= T ? T - 1 : tt[j]);
+      g[j] = *reinterpret_cast<const f32x4*>(temb + (size_t)t * D + c);
+      if (cemb) g[j] += *reinterpret_cast<const f32x4*>(cemb + (size_t)ee[j] * D + c);
+    }
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j) {
+      const int i = i0 + 256 * j;
+      if (i < SLOTS) {
+        f32x4 v = g[j];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = silu_fast(v[q]);
+        *reinterpret_cast<bf16x4*>(sg + (i / (D / 4)) * AS + (i % (D / 4)) * 4) = TBF16::cvt(v);
+      }
+    }
   }
   __syncthreads();
   const int l16 = lane & 15, lg = lane >> 4;
