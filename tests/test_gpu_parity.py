@@ -453,6 +453,7 @@ def test_kernel_timing_brackets_the_chosen_stages():
     t0, K, s = ti.make_schedule_inputs(wl, 6, t0=40)
     rows = _gpu_draft(S, t0, K, s, None)
     ctx.tsdp_verify(6, rows)
+    ctx.tsdp_accept(6, to_dev(s.astype(np.float32)), None, rows)
     before = {k: v.clone() for k, v in rows.items()}
     ctx.tsdp_kernel_timing(True)                               # all stages
     with pytest.raises(TsdpError):
@@ -462,7 +463,7 @@ def test_kernel_timing_brackets_the_chosen_stages():
     ctx.tsdp_verify(6, rows)
     ctx.tsdp_accept(6, to_dev(s.astype(np.float32)), None, rows)
     ms = [ctx.tsdp_kernel_ms(st) for st in range(4)]           # rollout, verify forward, acceptance, FiLM product
-    assert all(0.0 < m < 50.0 for m in ms), ms
+    assert all(0.0 < m < 1000.0 for m in ms), ms
     for k in ("states", "eps_p", "eps_q", "xi", "row_t"):      # timing changes no result
         assert torch_equal(rows[k], before[k]), k
     ctx.tsdp_kernel_timing(2 * 0b0010)                         # the verify forward only
