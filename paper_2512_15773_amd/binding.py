@@ -2,6 +2,10 @@
 
 torch is used for device memory and streams.  The library must have been built in-tree
 (`python -m paper_2512_15773_amd.build` or `__graft_entry__.build()`); there is no fallback.
+
+Calls only enqueue work on the given (default: torch's current) stream.  The binding passes raw pointers: a tensor
+handed to a call must stay alive until that stream has run the call -- torch's caching allocator does not know of the
+use and would hand a freed tensor's memory out again (keep a reference, or call Tensor.record_stream yourself).
 """
 import ctypes as C
 import os

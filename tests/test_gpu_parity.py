@@ -444,6 +444,47 @@ def test_row_table_of_a_batch_of_several_thousand_environments(bonus):
     S["ctx"].close()
 
 
+def test_two_contexts_on_two_streams_do_not_share_state():
+    # two contexts (different shapes, both with a FiLM product on their own second stream) run whole rounds at the same
+    # time on two streams; every result is bit-identical to the same rounds run one context after the other
+    import torch
+    specs = [(ti.small_variant(ti.C3, B=24), 24, 30), (ti.small_variant(ti.C5, B=40), 40, None)]
+    S, inputs = [], []
+    for wl, B, t_fix in specs:
+        S.append(_setup(wl, B, head_scale=0.3))
+        t0, K, s = ti.make_schedule_inputs(wl, B, t0=t_fix)
+        inputs.append((t0.astype(np.int32), K.astype(np.int32), s.astype(np.float32)))
+
+    def tensors(i):
+        t0, K, s = inputs[i]
+        return dict(x=to_dev(S[i]["x"]), t=to_dev(t0), K=to_dev(K), s=to_dev(s),
+                    na=torch.zeros(len(t0), dtype=torch.int32, device="cuda"),
+                    nd=torch.zeros(len(t0), dtype=torch.int32, device="cuda"))
+
+    def rounds(i, T, stream, n=3):
+        with torch.cuda.stream(stream):
+            for _ in range(n):
+                S[i]["ctx"].tsdp_round(T["x"], T["t"], T["K"], T["s"], None, T["na"], T["nd"])
+
+    main = torch.cuda.current_stream()
+    want = [tensors(0), tensors(1)]
+    for i in range(2):
+        rounds(i, want[i], main)
+        torch.cuda.synchronize()
+    # every input exists (and stays alive) before anything is enqueued on the side streams: a tensor freed while a
+    # stream that the allocator does not know of still reads it would be handed out again
+    got = [tensors(0), tensors(1)]
+    torch.cuda.synchronize()
+    st = [torch.cuda.Stream(), torch.cuda.Stream()]
+    rounds(0, got[0], st[0]); rounds(1, got[1], st[1])         # enqueued back to back, nothing waits in between
+    torch.cuda.synchronize()
+    for i in range(2):
+        for name in ("x", "t", "na", "nd"):
+            assert torch.equal(got[i][name], want[i][name]), (i, name)
+        assert S[i]["ctx"].tsdp_status() == 0
+        S[i]["ctx"].close()
+
+
 def test_kernel_timing_brackets_the_chosen_stages():
     # measurement aid: event pairs around the stage kernels; a stage without a timed launch is an error, not a number
     from paper_2512_15773_amd import TsdpError
